@@ -1,0 +1,197 @@
+/*
+ * cnr.h -- C ABI of libcnr: the GPU hot path of an incremental, quantized checkpoint encoder for
+ * embedding tables (Check-N-Run, arXiv 2010.08679), written for AMD MI355X (gfx950).
+ *
+ * The path, in call order:
+ *   cnr_clear_bitmap   start a new tracking window (Section 5.1: a new baseline, or every
+ *                      interval under the consecutive-increment policy)
+ *   cnr_mark_touched   once per training iteration and table: record which rows were looked up
+ *                      (Section 5.1.1, tracking bit-vector)
+ *   cnr_compact_dirty  at checkpoint time: the list of rows whose bit is set, i.e. the
+ *                      incremental view (Section 5.1)
+ *   cnr_quantize_rows  gather those rows and quantize each one with uniform per-row
+ *                      quantization F_Q (Section 5.2, Approach 1), the range being the row's
+ *                      min/max, the symmetric range, or the greedy-searched one (Approach 3);
+ *                      codes are packed densely in the same kernel
+ *   cnr_pack           dense packing alone, for codes produced one per byte
+ *   cnr_restore_rows   resume: de-quantize (x = scale * x_q + zero_point) and write the rows
+ *                      back over a stale baseline table (Sections 5.1 and 6.2)
+ *
+ * General rules
+ *   - Every pointer argument is a DEVICE pointer owned by the caller unless its comment says
+ *     "host".  The library allocates nothing on the hot path; cnr_create allocates a few bytes of
+ *     device and pinned host memory for the error counters, cnr_destroy frees them.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every call only
+ *     enqueues work on it and returns at once; the status returned covers argument checks and
+ *     launch failures.  Conditions found on the device (look-up indices outside the table, more
+ *     dirty rows than `capacity`, a row id outside the table) never fault: the offending item is
+ *     skipped, a counter / flag in the context is updated, and cnr_poll_errors reports it.
+ *   - Row counts that are only known on the device (the output of cnr_compact_dirty) are passed
+ *     on as device pointers, so that a checkpoint needs no host synchronisation between its
+ *     stages.  `n_max` bounds the count from the host side (it sizes the launch and the output
+ *     buffers); the kernels process min(*n_dev, n_max) rows.
+ *   - A context belongs to one device and must not be used from two host threads at once.
+ *   - No C++ type, exception or torch object crosses this boundary.
+ *
+ * Data layout
+ *   table     float [n_rows][dim], row-major, 16-byte aligned base, dim % 4 == 0
+ *   bitmap    uint32 [cnr_bitmap_words(n_rows)]; row i is bit (i & 31) of word (i >> 5);
+ *             8-byte aligned base; bits at positions >= n_rows are ignored
+ *   row_ids   uint32 [n], strictly ascending when produced by cnr_compact_dirty
+ *   scale,    float [n]: scale = (hi - lo) / (2^bits - 1) and bias = lo (the zero_point) of
+ *   bias      row_ids[k]'s range [lo, hi]
+ *   packed    uint8 [n][cnr_packed_row_bytes(dim, bits)], rows back to back without padding; per
+ *             row one little-endian bit stream in which element j occupies stream bits
+ *             [j*bits, (j+1)*bits), least-significant code bit first (stream bit t is bit
+ *             (t & 7) of byte (t >> 3)); 16-byte aligned base
+ *   codes_u8  uint8 [n][dim], one code per byte
+ */
+#ifndef CNR_H
+#define CNR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cnr_ctx cnr_ctx; /* opaque */
+
+typedef enum {
+    CNR_OK = 0,
+    CNR_E_INVALID = 1,     /* NULL where a pointer is required, bad enum value, n_rows >= 2^32 */
+    CNR_E_BITS = 2,        /* bits not in {2, 3, 4, 8} */
+    CNR_E_DIM = 3,         /* dim == 0, dim % 4 != 0, dim > CNR_MAX_DIM, or dim*bits % 8 != 0 */
+    CNR_E_ALIGN = 4,       /* a base pointer is not aligned as the layout section requires */
+    CNR_E_CAPACITY = 5,    /* device: more dirty rows than `capacity` (poll only) */
+    CNR_E_INDEX_RANGE = 6, /* device: look-up indices outside [0, n_rows) were skipped (poll only) */
+    CNR_E_ROW_ID = 7,      /* device: a row id >= n_rows was skipped (poll only) */
+    CNR_E_HIP = 8          /* a HIP runtime call failed; see cnr_last_hip_error */
+} cnr_status;
+
+typedef enum { CNR_IDX_I32 = 0, CNR_IDX_I64 = 1 } cnr_index_type;
+
+typedef enum {
+    CNR_RANGE_MINMAX = 0,   /* asymmetric: [min x, max x]            (Section 5.2, Approach 1) */
+    CNR_RANGE_GREEDY = 1,   /* adaptive asymmetric, greedy search    (Section 5.2, Approach 3) */
+    CNR_RANGE_SYMMETRIC = 2 /* [-max|x|, +max|x|]                    (Section 5.2, Approach 1) */
+} cnr_range_mode;
+
+/* Parameters of the greedy range search (Section 5.2, Approach 3).  step_size is the row's
+ * original range divided by num_bins; the search performs
+ *     n_iter = min(ceil(ratio * num_bins - 1e-4), num_bins - 1)
+ * iterations, i.e. it stops once the removed part reaches `ratio` of the original range and
+ * never lets the range collapse.  Each iteration tries [lo + step, hi] and [lo, hi - step], keeps
+ * the one with the smaller squared l2 error (the lower bound moves only on a strictly smaller
+ * error); the result is the range of the iteration with the smallest error, the un-shrunk range
+ * included (an earlier iteration wins ties). */
+typedef struct {
+    uint32_t num_bins;
+    float ratio;
+} cnr_greedy_params;
+
+#define CNR_MAX_DIM 4096u
+
+/* Flags reported by cnr_poll_errors. */
+#define CNR_FLAG_CAPACITY 1u
+#define CNR_FLAG_ROW_ID 2u
+
+/* ---- context ---------------------------------------------------------------------------- */
+
+/* Creates a context on HIP device `device` (host call; allocates the error counters).
+ * *out receives the context (host pointer, owned by the caller until cnr_destroy). */
+cnr_status cnr_create(cnr_ctx **out, int device);
+cnr_status cnr_destroy(cnr_ctx *ctx);
+
+/* Sizes (pure host arithmetic, no GPU involved). */
+size_t cnr_bitmap_words(uint64_t n_rows);               /* ceil(n_rows / 32) */
+size_t cnr_packed_row_bytes(uint32_t dim, int bits);    /* dim*bits/8; 0 if not a whole number */
+size_t cnr_scratch_bytes(uint64_t n_rows);              /* scratch cnr_compact_dirty needs */
+uint32_t cnr_greedy_iterations(uint32_t num_bins, float ratio); /* n_iter as defined above */
+
+/* ---- tracking (Section 5.1.1) ----------------------------------------------------------- */
+
+/* Zeroes bitmap[0 .. cnr_bitmap_words(n_rows)) with a fill kernel (safe under graph capture). */
+cnr_status cnr_clear_bitmap(cnr_ctx *ctx, uint32_t *bitmap, uint64_t n_rows, void *stream);
+
+/* For every t < n_indices with 0 <= indices[t] < n_rows sets bit indices[t] of `bitmap`
+ * (in place; bits accumulate over calls until the bitmap is cleared).  Duplicates are expected.
+ * Indices outside the table are skipped and counted in the context.
+ *   indices  int32 or int64 [n_indices] as `type` says; naturally aligned
+ *   n_rows   < 2^32 */
+cnr_status cnr_mark_touched(cnr_ctx *ctx, uint32_t *bitmap, uint64_t n_rows, const void *indices,
+                            uint64_t n_indices, cnr_index_type type, void *stream);
+
+/* ---- incremental view (Section 5.1) ------------------------------------------------------ */
+
+/* Writes the ascending list of set-bit positions below n_rows to row_ids and their number to
+ * *n_dirty_dev.  If there are more than `capacity`, only the first `capacity` ids are written,
+ * *n_dirty_dev still receives the full count and CNR_FLAG_CAPACITY is raised in the context.
+ *   row_ids      uint32 [capacity]
+ *   n_dirty_dev  uint64 [1] (device)
+ *   scratch      cnr_scratch_bytes(n_rows) bytes, 8-byte aligned, contents irrelevant */
+cnr_status cnr_compact_dirty(cnr_ctx *ctx, const uint32_t *bitmap, uint64_t n_rows,
+                             uint32_t *row_ids, uint64_t capacity, uint64_t *n_dirty_dev,
+                             void *scratch, void *stream);
+
+/* ---- quantization (Section 5.2) ---------------------------------------------------------- */
+
+/* For k < n = min(*n_dev, n_max): gathers row r = row_ids[k] (r = k when row_ids is NULL) of
+ * `table`, finds X_min / X_max, selects the range [lo, hi] by `mode`, and quantizes the row with
+ * F_Q(x, lo, hi) at `bits` bits: scale = (hi - lo) / (2^bits - 1), code = round-half-even
+ * ((clip(x, lo, hi) - lo) / scale) in fp32, all codes 0 when scale == 0.
+ *   n_dev     uint64 [1] device pointer, or NULL meaning n = n_max
+ *   greedy    host pointer, read during the call; required for CNR_RANGE_GREEDY only
+ *   scale, bias        float [n_max], required
+ *   row_min, row_max   float [n_max] or NULL: X_min / X_max before any shrinking (-0.0 reported
+ *                      as +0.0)
+ *   codes_u8  uint8 [n_max][dim] or NULL: the codes one per byte
+ *   packed    uint8 [n_max][cnr_packed_row_bytes] or NULL: the codes packed (fused path)
+ * Rows must hold finite values with |x| < FLT_MAX / 2; anything else gives unspecified codes
+ * (never a fault).  A row id >= n_rows is skipped and CNR_FLAG_ROW_ID raised. */
+cnr_status cnr_quantize_rows(cnr_ctx *ctx, const float *table, uint64_t n_rows, uint32_t dim,
+                             const uint32_t *row_ids, const uint64_t *n_dev, uint64_t n_max,
+                             int bits, cnr_range_mode mode, const cnr_greedy_params *greedy,
+                             float *scale, float *bias, float *row_min, float *row_max,
+                             uint8_t *codes_u8, uint8_t *packed, void *stream);
+
+/* Packs codes_u8 [n][dim] (values < 2^bits) into `packed` as laid out above. */
+cnr_status cnr_pack(cnr_ctx *ctx, const uint8_t *codes_u8, const uint64_t *n_dev, uint64_t n_max,
+                    uint32_t dim, int bits, uint8_t *packed, void *stream);
+
+/* ---- restore (Sections 5.1, 5.2, 6.2) ----------------------------------------------------- */
+
+/* For k < n = min(*n_dev, n_max): table[row_ids[k]][j] = scale[k] * code_kj + bias[k] (fp32, one
+ * rounding for the product and one for the sum) for all j; rows not listed keep their contents.
+ * row_ids == NULL means row k.  Row ids must not repeat.  A row id >= n_rows is skipped and
+ * CNR_FLAG_ROW_ID raised. */
+cnr_status cnr_restore_rows(cnr_ctx *ctx, float *table, uint64_t n_rows, uint32_t dim,
+                            const uint32_t *row_ids, const uint64_t *n_dev, uint64_t n_max,
+                            int bits, const uint8_t *packed, const float *scale,
+                            const float *bias, void *stream);
+
+/* ---- device-side conditions ---------------------------------------------------------------- */
+
+/* Waits for `stream`, then reports and resets what the kernels recorded since the last poll.
+ *   n_bad_indices  host uint64 [1] or NULL: look-up indices skipped by cnr_mark_touched
+ *   flags          host uint32 [1] or NULL: CNR_FLAG_* bits
+ * Returns CNR_OK when nothing was recorded, else CNR_E_CAPACITY, CNR_E_ROW_ID or
+ * CNR_E_INDEX_RANGE (in that order of precedence). */
+cnr_status cnr_poll_errors(cnr_ctx *ctx, void *stream, uint64_t *n_bad_indices, uint32_t *flags);
+
+const char *cnr_status_str(cnr_status s);
+/* hipError_t of the last failed HIP call on this context (0 if none), as an int. */
+int cnr_last_hip_error(const cnr_ctx *ctx);
+
+/* ---- checkpoint policy (Section 5.1, intermittent incremental checkpoint; host only) -------- */
+
+/* sizes[0..i) = S_1..S_i, the sizes of the incremental checkpoints since the last full one as
+ * fractions of a full checkpoint.  Returns 1 when a full checkpoint should be taken at interval
+ * i+1, i.e. when F_c = 1 + S_1 + ... + S_i <= I_c = (i + 1) * S_i, else 0 (also for i == 0). */
+int cnr_full_checkpoint_due(const double *sizes /* host */, uint32_t i);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CNR_H */

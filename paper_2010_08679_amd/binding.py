@@ -1,0 +1,240 @@
+"""ctypes binding of libcnr.so: argument marshalling only.
+
+Every function has the name and the argument order of its C declaration in ``include/cnr.h``
+(which documents meaning, layout and error behaviour) and takes ``torch`` tensors that live on
+the context's GPU where the C side takes device pointers.  Nothing is computed here: checks are
+limited to dtype / device / contiguity of the tensors handed over, and a non-zero status is
+raised as :class:`CnrError`.  There is no fallback: without the compiled library, or without a
+GPU, these calls fail.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import threading
+
+import torch
+
+from . import build as _build
+
+CNR_OK = 0
+CNR_E_INVALID, CNR_E_BITS, CNR_E_DIM, CNR_E_ALIGN = 1, 2, 3, 4
+CNR_E_CAPACITY, CNR_E_INDEX_RANGE, CNR_E_ROW_ID, CNR_E_HIP = 5, 6, 7, 8
+CNR_IDX_I32, CNR_IDX_I64 = 0, 1
+CNR_RANGE_MINMAX, CNR_RANGE_GREEDY, CNR_RANGE_SYMMETRIC = 0, 1, 2
+CNR_FLAG_CAPACITY, CNR_FLAG_ROW_ID = 1, 2
+CNR_MAX_DIM = 4096
+
+# Every symbol include/cnr.h declares.
+EXPORTS = (
+    "cnr_create", "cnr_destroy", "cnr_bitmap_words", "cnr_packed_row_bytes", "cnr_scratch_bytes",
+    "cnr_greedy_iterations", "cnr_clear_bitmap", "cnr_mark_touched", "cnr_compact_dirty",
+    "cnr_quantize_rows", "cnr_pack", "cnr_restore_rows", "cnr_poll_errors", "cnr_status_str",
+    "cnr_last_hip_error", "cnr_full_checkpoint_due",
+)
+
+
+class CnrError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, status_str(status), status))
+
+
+class cnr_greedy_params(ctypes.Structure):
+    _fields_ = [("num_bins", ctypes.c_uint32), ("ratio", ctypes.c_float)]
+
+
+_lock = threading.Lock()
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Loads libcnr.so, compiling it first only when no built library is there."""
+    global _lib
+    with _lock:
+        if _lib is not None:
+            return _lib
+        if not os.path.exists(_build.LIB):
+            _build.build_lib(force=True)
+        lib = ctypes.CDLL(_build.LIB)
+        vp, u64, u32, i32, f32 = (ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int,
+                                  ctypes.c_float)
+        sz = ctypes.c_size_t
+        sig = {
+            "cnr_create": (i32, [ctypes.POINTER(vp), i32]),
+            "cnr_destroy": (i32, [vp]),
+            "cnr_bitmap_words": (sz, [u64]),
+            "cnr_packed_row_bytes": (sz, [u32, i32]),
+            "cnr_scratch_bytes": (sz, [u64]),
+            "cnr_greedy_iterations": (u32, [u32, f32]),
+            "cnr_clear_bitmap": (i32, [vp, vp, u64, vp]),
+            "cnr_mark_touched": (i32, [vp, vp, u64, vp, u64, i32, vp]),
+            "cnr_compact_dirty": (i32, [vp, vp, u64, vp, u64, vp, vp, vp]),
+            "cnr_quantize_rows": (i32, [vp, vp, u64, u32, vp, vp, u64, i32, i32,
+                                        ctypes.POINTER(cnr_greedy_params), vp, vp, vp, vp, vp, vp, vp]),
+            "cnr_pack": (i32, [vp, vp, vp, u64, u32, i32, vp, vp]),
+            "cnr_restore_rows": (i32, [vp, vp, u64, u32, vp, vp, u64, i32, vp, vp, vp, vp]),
+            "cnr_poll_errors": (i32, [vp, vp, ctypes.POINTER(u64), ctypes.POINTER(u32)]),
+            "cnr_status_str": (ctypes.c_char_p, [i32]),
+            "cnr_last_hip_error": (i32, [vp]),
+            "cnr_full_checkpoint_due": (i32, [ctypes.POINTER(ctypes.c_double), u32]),
+        }
+        for name, (res, args) in sig.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+        return lib
+
+
+def status_str(status: int) -> str:
+    return load().cnr_status_str(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != CNR_OK:
+        raise CnrError(status, where)
+
+
+def _dev(t, dtype, name: str):
+    """Device pointer of a contiguous tensor of the given dtype (None passes through as NULL)."""
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a tensor on the GPU" % name)
+    if t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    """hipStream_t of a torch stream (the current one when None) as void*."""
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+# uint32 / uint64 buffers are held in torch's int32 / int64 tensors (same bits).
+U32, U64, F32, U8 = torch.int32, torch.int64, torch.float32, torch.uint8
+
+
+# ---- context and sizes -----------------------------------------------------------------------
+
+def cnr_create(device: int = 0) -> ctypes.c_void_p:
+    ctx = ctypes.c_void_p()
+    _check(load().cnr_create(ctypes.byref(ctx), int(device)), "cnr_create")
+    return ctx
+
+
+def cnr_destroy(ctx) -> None:
+    _check(load().cnr_destroy(ctx), "cnr_destroy")
+
+
+def cnr_bitmap_words(n_rows: int) -> int:
+    return int(load().cnr_bitmap_words(n_rows))
+
+
+def cnr_packed_row_bytes(dim: int, bits: int) -> int:
+    return int(load().cnr_packed_row_bytes(dim, bits))
+
+
+def cnr_scratch_bytes(n_rows: int) -> int:
+    return int(load().cnr_scratch_bytes(n_rows))
+
+
+def cnr_greedy_iterations(num_bins: int, ratio: float) -> int:
+    return int(load().cnr_greedy_iterations(num_bins, ratio))
+
+
+# ---- the path ------------------------------------------------------------------------------------
+
+def cnr_clear_bitmap(ctx, bitmap, n_rows: int, stream=None) -> None:
+    _check(load().cnr_clear_bitmap(ctx, _dev(bitmap, U32, "bitmap"), n_rows, _stream(stream)),
+           "cnr_clear_bitmap")
+
+
+def cnr_mark_touched(ctx, bitmap, n_rows: int, indices, stream=None) -> None:
+    if indices.dtype == torch.int64:
+        kind = CNR_IDX_I64
+    elif indices.dtype == torch.int32:
+        kind = CNR_IDX_I32
+    else:
+        raise TypeError("indices must be int32 or int64")
+    _check(load().cnr_mark_touched(ctx, _dev(bitmap, U32, "bitmap"), n_rows,
+                                   _dev(indices, indices.dtype, "indices"), indices.numel(), kind,
+                                   _stream(stream)), "cnr_mark_touched")
+
+
+def cnr_compact_dirty(ctx, bitmap, n_rows: int, row_ids, capacity: int, n_dirty_dev, scratch,
+                      stream=None) -> None:
+    if scratch.numel() * scratch.element_size() < cnr_scratch_bytes(n_rows):
+        raise ValueError("scratch smaller than cnr_scratch_bytes(n_rows)")
+    if row_ids is not None and row_ids.numel() < capacity:
+        raise ValueError("row_ids shorter than capacity")
+    _check(load().cnr_compact_dirty(ctx, _dev(bitmap, U32, "bitmap"), n_rows,
+                                    _dev(row_ids, U32, "row_ids"), capacity,
+                                    _dev(n_dirty_dev, U64, "n_dirty_dev"),
+                                    _dev(scratch, scratch.dtype, "scratch"), _stream(stream)),
+           "cnr_compact_dirty")
+
+
+def cnr_quantize_rows(ctx, table, n_rows: int, dim: int, row_ids, n_dev, n_max: int, bits: int,
+                      mode: int, greedy, scale, bias, row_min=None, row_max=None, codes_u8=None,
+                      packed=None, stream=None) -> None:
+    """``greedy`` is None or a (num_bins, ratio) pair."""
+    gp = None
+    if greedy is not None:
+        gp = ctypes.pointer(cnr_greedy_params(int(greedy[0]), float(greedy[1])))
+    if table.numel() < n_rows * dim:
+        raise ValueError("table smaller than n_rows * dim")
+    for name, t, per_row in (("scale", scale, 1), ("bias", bias, 1), ("row_min", row_min, 1),
+                             ("row_max", row_max, 1), ("codes_u8", codes_u8, dim),
+                             ("packed", packed, cnr_packed_row_bytes(dim, bits))):
+        if t is not None and t.numel() < n_max * per_row:
+            raise ValueError("%s too small for n_max rows" % name)
+    if row_ids is not None and row_ids.numel() < n_max:
+        raise ValueError("row_ids shorter than n_max")
+    _check(load().cnr_quantize_rows(ctx, _dev(table, F32, "table"), n_rows, dim,
+                                    _dev(row_ids, U32, "row_ids"), _dev(n_dev, U64, "n_dev"), n_max,
+                                    bits, mode, gp, _dev(scale, F32, "scale"), _dev(bias, F32, "bias"),
+                                    _dev(row_min, F32, "row_min"), _dev(row_max, F32, "row_max"),
+                                    _dev(codes_u8, U8, "codes_u8"), _dev(packed, U8, "packed"),
+                                    _stream(stream)), "cnr_quantize_rows")
+
+
+def cnr_pack(ctx, codes_u8, n_dev, n_max: int, dim: int, bits: int, packed, stream=None) -> None:
+    if codes_u8.numel() < n_max * dim or packed.numel() < n_max * cnr_packed_row_bytes(dim, bits):
+        raise ValueError("buffer too small for n_max rows")
+    _check(load().cnr_pack(ctx, _dev(codes_u8, U8, "codes_u8"), _dev(n_dev, U64, "n_dev"), n_max, dim,
+                           bits, _dev(packed, U8, "packed"), _stream(stream)), "cnr_pack")
+
+
+def cnr_restore_rows(ctx, table, n_rows: int, dim: int, row_ids, n_dev, n_max: int, bits: int,
+                     packed, scale, bias, stream=None) -> None:
+    if table.numel() < n_rows * dim:
+        raise ValueError("table smaller than n_rows * dim")
+    if (packed.numel() < n_max * cnr_packed_row_bytes(dim, bits) or scale.numel() < n_max
+            or bias.numel() < n_max or (row_ids is not None and row_ids.numel() < n_max)):
+        raise ValueError("buffer too small for n_max rows")
+    _check(load().cnr_restore_rows(ctx, _dev(table, F32, "table"), n_rows, dim,
+                                   _dev(row_ids, U32, "row_ids"), _dev(n_dev, U64, "n_dev"), n_max,
+                                   bits, _dev(packed, U8, "packed"), _dev(scale, F32, "scale"),
+                                   _dev(bias, F32, "bias"), _stream(stream)), "cnr_restore_rows")
+
+
+def cnr_poll_errors(ctx, stream=None):
+    """Returns (status, n_bad_indices, flags); synchronises the stream."""
+    bad, flags = ctypes.c_uint64(0), ctypes.c_uint32(0)
+    st = load().cnr_poll_errors(ctx, _stream(stream), ctypes.byref(bad), ctypes.byref(flags))
+    if st in (CNR_E_HIP, CNR_E_INVALID):
+        raise CnrError(st, "cnr_poll_errors")
+    return st, int(bad.value), int(flags.value)
+
+
+def cnr_last_hip_error(ctx) -> int:
+    return int(load().cnr_last_hip_error(ctx))
+
+
+def cnr_full_checkpoint_due(sizes) -> bool:
+    arr = (ctypes.c_double * len(sizes))(*[float(s) for s in sizes])
+    return bool(load().cnr_full_checkpoint_due(arr, len(sizes)))

@@ -1,0 +1,81 @@
+"""Device buffers for one table's checkpoints and the order of the library calls.
+
+Plumbing only: torch allocates the memory and provides the stream, every step of the path runs in
+libcnr's kernels.  One :class:`TableCheckpointer` serves one embedding table (one shard of the
+model on this GPU, Section 4.1): it keeps the tracking bit-vector between iterations
+(Section 5.1.1) and, at checkpoint time, produces the incremental, quantized view of the table
+(Sections 5.1 and 5.2).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import torch
+
+from . import binding as B
+
+
+@dataclass
+class EncodedRows:
+    """One table's incremental checkpoint as it sits in device memory (valid up to ``n`` rows)."""
+    n_dev: torch.Tensor      # int64 [1]: number of dirty rows
+    row_ids: torch.Tensor    # int32 (uint32 bits) [capacity]
+    scale: torch.Tensor      # float32 [capacity]
+    bias: torch.Tensor       # float32 [capacity]
+    packed: torch.Tensor     # uint8 [capacity * packed_row_bytes]
+    bits: int
+    dim: int
+    row_min: torch.Tensor | None = None
+    row_max: torch.Tensor | None = None
+
+    def count(self) -> int:
+        """Number of rows encoded (synchronises)."""
+        return int(self.n_dev.item())
+
+
+class TableCheckpointer:
+    def __init__(self, ctx, n_rows: int, dim: int, capacity: int | None = None, device="cuda:0"):
+        self.ctx, self.n_rows, self.dim = ctx, int(n_rows), int(dim)
+        self.capacity = self.n_rows if capacity is None else int(capacity)
+        self.device = torch.device(device)
+        dev = self.device
+        self.bitmap = torch.zeros(max(1, B.cnr_bitmap_words(n_rows)), dtype=torch.int32, device=dev)
+        self.scratch = torch.empty((B.cnr_scratch_bytes(n_rows) + 7) // 8, dtype=torch.int64, device=dev)
+        self.row_ids = torch.empty(max(1, self.capacity), dtype=torch.int32, device=dev)
+        self.n_dirty = torch.zeros(1, dtype=torch.int64, device=dev)
+
+    # -- tracking ---------------------------------------------------------------------------
+    def clear(self, stream=None) -> None:
+        B.cnr_clear_bitmap(self.ctx, self.bitmap, self.n_rows, stream)
+
+    def mark(self, indices: torch.Tensor, stream=None) -> None:
+        B.cnr_mark_touched(self.ctx, self.bitmap, self.n_rows, indices.reshape(-1), stream)
+
+    # -- checkpoint -------------------------------------------------------------------------
+    def compact(self, stream=None) -> None:
+        B.cnr_compact_dirty(self.ctx, self.bitmap, self.n_rows, self.row_ids, self.capacity,
+                            self.n_dirty, self.scratch, stream)
+
+    def alloc_output(self, bits: int, want_range: bool = False) -> EncodedRows:
+        cap, dev = max(1, self.capacity), self.device
+        f = lambda: torch.empty(cap, dtype=torch.float32, device=dev)  # noqa: E731
+        return EncodedRows(self.n_dirty, self.row_ids, f(), f(),
+                           torch.empty(cap * B.cnr_packed_row_bytes(self.dim, bits), dtype=torch.uint8,
+                                       device=dev),
+                           bits, self.dim, f() if want_range else None, f() if want_range else None)
+
+    def encode(self, table: torch.Tensor, out: EncodedRows, mode: int = B.CNR_RANGE_MINMAX,
+               greedy=None, codes_u8=None, fused: bool = True, stream=None) -> EncodedRows:
+        """Quantizes the rows listed by the last :meth:`compact` into ``out``."""
+        B.cnr_quantize_rows(self.ctx, table, self.n_rows, self.dim, self.row_ids, self.n_dirty,
+                            self.capacity, out.bits, mode, greedy, out.scale, out.bias, out.row_min,
+                            out.row_max, codes_u8, out.packed if fused else None, stream)
+        if not fused:
+            B.cnr_pack(self.ctx, codes_u8, self.n_dirty, self.capacity, self.dim, out.bits, out.packed,
+                       stream)
+        return out
+
+    def restore(self, table: torch.Tensor, enc: EncodedRows, stream=None) -> None:
+        """Writes the de-quantized rows of ``enc`` over the same rows of ``table`` in place."""
+        B.cnr_restore_rows(self.ctx, table, self.n_rows, self.dim, enc.row_ids, enc.n_dev, self.capacity,
+                           enc.bits, enc.packed, enc.scale, enc.bias, stream)

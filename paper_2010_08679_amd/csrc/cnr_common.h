@@ -1,0 +1,98 @@
+// Internal declarations shared by the translation units of libcnr (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cnr.h"
+
+// Counters the kernels update when they meet a condition they must not fault on.
+struct cnr_dev_errors {
+    unsigned long long n_bad_indices;  // look-up indices outside the table (mark)
+    unsigned int flags;                // CNR_FLAG_*
+    unsigned int pad;
+};
+
+struct cnr_ctx {
+    int device;
+    int n_cu;                  // compute units of the device
+    cnr_dev_errors *dev_err;   // device
+    cnr_dev_errors *host_err;  // pinned host mirror used by cnr_poll_errors
+    int last_hip_error;
+};
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;                    // threads per workgroup everywhere
+constexpr int kWavesPerBlock = kBlock / kWave;
+
+// Rows of the bitmap one compact workgroup covers: one 64-bit bitmap word per thread.
+constexpr uint64_t kCompactRowsPerBlock = (uint64_t)kBlock * 64u;
+
+static inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+// Makes ctx's device current; returns CNR_OK or CNR_E_HIP.
+cnr_status cnr_enter(cnr_ctx *ctx);
+// Records a HIP failure in the context and maps it to a status.
+cnr_status cnr_hip_status(cnr_ctx *ctx, hipError_t e);
+// Status of the launch that was just enqueued.
+static inline cnr_status cnr_launch_status(cnr_ctx *ctx) { return cnr_hip_status(ctx, hipGetLastError()); }
+
+static inline bool cnr_valid_bits(int bits) { return bits == 2 || bits == 3 || bits == 4 || bits == 8; }
+
+// Number of workgroups for `work_items` items at `per_block` items per workgroup pass, capped so
+// that a grid-stride loop keeps every compute unit busy without oversubscribing the dispatcher.
+static inline unsigned cnr_grid(const cnr_ctx *ctx, uint64_t work_items, uint64_t per_block,
+                                unsigned blocks_per_cu) {
+    uint64_t need = (work_items + per_block - 1) / per_block;
+    uint64_t cap = (uint64_t)ctx->n_cu * blocks_per_cu;
+    if (need < 1) need = 1;
+    return (unsigned)(need < cap ? need : cap);
+}
+
+#ifdef __HIPCC__
+// ---- cross-lane helpers (wave64) -------------------------------------------------------------
+// DPP controls: quad_perm [1,0,3,2] = 0xB1 (lane ^ 1), quad_perm [2,3,0,1] = 0x4E (lane ^ 2),
+// row_half_mirror = 0x141 (lane i <-> 7 - i within 8), row_mirror = 0x140 (i <-> 15 - i within 16).
+// After those four exchanges, applied in that order with a commutative and associative combine,
+// all 16 lanes of a DPP row hold the combination of the row's 16 values.
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+    return __int_as_float(dpp_i<CTRL>(__float_as_int(v)));
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_d(double v) {
+    int lo = dpp_i<CTRL>(__double2loint(v));
+    int hi = dpp_i<CTRL>(__double2hiint(v));
+    return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ float row16_min(float v) {
+    v = fminf(v, dpp_f<0xB1>(v));
+    v = fminf(v, dpp_f<0x4E>(v));
+    v = fminf(v, dpp_f<0x141>(v));
+    v = fminf(v, dpp_f<0x140>(v));
+    return v;
+}
+__device__ __forceinline__ float row16_max(float v) {
+    v = fmaxf(v, dpp_f<0xB1>(v));
+    v = fmaxf(v, dpp_f<0x4E>(v));
+    v = fmaxf(v, dpp_f<0x141>(v));
+    v = fmaxf(v, dpp_f<0x140>(v));
+    return v;
+}
+__device__ __forceinline__ double row16_sum(double v) {
+    v += dpp_d<0xB1>(v);
+    v += dpp_d<0x4E>(v);
+    v += dpp_d<0x141>(v);
+    v += dpp_d<0x140>(v);
+    return v;
+}
+
+__device__ __forceinline__ void raise_flag(cnr_dev_errors *err, unsigned flag) {
+    atomicOr(&err->flags, flag);
+}
+#endif

@@ -1,0 +1,338 @@
+"""GPU parity: libcnr (through its C ABI) against the CPU oracle, element by element, on the same
+seeded inputs.  Sizes span several 16-row wave batches, several workgroups and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2010_08679_amd as P
+from paper_2010_08679_amd import synth
+from util_parity import (GpuTable, compare_quantized, gpu_encode_all_outputs, u32)
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+BITS = (2, 3, 4, 8)
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = P.cnr_create(0)
+    yield c
+    torch.cuda.synchronize()
+    P.cnr_destroy(c)
+
+
+def _poll_clean(ctx):
+    st, bad, flags = P.cnr_poll_errors(ctx)
+    assert (st, bad, flags) == (P.CNR_OK, 0, 0)
+
+
+def _oracle_track(n_rows, batches):
+    bm = O.new_bitmap(n_rows)
+    skipped = 0
+    for b in batches:
+        skipped += O.mark_touched(bm, n_rows, b)
+    ids, n = O.compact_dirty(bm, n_rows)
+    return bm, ids, n, skipped
+
+
+# ------------------------------------------------------------------ tracking + compaction
+
+@pytest.mark.parametrize("n_rows", [1, 31, 32, 33, 63, 64, 65, 1000, 16384, 16385, 100_000, 1_000_003])
+@pytest.mark.parametrize("dtype", [torch.int64, torch.int32])
+def test_mark_and_compact_bit_exact(ctx, n_rows, dtype):
+    print("case n_rows=%d dtype=%s" % (n_rows, dtype), flush=True)
+    g = torch.Generator(device=DEV).manual_seed(n_rows)
+    ck = P.TableCheckpointer(ctx, n_rows, 64, device=DEV)
+    ck.clear()
+    batches = []
+    for it in range(3):
+        n_idx = max(1, min(200_000, n_rows // 4 + 5))
+        idx = torch.randint(0, n_rows, (n_idx,), generator=g, device=DEV).to(dtype)
+        batches.append(idx)
+        ck.mark(idx)
+    ck.compact()
+    torch.cuda.synchronize()
+    bm, ids, n, _ = _oracle_track(n_rows, [b.cpu().numpy() for b in batches])
+    assert np.array_equal(u32(ck.bitmap)[:bm.size], bm)
+    assert int(ck.n_dirty.item()) == n
+    assert np.array_equal(u32(ck.row_ids)[:n], ids)
+    _poll_clean(ctx)
+
+
+def test_mark_skips_and_counts_out_of_range(ctx):
+    n_rows = 5000
+    ck = P.TableCheckpointer(ctx, n_rows, 64, device=DEV)
+    ck.clear()
+    g = torch.Generator(device=DEV).manual_seed(5)
+    idx = torch.randint(-50, n_rows + 50, (20_000,), generator=g, device=DEV)
+    ck.mark(idx)
+    ck.compact()
+    bm, ids, n, skipped = _oracle_track(n_rows, [idx.cpu().numpy()])
+    st, bad, flags = P.cnr_poll_errors(ctx)
+    assert st == P.CNR_E_INDEX_RANGE and bad == skipped and skipped > 0 and flags == 0
+    assert np.array_equal(u32(ck.bitmap)[:bm.size], bm)
+    assert np.array_equal(u32(ck.row_ids)[:n], ids)
+    _poll_clean(ctx)                                            # counters were reset by the poll
+
+
+def test_compact_empty_full_garbage_padding_and_capacity(ctx):
+    n_rows = 40_001
+    ck = P.TableCheckpointer(ctx, n_rows, 64, device=DEV)
+    ck.clear()
+    ck.compact()
+    assert int(ck.n_dirty.item()) == 0
+    ck.bitmap.fill_(-1)                                         # every bit, padding bits included
+    ck.compact()
+    torch.cuda.synchronize()
+    assert int(ck.n_dirty.item()) == n_rows
+    assert np.array_equal(u32(ck.row_ids)[:n_rows], np.arange(n_rows, dtype=np.uint32))
+    small = P.TableCheckpointer(ctx, n_rows, 64, capacity=1000, device=DEV)
+    small.bitmap.fill_(-1)
+    small.row_ids.fill_(-1)
+    small.compact()
+    st, bad, flags = P.cnr_poll_errors(ctx)
+    assert st == P.CNR_E_CAPACITY and flags & P.CNR_FLAG_CAPACITY
+    assert int(small.n_dirty.item()) == n_rows                  # true count is still reported
+    assert np.array_equal(u32(small.row_ids), np.arange(1000, dtype=np.uint32))
+    _poll_clean(ctx)
+
+
+def test_clear_bitmap_after_marking(ctx):
+    n_rows = 70_000
+    ck = P.TableCheckpointer(ctx, n_rows, 64, device=DEV)
+    ck.mark(torch.arange(0, n_rows, 3, device=DEV))
+    ck.clear()
+    torch.cuda.synchronize()
+    assert not ck.bitmap.any()
+
+
+# ------------------------------------------------------------------ quantize + pack + restore
+
+def _table(n_rows, dim, seed, kind="normal"):
+    if kind == "normal":
+        return synth.table_normal(n_rows, dim, 0.05, seed, DEV)
+    return synth.table_outlier_mix(n_rows, dim, 0.02, seed, DEV)
+
+
+def _dirty(gt, frac, seed):
+    idx = synth.bernoulli_lookup_stream(gt.n_rows, frac, seed, DEV)
+    gt.ck.clear()
+    gt.ck.mark(idx)
+    gt.ck.compact()
+    return idx
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("dim", [64, 128, 256, 8, 40, 96])
+def test_minmax_encode_and_restore(ctx, bits, dim):
+    print("case bits=%d dim=%d" % (bits, dim), flush=True)
+    n_rows = 3001
+    gt = GpuTable(ctx, _table(n_rows, dim, 100 + dim + bits))
+    idx = _dirty(gt, 0.37, bits * 7 + dim)
+    got = gpu_encode_all_outputs(gt, bits)
+    _, ids, n, _ = _oracle_track(n_rows, [idx.cpu().numpy()])
+    assert got["n"] == n
+    ora = O.quantize_rows(gt.host, ids, bits)
+    compare_quantized(gt.host[ids], got, ora, bits, what="minmax b%d d%d" % (bits, dim))
+    # the fused pack is the dense layout of the codes the same kernel reports
+    assert np.array_equal(got["packed"], O.pack(got["codes"], bits))
+    # restore into a stale copy: listed rows are scale*q+bias bit for bit, the rest untouched
+    stale = torch.full_like(gt.table, 123.0)
+    d = got["dev"]
+    P.cnr_restore_rows(ctx, stale, n_rows, dim, d["row_ids"], d["n_dev"], d["n_max"], bits,
+                       d["packed"], d["scale"], d["bias"])
+    torch.cuda.synchronize()
+    want = np.full_like(gt.host, 123.0)
+    O.restore_rows(want, ids, bits, got["packed"], got["scale"], got["bias"])
+    assert np.array_equal(stale.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    _poll_clean(ctx)
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("dim", [64, 128, 24])
+def test_unfused_pack_equals_fused(ctx, bits, dim):
+    n_rows = 1500
+    gt = GpuTable(ctx, _table(n_rows, dim, 7))
+    _dirty(gt, 0.5, 3)
+    got = gpu_encode_all_outputs(gt, bits)
+    n = got["n"]
+    codes = torch.from_numpy(got["codes"].copy()).to(DEV).reshape(-1)
+    out = torch.zeros(max(1, n) * P.cnr_packed_row_bytes(dim, bits), dtype=torch.uint8, device=DEV)
+    n_dev = torch.tensor([n], dtype=torch.int64, device=DEV)
+    P.cnr_pack(ctx, codes, n_dev, n, dim, bits, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy().reshape(n, -1), got["packed"])
+    assert np.array_equal(got["packed"], O.pack(got["codes"], bits))
+
+
+@pytest.mark.parametrize("n", [0, 1, 3, 15, 16, 17, 63, 64, 65, 1000])
+def test_row_counts_without_row_ids(ctx, n):
+    # row_ids == NULL quantizes rows 0..n-1; n is chosen around the 16-row batch of a wavefront
+    dim, bits = 64, 4
+    gt = GpuTable(ctx, _table(max(n, 1), dim, 11 + n))
+    got = gpu_encode_all_outputs(gt, bits, row_ids=None, n=n)
+    if n == 0:
+        return
+    ora = O.quantize_rows(gt.host[:n].copy(), None, bits)
+    compare_quantized(gt.host[:n], got, ora, bits, what="n=%d" % n)
+    assert np.array_equal(got["packed"], O.pack(got["codes"], bits))
+
+
+def test_device_count_overrides_n_max(ctx):
+    dim, bits, n_rows = 128, 3, 900
+    gt = GpuTable(ctx, _table(n_rows, dim, 5))
+    ids = torch.arange(0, n_rows, 2, dtype=torch.int32, device=DEV)
+    n_dev = torch.tensor([37], dtype=torch.int64, device=DEV)
+    scale = torch.full((ids.numel(),), -7.0, device=DEV)
+    bias = torch.full((ids.numel(),), -7.0, device=DEV)
+    packed = torch.full((ids.numel() * 48,), 0xEE, dtype=torch.uint8, device=DEV)
+    P.cnr_quantize_rows(ctx, gt.table, n_rows, dim, ids, n_dev, ids.numel(), bits, P.CNR_RANGE_MINMAX,
+                        None, scale, bias, packed=packed)
+    torch.cuda.synchronize()
+    ora = O.quantize_rows(gt.host, ids.cpu().numpy().view(np.uint32)[:37], bits)
+    assert np.array_equal(scale.cpu().numpy()[:37], ora["scale"])
+    assert torch.all(scale[37:] == -7.0) and torch.all(packed[37 * 48:] == 0xEE)
+    assert np.array_equal(packed.cpu().numpy()[:37 * 48].reshape(37, 48), O.pack(ora["codes"], bits))
+
+
+def test_special_rows(ctx):
+    dim = 64
+    rows = np.zeros((8, dim), dtype=np.float32)
+    rows[0] = 0.375                                    # constant
+    rows[1, ::2] = -0.0                                # zeros of both signs
+    rows[2] = np.linspace(-1, 1, dim)                  # exact-tie prone, symmetric
+    rows[3] = np.float32(1e-41) * np.arange(dim)       # denormals
+    rows[4] = np.float32(1e30) * np.cos(np.arange(dim))
+    rows[5, 7] = 5.0                                   # single spike
+    rows[6] = -np.arange(dim, dtype=np.float32)
+    rows[7] = np.arange(dim) % 4                       # exactly on a 2-bit grid
+    gt = GpuTable(ctx, torch.from_numpy(rows).to(DEV))
+    for bits in BITS:
+        for mode in (P.CNR_RANGE_MINMAX, P.CNR_RANGE_SYMMETRIC):
+            got = gpu_encode_all_outputs(gt, bits, mode=mode, row_ids=None, n=8)
+            ora = O.quantize_rows(rows, None, bits, mode=mode)
+            for k in ("scale", "bias", "row_min", "row_max"):
+                assert np.array_equal(got[k].view(np.uint32), ora[k].view(np.uint32)), (bits, mode, k)
+            assert np.array_equal(got["codes"], ora["codes"]), (bits, mode)
+
+
+@pytest.mark.parametrize("bits", (2, 3, 4))
+@pytest.mark.parametrize("dim", [64, 128, 40])
+@pytest.mark.parametrize("params", [(25, 1.0), (45, 0.6), (100, 1.0)])
+def test_greedy_encode(ctx, bits, dim, params):
+    print("case greedy bits=%d dim=%d params=%s" % (bits, dim, params), flush=True)
+    n_rows = 1237
+    gt = GpuTable(ctx, _table(n_rows, dim, 31 + bits, kind="outlier"))
+    idx = _dirty(gt, 0.3, dim + bits)
+    got = gpu_encode_all_outputs(gt, bits, mode=P.CNR_RANGE_GREEDY, greedy=params)
+    _, ids, n, _ = _oracle_track(n_rows, [idx.cpu().numpy()])
+    assert got["n"] == n
+    ora = O.quantize_rows(gt.host, ids, bits, mode=O.RANGE_GREEDY, num_bins=params[0], ratio=params[1],
+                          n_threads=8)
+    compare_quantized(gt.host[ids], got, ora, bits, greedy=True, what="greedy b%d d%d" % (bits, dim))
+    assert np.array_equal(got["packed"], O.pack(got["codes"], bits))
+    # the search must have moved a fair share of the outlier rows off their min/max range
+    plain = O.quantize_rows(gt.host, ids, bits)
+    assert np.mean(got["scale"] < plain["scale"]) > 0.2
+
+
+def test_greedy_zero_ratio_is_minmax(ctx):
+    gt = GpuTable(ctx, _table(500, 64, 3, kind="outlier"))
+    a = gpu_encode_all_outputs(gt, 4, row_ids=None, n=500)
+    b = gpu_encode_all_outputs(gt, 4, mode=P.CNR_RANGE_GREEDY, greedy=(50, 0.0), row_ids=None, n=500)
+    for k in ("scale", "bias", "codes", "packed"):
+        assert np.array_equal(a[k], b[k])
+
+
+def test_bad_row_ids_are_skipped_and_flagged(ctx):
+    dim, bits, n_rows = 64, 4, 100
+    gt = GpuTable(ctx, _table(n_rows, dim, 9))
+    ids_np = np.array([5, 7, 100, 9, 4_000_000_000, 11], dtype=np.uint32)
+    ids = torch.from_numpy(ids_np.view(np.int32)).to(DEV)
+    scale = torch.full((6,), -7.0, device=DEV)
+    bias = torch.full((6,), -7.0, device=DEV)
+    packed = torch.full((6 * 32,), 0xEE, dtype=torch.uint8, device=DEV)
+    P.cnr_quantize_rows(ctx, gt.table, n_rows, dim, ids, None, 6, bits, P.CNR_RANGE_MINMAX, None, scale,
+                        bias, packed=packed)
+    st, _, flags = P.cnr_poll_errors(ctx)
+    assert st == P.CNR_E_ROW_ID and flags == P.CNR_FLAG_ROW_ID
+    good = [0, 1, 3, 5]
+    ora = O.quantize_rows(gt.host, ids_np[good], bits)
+    assert np.array_equal(scale.cpu().numpy()[good], ora["scale"])
+    assert np.array_equal(packed.cpu().numpy().reshape(6, 32)[good], O.pack(ora["codes"], bits))
+    assert torch.all(scale[[2, 4]] == -7.0) and torch.all(packed.reshape(6, 32)[[2, 4]] == 0xEE)
+    # restore: bad ids are skipped too, nothing outside the table is written
+    stale = torch.zeros_like(gt.table)
+    P.cnr_restore_rows(ctx, stale, n_rows, dim, ids, None, 6, bits, packed, scale, bias)
+    st, _, flags = P.cnr_poll_errors(ctx)
+    assert st == P.CNR_E_ROW_ID
+    touched = torch.nonzero(stale.abs().sum(dim=1)).reshape(-1).cpu().tolist()
+    assert set(touched) <= {5, 7, 9, 11}
+    _poll_clean(ctx)
+
+
+def test_argument_errors(ctx):
+    t = torch.zeros((16, 64), device=DEV)
+    s = torch.zeros(16, device=DEV)
+    with pytest.raises(P.CnrError) as e:
+        P.cnr_quantize_rows(ctx, t, 16, 64, None, None, 16, 5, P.CNR_RANGE_MINMAX, None, s, s)
+    assert e.value.status == P.CNR_E_BITS
+    t2 = torch.zeros((16, 12), device=DEV)
+    with pytest.raises(P.CnrError) as e:
+        P.cnr_quantize_rows(ctx, t2, 16, 12, None, None, 16, 3, P.CNR_RANGE_MINMAX, None, s, s)
+    assert e.value.status == P.CNR_E_DIM                       # 36 bits per row: not whole bytes
+    with pytest.raises(P.CnrError) as e:
+        P.cnr_quantize_rows(ctx, t, 16, 64, None, None, 16, 4, P.CNR_RANGE_GREEDY, None, s, s)
+    assert e.value.status == P.CNR_E_INVALID                   # greedy without parameters
+    with pytest.raises(P.CnrError) as e:
+        P.cnr_quantize_rows(ctx, t.reshape(-1)[1:], 15, 64, None, None, 15, 4, P.CNR_RANGE_MINMAX, None, s, s)
+    assert e.value.status == P.CNR_E_ALIGN
+    _poll_clean(ctx)
+
+
+# ------------------------------------------------------------------ the small benchmark configurations
+
+def test_cfg1_end_to_end(ctx):
+    w = synth.WORKLOADS["cfg1"]
+    gt = GpuTable(ctx, synth.make_table(w, 0, 1, DEV))
+    batches = list(synth.lookup_batches(w, 0, 1, DEV))
+    gt.ck.clear()
+    for b in batches:
+        gt.ck.mark(b)
+    gt.ck.compact()
+    got = gpu_encode_all_outputs(gt, 4)
+    bm, ids, n, _ = _oracle_track(w.n_rows, [b.cpu().numpy() for b in batches])
+    assert np.array_equal(u32(gt.ck.bitmap)[:bm.size], bm)
+    assert got["n"] == n and np.array_equal(u32(gt.ck.row_ids)[:n], ids) and 0 < n <= 4096
+    ora = O.quantize_rows(gt.host, ids, 4)
+    compare_quantized(gt.host[ids], got, ora, 4, what="cfg1")
+    assert np.array_equal(got["packed"], O.pack(ora["codes"], 4))
+    stale = torch.zeros_like(gt.table)
+    d = got["dev"]
+    P.cnr_restore_rows(ctx, stale, w.n_rows, w.dim, d["row_ids"], d["n_dev"], d["n_max"], 4, d["packed"],
+                       d["scale"], d["bias"])
+    want = np.zeros_like(gt.host)
+    O.restore_rows(want, ids, 4, O.pack(ora["codes"], 4), ora["scale"], ora["bias"])
+    assert np.array_equal(stale.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    _poll_clean(ctx)
+
+
+def test_cfg2_two_tables_accumulated_tracking(ctx):
+    # configuration 2 at reduced length: 2 of the 8 tables, 12 of the 200 iterations, full shapes
+    w = synth.WORKLOADS["cfg2"]
+    for ti in range(2):
+        gt = GpuTable(ctx, synth.make_table(w, ti, 2, DEV))
+        batches = list(synth.lookup_batches(w, ti, 2, DEV, iterations=12))
+        gt.ck.clear()
+        for b in batches:
+            gt.ck.mark(b)
+        gt.ck.compact()
+        got = gpu_encode_all_outputs(gt, 4)
+        bm, ids, n, _ = _oracle_track(w.n_rows, [b.cpu().numpy() for b in batches])
+        assert np.array_equal(u32(gt.ck.bitmap)[:bm.size], bm)
+        assert got["n"] == n and np.array_equal(u32(gt.ck.row_ids)[:n], ids)
+        ora = O.quantize_rows(gt.host, ids, 4, n_threads=8)
+        compare_quantized(gt.host[ids], got, ora, 4, what="cfg2 table %d" % ti)
+        assert np.array_equal(got["packed"], O.pack(got["codes"], 4))
+    _poll_clean(ctx)

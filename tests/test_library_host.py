@@ -1,0 +1,116 @@
+"""CPU-side checks of libcnr: the library loads, exports what the header declares, its host-only
+arithmetic agrees with the oracle's, the binding refuses what it must, and the product path has no
+route into the oracle.  No kernel is launched here."""
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2010_08679_amd as P
+from paper_2010_08679_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "cnr.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cnr_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = P.load()
+    declared = _declared_symbols()
+    assert "cnr_mark_touched" in declared and "cnr_restore_rows" in declared and len(declared) >= 15
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert sorted(binding.EXPORTS) == declared
+
+
+def test_size_helpers_match_oracle():
+    for n_rows in (0, 1, 31, 32, 33, 100_000, 5_000_000, 40_000_000):
+        assert P.cnr_bitmap_words(n_rows) == O.bitmap_words(n_rows)
+        assert P.cnr_scratch_bytes(n_rows) >= 4 * max(1, -(-n_rows // 16384))
+    for dim in (4, 8, 12, 64, 100, 128, 4096):
+        for bits in (2, 3, 4, 8):
+            want = O.packed_row_bytes(dim, bits) if (dim * bits) % 8 == 0 else 0
+            assert P.cnr_packed_row_bytes(dim, bits) == want
+    assert P.cnr_packed_row_bytes(64, 5) == 0 and P.cnr_packed_row_bytes(64, 0) == 0
+    # tracking footprint (Section 5.1.1): below 0.05 % of the table for dim >= 64
+    assert 4 * P.cnr_bitmap_words(5_000_000) / (5_000_000 * 64 * 4) < 0.0005
+
+
+def test_greedy_iteration_count_matches_oracle():
+    for num_bins in (0, 1, 2, 10, 25, 45, 50, 100, 1000):
+        for ratio in (0.0, 0.05, 0.1, 0.25, 0.5, 0.6, 0.75, 0.9, 1.0, 1.5):
+            assert P.cnr_greedy_iterations(num_bins, ratio) == O.greedy_iterations(num_bins, ratio)
+    assert P.cnr_greedy_iterations(25, 0.6) == 15 and P.cnr_greedy_iterations(100, 1.0) == 99
+
+
+def test_policy_predictor_matches_oracle():
+    rng = np.random.default_rng(0)
+    assert not P.cnr_full_checkpoint_due([])
+    for _ in range(200):
+        i = int(rng.integers(1, 15))
+        sizes = np.sort(rng.uniform(0.05, 1.0, size=i)).tolist()
+        assert P.cnr_full_checkpoint_due(sizes) == O.full_checkpoint_due(sizes)
+    growth = [0.25 + 0.03 * k for k in range(12)]
+    first = next(i for i in range(1, 12) if P.cnr_full_checkpoint_due(growth[:i]))
+    assert first + 1 == 8                                      # Section 6.3.1: switch at interval 8
+
+
+def test_status_strings():
+    seen = {P.status_str(s) for s in range(9)}
+    assert len(seen) == 9 and "ok" in seen
+
+
+def test_binding_refuses_host_tensors_and_wrong_dtypes():
+    ctx = None                                                 # never reached: checks come first
+    cpu = torch.zeros(8, dtype=torch.int32)
+    with pytest.raises(TypeError):
+        P.cnr_clear_bitmap(ctx, cpu, 8)
+    with pytest.raises(TypeError):
+        P.cnr_mark_touched(ctx, cpu, 8, torch.zeros(4, dtype=torch.float32))
+
+
+def test_no_gpu_means_a_loud_failure():
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(P.CnrError):
+        P.cnr_create(0)
+
+
+def test_product_path_never_touches_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2010_08679_amd")
+    for base, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp", ".c")):
+                text = open(os.path.join(base, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle\b", text, flags=re.M), f
+                assert "cnr_oracle" not in text and "cnro_" not in text, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2010_08679_amd" not in text and "libcnr.so" not in text, f
+
+
+def test_synthetic_inputs_are_seeded_and_shaped():
+    w = synth.WORKLOADS["cfg4"]
+    a = synth.make_table(w, 0, 3, "cpu", n_rows=2000)
+    b = synth.make_table(w, 0, 3, "cpu", n_rows=2000)
+    assert torch.equal(a, b) and a.shape == (2000, 64) and a.dtype == torch.float32
+    frac_out = float((a.abs() > 0.1).float().mean())          # 5 sigma: Laplace tail only
+    assert 0.002 < frac_out < 0.012
+    s = synth.bernoulli_lookup_stream(50_000, 0.3, 1, "cpu")
+    assert 0.28 < torch.unique(s).numel() / 50_000 < 0.32 and s.numel() > torch.unique(s).numel()
+    z = synth.ZipfSampler(10_000, 1.1, 5, "cpu")
+    d = z.draw(200_000)
+    assert d.min() >= 0 and d.max() < 10_000
+    counts = torch.bincount(d, minlength=10_000).sort(descending=True).values
+    assert counts[0] > 20 * counts[500]                        # heavy head
+    w2 = synth.WORKLOADS["cfg2"]
+    it = list(synth.lookup_batches(w2, 0, 1, "cpu", n_rows=10_000, iterations=3))
+    assert len(it) == 3 and it[0].numel() == 2048 * 20
