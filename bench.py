@@ -1,0 +1,265 @@
+#!/usr/bin/env python3
+"""Benchmark of the checkpoint-encoder hot path on one MI355X.
+
+One step = one checkpoint of the whole workload: for every table, clear the tracking bitmap, mark
+it from the table's look-up stream, compact it into the dirty-row list, gather + quantize + pack the
+dirty rows (fused kernel), and restore them into a stale baseline table.  Inputs (tables, index
+streams) are resident in HBM before the timed region.  The reported value is fp32 table bytes
+checkpointed per second over the whole step.
+
+Default workload: the 8 x 5M x 64 outlier-mix tables with 30 % dirty rows, 4 bits, min/max range.
+The same tables are also encoded once per run with the greedy range search (100 bins, ratio 1),
+reported separately against the vector-ALU roofline, and the CPU oracle is timed on a bounded
+sample of the same workload.
+
+Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import paper_2010_08679_amd as P  # noqa: E402
+from paper_2010_08679_amd import synth  # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published
+ISSUE_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # one vector instruction per lane per clock
+
+# HBM traffic of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), in bytes
+# per dirty row, valid only for the kernel source whose hash is recorded with it.
+TRAFFIC_PER_ROW = {
+    # sha256 of csrc/cnr_quantize.hip : (workload, bytes per dirty row)
+}
+
+
+def _kernel_hash() -> str:
+    with open(os.path.join(ROOT, "paper_2010_08679_amd", "csrc", "cnr_quantize.hip"), "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()
+
+
+def encode_bytes_per_row(dim: int, bits: int) -> int:
+    """Algorithmic bytes of the fused encode per dirty row: row id + gathered row + packed codes +
+    scale and bias."""
+    return 4 + 4 * dim + dim * bits // 8 + 8
+
+
+def restore_bytes_per_row(dim: int, bits: int) -> int:
+    return 4 + dim * bits // 8 + 8 + 4 * dim
+
+
+class Timer:
+    """Pairs of events on the current stream, summed per label."""
+
+    def __init__(self):
+        self.pairs = {}
+
+    def span(self, label):
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        self.pairs.setdefault(label, []).append((a, b))
+        return a, b
+
+    def totals_ms(self):
+        return {k: sum(a.elapsed_time(b) for a, b in v) for k, v in self.pairs.items()}
+
+    def counts(self):
+        return {k: len(v) for k, v in self.pairs.items()}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg4", choices=sorted(synth.WORKLOADS))
+    ap.add_argument("--tables", type=int, default=0, help="use only the first N tables (0 = all)")
+    ap.add_argument("--bits", type=int, default=4)
+    ap.add_argument("--no-greedy", action="store_true", help="skip the greedy-range extra")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--seed", type=int, default=4)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (each GPU checkpoints its own table "
+              "shard independently); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = synth.WORKLOADS[args.workload]
+    n_tables = w.n_tables if args.tables <= 0 else min(args.tables, w.n_tables)
+    bits = args.bits
+    ctx = P.cnr_create(0)
+
+    # ---- resident inputs ------------------------------------------------------------------------
+    tables, streams, cks, encs = [], [], [], []
+    for ti in range(n_tables):
+        tables.append(synth.make_table(w, ti, args.seed, dev))
+        if w.lookups == "bernoulli":
+            batches = list(synth.lookup_batches(w, ti, args.seed, dev))
+        else:
+            batches = list(synth.lookup_batches(w, ti, args.seed, dev, iterations=min(w.iterations or 8, 64)))
+        streams.append(torch.cat([b.reshape(-1) for b in batches]))
+        ck = P.TableCheckpointer(ctx, w.n_rows, w.dim, device=dev)
+        cks.append(ck)
+        encs.append(ck.alloc_output(bits))
+    stale = torch.zeros((w.n_rows, w.dim), dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+
+    def step(timer: Timer | None):
+        for ti in range(n_tables):
+            ck, enc = cks[ti], encs[ti]
+            if timer is None:
+                ck.clear(); ck.mark(streams[ti]); ck.compact(); ck.encode(tables[ti], enc); ck.restore(stale, enc)
+                continue
+            for label, fn in (("clear", ck.clear), ("mark", lambda: ck.mark(streams[ti])),
+                              ("compact", ck.compact), ("encode", lambda: ck.encode(tables[ti], enc)),
+                              ("restore", lambda: ck.restore(stale, enc))):
+                a, b = timer.span(label)
+                a.record()
+                fn()
+                b.record()
+
+    for _ in range(args.warmup):
+        step(None)
+    torch.cuda.synchronize()
+    st, bad, flags = P.cnr_poll_errors(ctx)
+    assert (st, bad, flags) == (P.CNR_OK, 0, 0), (st, bad, flags)
+    n_dirty = [int(c.n_dirty.item()) for c in cks]
+
+    timer = Timer()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(timer)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_per_step = wall * 1e3 / args.steps
+    table_bytes = sum(n_dirty) * w.dim * 4
+    value = table_bytes / (ms_per_step * 1e-3) / 1e9
+    stage_ms = {k: v / args.steps for k, v in timer.totals_ms().items()}
+    launches = timer.counts()
+
+    # dominant kernel: the fused gather + quantize + pack
+    enc_launch_ms = timer.totals_ms()["encode"] / launches["encode"]
+    rows_per_launch = sum(n_dirty) / n_tables
+    enc_bytes = encode_bytes_per_row(w.dim, bits) * rows_per_launch
+    achieved = enc_bytes / (enc_launch_ms * 1e-3) / 1e9
+    traffic = None
+    rec = TRAFFIC_PER_ROW.get(_kernel_hash())
+    if rec and rec[0] == "%s/b%d" % (w.name, bits):
+        traffic = rec[1] * rows_per_launch
+    roofline = {"bound": "hbm", "kernel": "quantize_rows16_kernel<%d,%d,false>" % (w.dim // 64, bits),
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                "bytes_per_launch": int(enc_bytes), "avg_launch_ms": round(enc_launch_ms, 5)}
+    res_ms = timer.totals_ms()["restore"] / launches["restore"]
+    res_bytes = restore_bytes_per_row(w.dim, bits) * rows_per_launch
+    stages = {k: round(v, 4) for k, v in stage_ms.items()}
+    stages["encode_only_GBps_table_bytes"] = round(table_bytes / ((stage_ms["compact"] + stage_ms["encode"]) * 1e-3) / 1e9, 1)
+    stages["restore_hbm_GBps"] = round(res_bytes / (res_ms * 1e-3) / 1e9, 1)
+    stages["mark_Gidx_per_s"] = round(sum(s.numel() for s in streams) / (stage_ms["mark"] * 1e-3) / 1e9, 2)
+
+    out = {
+        "metric": "checkpoint encode GB/s (fp32 table bytes)", "value": round(value, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s: %d tables x %d rows x dim %d, %s values, %.1f%% dirty, %d-bit min/max "
+                               "range, step = clear+mark+compact+encode+restore per table"
+                               % (w.name, n_tables, w.n_rows, w.dim, w.values,
+                                  100.0 * sum(n_dirty) / (n_tables * w.n_rows), bits),
+                   "dirty_rows": sum(n_dirty), "lookups_per_step": int(sum(s.numel() for s in streams)),
+                   "index_dtype": "int64"},
+        "roofline": roofline,
+        "stages_ms_per_step": stages,
+    }
+
+    # ---- greedy range search on the same tables (ALU-bound) ---------------------------------------
+    if not args.no_greedy and w.num_bins:
+        g_ms = []
+        for rep in range(2):
+            a = torch.cuda.Event(enable_timing=True)
+            b = torch.cuda.Event(enable_timing=True)
+            a.record()
+            for ti in range(n_tables):
+                cks[ti].encode(tables[ti], encs[ti], mode=P.CNR_RANGE_GREEDY, greedy=(w.num_bins, w.ratio))
+            b.record()
+            torch.cuda.synchronize()
+            g_ms.append(a.elapsed_time(b))
+        g = min(g_ms)
+        n_iter = P.cnr_greedy_iterations(w.num_bins, w.ratio)
+        # arithmetic the search itself prescribes, per element and candidate range: clip (2), subtract,
+        # divide, round, multiply, add, subtract, square, accumulate = 10
+        flops = sum(n_dirty) * w.dim * (1 + 2 * n_iter) * 10.0
+        out["greedy"] = {
+            "workload": "%d-bit greedy range, num_bins=%d, ratio=%.2f (%d candidate ranges per row)"
+                        % (bits, w.num_bins, w.ratio, 1 + 2 * n_iter),
+            "ms": round(g, 3), "value": round(table_bytes / (g * 1e-3) / 1e9, 2), "unit": "GB/s",
+            "roofline": {"bound": "alu", "achieved": round(flops / (g * 1e-3) / 1e12, 2),
+                         "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": round(flops / (g * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TFLOPS, 4),
+                         "issue_peak_Tops": round(ISSUE_PEAK_TOPS, 1), "traffic": None},
+        }
+
+    # ---- CPU oracle on a bounded sample -----------------------------------------------------------
+    if not args.no_cpu:
+        import oracle as O
+        threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)
+        threads = max(1, min(threads, os.cpu_count() or 1))
+        host_table = tables[0].cpu().numpy()
+        host_idx = streams[0].cpu().numpy()
+        t0 = time.perf_counter()
+        bm = O.new_bitmap(w.n_rows)
+        O.mark_touched(bm, w.n_rows, host_idx)
+        ids, n = O.compact_dirty(bm, w.n_rows)
+        q = O.quantize_rows(host_table, ids, bits, n_threads=threads)
+        packed = O.pack(q["codes"], bits)
+        host_stale = np.zeros_like(host_table)
+        O.restore_rows(host_stale, ids, bits, packed, q["scale"], q["bias"], n_threads=threads)
+        cpu_s = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(n * w.dim * 4 / cpu_s / 1e9, 4), "unit": "GB/s", "cores": threads,
+                               "kind": "oracle", "seconds": round(cpu_s, 2),
+                               "sample": "table 0 of %d (%d rows, %d dirty): mark+compact+%d-bit min/max "
+                                         "quantize+pack+restore; quantize and restore on %d threads, the "
+                                         "rest on one" % (n_tables, w.n_rows, n, bits, threads)}
+        # the GPU result for the same table must be what the oracle produced
+        assert n == n_dirty[0]
+        cks[0].clear(); cks[0].mark(streams[0]); cks[0].compact(); cks[0].encode(tables[0], encs[0])
+        torch.cuda.synchronize()
+        assert np.array_equal(encs[0].row_ids.cpu().numpy().view(np.uint32)[:n], ids)
+        assert np.array_equal(encs[0].scale.cpu().numpy()[:n], q["scale"])
+        gp = encs[0].packed.cpu().numpy()[:n * packed.shape[1]].reshape(n, -1)
+        assert np.mean(gp != packed) <= 1e-4
+        if "greedy" in out:
+            m = min(n, 20000)
+            t0 = time.perf_counter()
+            O.quantize_rows(host_table, ids[:m], bits, mode=O.RANGE_GREEDY, num_bins=w.num_bins,
+                            ratio=w.ratio, n_threads=threads, want_codes=False)
+            gs = time.perf_counter() - t0
+            out["greedy"]["cpu_baseline"] = {"value": round(m * w.dim * 4 / gs / 1e9, 5), "unit": "GB/s",
+                                             "cores": threads, "kind": "oracle",
+                                             "sample": "first %d dirty rows of table 0" % m}
+
+    P.cnr_destroy(ctx)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
