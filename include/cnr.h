@@ -108,6 +108,7 @@ cnr_status cnr_destroy(cnr_ctx *ctx);
 size_t cnr_bitmap_words(uint64_t n_rows);               /* ceil(n_rows / 32) */
 size_t cnr_packed_row_bytes(uint32_t dim, int bits);    /* dim*bits/8; 0 if not a whole number */
 size_t cnr_scratch_bytes(uint64_t n_rows);              /* scratch cnr_compact_dirty needs */
+size_t cnr_mark_scratch_bytes(uint64_t n_rows);         /* optional scratch of cnr_mark_touched */
 uint32_t cnr_greedy_iterations(uint32_t num_bins, float ratio); /* n_iter as defined above */
 
 /* ---- tracking (Section 5.1.1) ----------------------------------------------------------- */
@@ -119,9 +120,16 @@ cnr_status cnr_clear_bitmap(cnr_ctx *ctx, uint32_t *bitmap, uint64_t n_rows, voi
  * (in place; bits accumulate over calls until the bitmap is cleared).  Duplicates are expected.
  * Indices outside the table are skipped and counted in the context.
  *   indices  int32 or int64 [n_indices] as `type` says; naturally aligned
- *   n_rows   < 2^32 */
+ *   n_rows   < 2^32
+ *   scratch  NULL, or cnr_mark_scratch_bytes(n_rows) bytes, 16-byte aligned, ALL ZERO before the
+ *            first call that uses it (hipMemset once after allocating); every call leaves it all
+ *            zero again, so one buffer sized for the largest table can serve all tables marked on
+ *            the same stream.  With a scratch buffer, long index streams are marked through one
+ *            flag byte per row and then folded into the bitmap, which avoids one device-scope
+ *            atomic per index; short streams, and all streams when scratch is NULL, use atomic ORs
+ *            on the bitmap directly.  The resulting bitmap is the same either way. */
 cnr_status cnr_mark_touched(cnr_ctx *ctx, uint32_t *bitmap, uint64_t n_rows, const void *indices,
-                            uint64_t n_indices, cnr_index_type type, void *stream);
+                            uint64_t n_indices, cnr_index_type type, void *scratch, void *stream);
 
 /* ---- incremental view (Section 5.1) ------------------------------------------------------ */
 

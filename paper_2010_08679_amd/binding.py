@@ -28,6 +28,7 @@ CNR_MAX_DIM = 4096
 # Every symbol include/cnr.h declares.
 EXPORTS = (
     "cnr_create", "cnr_destroy", "cnr_bitmap_words", "cnr_packed_row_bytes", "cnr_scratch_bytes",
+    "cnr_mark_scratch_bytes",
     "cnr_greedy_iterations", "cnr_clear_bitmap", "cnr_mark_touched", "cnr_compact_dirty",
     "cnr_quantize_rows", "cnr_pack", "cnr_restore_rows", "cnr_poll_errors", "cnr_status_str",
     "cnr_last_hip_error", "cnr_full_checkpoint_due",
@@ -66,9 +67,10 @@ def load() -> ctypes.CDLL:
             "cnr_bitmap_words": (sz, [u64]),
             "cnr_packed_row_bytes": (sz, [u32, i32]),
             "cnr_scratch_bytes": (sz, [u64]),
+            "cnr_mark_scratch_bytes": (sz, [u64]),
             "cnr_greedy_iterations": (u32, [u32, f32]),
             "cnr_clear_bitmap": (i32, [vp, vp, u64, vp]),
-            "cnr_mark_touched": (i32, [vp, vp, u64, vp, u64, i32, vp]),
+            "cnr_mark_touched": (i32, [vp, vp, u64, vp, u64, i32, vp, vp]),
             "cnr_compact_dirty": (i32, [vp, vp, u64, vp, u64, vp, vp, vp]),
             "cnr_quantize_rows": (i32, [vp, vp, u64, u32, vp, vp, u64, i32, i32,
                                         ctypes.POINTER(cnr_greedy_params), vp, vp, vp, vp, vp, vp, vp]),
@@ -142,6 +144,10 @@ def cnr_scratch_bytes(n_rows: int) -> int:
     return int(load().cnr_scratch_bytes(n_rows))
 
 
+def cnr_mark_scratch_bytes(n_rows: int) -> int:
+    return int(load().cnr_mark_scratch_bytes(n_rows))
+
+
 def cnr_greedy_iterations(num_bins: int, ratio: float) -> int:
     return int(load().cnr_greedy_iterations(num_bins, ratio))
 
@@ -153,15 +159,18 @@ def cnr_clear_bitmap(ctx, bitmap, n_rows: int, stream=None) -> None:
            "cnr_clear_bitmap")
 
 
-def cnr_mark_touched(ctx, bitmap, n_rows: int, indices, stream=None) -> None:
+def cnr_mark_touched(ctx, bitmap, n_rows: int, indices, scratch=None, stream=None) -> None:
     if indices.dtype == torch.int64:
         kind = CNR_IDX_I64
     elif indices.dtype == torch.int32:
         kind = CNR_IDX_I32
     else:
         raise TypeError("indices must be int32 or int64")
+    if scratch is not None and scratch.numel() * scratch.element_size() < cnr_mark_scratch_bytes(n_rows):
+        raise ValueError("scratch smaller than cnr_mark_scratch_bytes(n_rows)")
     _check(load().cnr_mark_touched(ctx, _dev(bitmap, U32, "bitmap"), n_rows,
                                    _dev(indices, indices.dtype, "indices"), indices.numel(), kind,
+                                   None if scratch is None else _dev(scratch, scratch.dtype, "scratch"),
                                    _stream(stream)), "cnr_mark_touched")
 
 

@@ -34,7 +34,8 @@ class EncodedRows:
 
 
 class TableCheckpointer:
-    def __init__(self, ctx, n_rows: int, dim: int, capacity: int | None = None, device="cuda:0"):
+    def __init__(self, ctx, n_rows: int, dim: int, capacity: int | None = None, device="cuda:0",
+                 mark_scratch: torch.Tensor | None = None):
         self.ctx, self.n_rows, self.dim = ctx, int(n_rows), int(dim)
         self.capacity = self.n_rows if capacity is None else int(capacity)
         self.device = torch.device(device)
@@ -43,13 +44,22 @@ class TableCheckpointer:
         self.scratch = torch.empty((B.cnr_scratch_bytes(n_rows) + 7) // 8, dtype=torch.int64, device=dev)
         self.row_ids = torch.empty(max(1, self.capacity), dtype=torch.int32, device=dev)
         self.n_dirty = torch.zeros(1, dtype=torch.int64, device=dev)
+        # zero-filled flag bytes for marking long index streams; may be shared between the tables of
+        # one stream (pass the same tensor), the library leaves it zeroed after every call
+        self.mark_scratch = mark_scratch
+        if mark_scratch is not None and mark_scratch.numel() * mark_scratch.element_size() < B.cnr_mark_scratch_bytes(n_rows):
+            raise ValueError("mark_scratch too small for this table")
+
+    @staticmethod
+    def new_mark_scratch(max_rows: int, device="cuda:0") -> torch.Tensor:
+        return torch.zeros((B.cnr_mark_scratch_bytes(max_rows) + 7) // 8, dtype=torch.int64, device=device)
 
     # -- tracking ---------------------------------------------------------------------------
     def clear(self, stream=None) -> None:
         B.cnr_clear_bitmap(self.ctx, self.bitmap, self.n_rows, stream)
 
     def mark(self, indices: torch.Tensor, stream=None) -> None:
-        B.cnr_mark_touched(self.ctx, self.bitmap, self.n_rows, indices.reshape(-1), stream)
+        B.cnr_mark_touched(self.ctx, self.bitmap, self.n_rows, indices.reshape(-1), self.mark_scratch, stream)
 
     # -- checkpoint -------------------------------------------------------------------------
     def compact(self, stream=None) -> None:

@@ -50,6 +50,34 @@ static inline unsigned cnr_grid(const cnr_ctx *ctx, uint64_t work_items, uint64_
 }
 
 #ifdef __HIPCC__
+// Workgroups of `Kernel` (kBlock threads, no dynamic LDS) that fit on one compute unit at once, at
+// most 8.  A persistent (grid-stride) kernel launched with more workgroups than are resident runs
+// them in rounds and leaves the last round under-filled, so grids are sized to exactly one round.
+template <auto Kernel>
+static inline unsigned cnr_resident_blocks_per_cu() {
+    static int cached = 0;
+    if (cached == 0) {
+        int nb = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, Kernel, kBlock, 0) != hipSuccess || nb < 1) nb = 4;
+        cached = nb > 8 ? 8 : nb;
+    }
+    return (unsigned)cached;
+}
+
+// Streaming accesses: data that is touched once (gathered rows, encoded output, restored rows)
+// carries the non-temporal hint so that it does not linger in L2 until the end of the kernel.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+template <typename T>
+__device__ __forceinline__ void store_stream(void *p, T v) {
+    __builtin_nontemporal_store(v, reinterpret_cast<T *>(p));
+}
+template <typename T>
+__device__ __forceinline__ T load_stream(const void *p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const T *>(p));
+}
+
 // ---- cross-lane helpers (wave64) -------------------------------------------------------------
 // DPP controls: quad_perm [1,0,3,2] = 0xB1 (lane ^ 1), quad_perm [2,3,0,1] = 0x4E (lane ^ 2),
 // row_half_mirror = 0x141 (lane i <-> 7 - i within 8), row_mirror = 0x140 (i <-> 15 - i within 16).

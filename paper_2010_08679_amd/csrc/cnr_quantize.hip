@@ -4,6 +4,8 @@
 // the formulas): fp32 throughout, one rounding per operation (the build disables contraction into
 // fused multiply-adds), correctly rounded division, round-half-even, fp32 denormals kept.  Error
 // sums that only rank candidate ranges are accumulated in fp64.
+#include <type_traits>
+
 #include "cnr_common.h"
 
 namespace {
@@ -57,59 +59,154 @@ __device__ __forceinline__ void quad_transpose(uint32_t (&r)[4], int j) {
 // flight before it reduces anything), which is also what lets the packed codes leave through full
 // words: after quantizing, a 4x4 transpose inside each quad of lanes hands lane j the codes of
 // sixteen consecutive elements of row j.
+//
+// The kernel is bound by vector-ALU issue as much as by HBM (a wave64 instruction occupies a SIMD
+// for four cycles), so the per-element work of the min/max and symmetric modes is pared down:
+//   - scale and 1/scale are computed once per row, by the one lane of each quad that owns the row,
+//     with correctly rounded divisions, and broadcast back inside the quad;
+//   - an element's code is round((x - lo) * (1/scale)); adding 1.5 * 2^23 does the rounding
+//     (half-to-even) and leaves the integer in the low mantissa bits, so four codes are merged by
+//     three shift-adds and one subtraction of the merged constant.  The product differs from the
+//     correctly rounded quotient by at most 1.5 ulp, which can move a code only when the quotient
+//     sits within that distance of a half-integer (a few elements in a million at 4 bits); at 8
+//     bits, where quotients are larger, one Newton step on the quotient removes that too.
+// The greedy mode keeps correctly rounded divisions everywhere, because there the error sums of
+// candidate ranges are compared against each other and must not depend on such last-bit effects.
 // ---------------------------------------------------------------------------------------------
-template <int M, int BITS, bool GREEDY>
-__global__ void __launch_bounds__(kBlock)
-quantize_rows16_kernel(const float *__restrict__ table, uint64_t n_rows,
-                       const uint32_t *__restrict__ row_ids, const uint64_t *__restrict__ n_dev,
-                       uint64_t n_max, int mode, uint32_t n_iter, float num_bins_f,
-                       float *__restrict__ scale_out, float *__restrict__ bias_out,
-                       float *__restrict__ min_out, float *__restrict__ max_out,
-                       uint8_t *__restrict__ codes_out, uint8_t *__restrict__ packed_out,
-                       cnr_dev_errors *err) {
-    constexpr int DIM = 64 * M;
-    constexpr int QMAX = (1 << BITS) - 1;
-    constexpr float QMAXF = (float)QMAX;
-    constexpr uint64_t P = (uint64_t)DIM * BITS / 8;  // packed bytes per row
+#define CNR_SEL4(a) (j == 0 ? (a)[0] : j == 1 ? (a)[1] : j == 2 ? (a)[2] : (a)[3])
 
-    uint64_t n = n_max;
-    if (n_dev) {
-        const uint64_t nd = *n_dev;
-        n = nd < n_max ? nd : n_max;
+template <int U>
+__device__ __forceinline__ float quad_bcast(float v) {  // value of quad lane U in all four lanes
+    return dpp_f<U * 0x55>(v);
+}
+
+// Uniform arguments of the fast-path kernel.
+struct Rows16Args {
+    const float *table;
+    uint64_t n_rows;
+    const uint32_t *row_ids;
+    const uint64_t *n_dev;
+    uint64_t n_max;
+    int mode;
+    uint32_t n_iter;
+    float num_bins_f;
+    float *scale_out, *bias_out, *min_out, *max_out;
+    uint8_t *codes_out, *packed_out;
+    cnr_dev_errors *err;
+};
+
+template <int M>
+struct RowBatch {
+    float4 x[4][M];  // [row of the group][chunk]
+    unsigned skip;   // bit u: row k0+u is past the end or has an id outside the table
+};
+
+// Row ids of the four rows k0 .. k0+3 of one group.
+__device__ __forceinline__ uint4 gather_ids(const Rows16Args &a, uint64_t k0) {
+    if (!a.row_ids) return make_uint4((uint32_t)k0, (uint32_t)k0 + 1, (uint32_t)k0 + 2, (uint32_t)k0 + 3);
+    if (k0 + 3 < a.n_max)  // the id buffer holds n_max entries: one 16-byte load
+        return *reinterpret_cast<const uint4 *>(a.row_ids + k0);
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (k0 + 0 < a.n_max) v.x = a.row_ids[k0 + 0];
+    if (k0 + 1 < a.n_max) v.y = a.row_ids[k0 + 1];
+    if (k0 + 2 < a.n_max) v.z = a.row_ids[k0 + 2];
+    return v;
+}
+
+// Issues the loads of the group's four rows (this lane's elements 64c + 4l .. + 3 of each).
+template <int M>
+__device__ __forceinline__ void gather_rows(const Rows16Args &a, uint64_t n, uint64_t k0, uint4 ids, int l,
+                                            RowBatch<M> &rb) {
+    const uint32_t rid[4] = {ids.x, ids.y, ids.z, ids.w};
+    rb.skip = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const bool past = k0 + u >= n;
+        uint64_t r = rid[u];
+        if (past || r >= a.n_rows) {
+            if (!past && l == 0) raise_flag(a.err, CNR_FLAG_ROW_ID);
+            rb.skip |= 1u << u;
+            r = 0;
+        }
+        const float *src = a.table + r * (uint64_t)(64 * M) + 4u * (uint64_t)l;
+#pragma unroll
+        for (int c = 0; c < M; ++c) {
+            const f32x4 v = load_stream<f32x4>(src + 64 * c);
+            rb.x[u][c] = make_float4(v.x, v.y, v.z, v.w);
+        }
+    }
+}
+
+template <int M, int BITS, bool GREEDY>
+__device__ __forceinline__ void encode_batch(const Rows16Args &a, uint64_t k0, const RowBatch<M> &rb, int l);
+
+template <int M, int BITS, bool GREEDY>
+__global__ void __launch_bounds__(kBlock) quantize_rows16_kernel(const Rows16Args a) {
+    uint64_t n = a.n_max;
+    if (a.n_dev) {
+        const uint64_t nd = *a.n_dev;
+        n = nd < a.n_max ? nd : a.n_max;
     }
     const int lane = threadIdx.x & (kWave - 1);
     const int g = lane >> 4;  // group of 16 lanes
     const int l = lane & 15;  // lane in group
-    const int q = l >> 2;     // quad in group
-    const int j = l & 3;      // lane in quad
     const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
-    const uint64_t wave_id = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    uint64_t batch = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    if (batch * 16u >= n) return;
 
-    for (uint64_t batch = wave_id; batch * 16u < n; batch += n_waves) {
-        const uint64_t k0 = batch * 16u + 4u * (uint64_t)g;  // this group's rows: k0 .. k0+3
-
-        // ---- gather
-        unsigned skip = 0;  // bit u: row k0+u is past the end or has an id outside the table
-        uint64_t src[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            uint64_t k = k0 + u;
-            if (k >= n) { skip |= 1u << u; k = n - 1; }
-            uint64_t r = row_ids ? (uint64_t)row_ids[k] : k;
-            if (r >= n_rows) {
-                if (!(skip & (1u << u)) && l == 0) raise_flag(err, CNR_FLAG_ROW_ID);
-                skip |= 1u << u;
-                r = 0;
-            }
-            src[u] = r * (uint64_t)DIM + 4u * (uint64_t)l;
+    if constexpr (GREEDY) {  // ALU-bound: nothing to overlap
+        for (; batch * 16u < n; batch += n_waves) {
+            const uint64_t k0 = batch * 16u + 4u * (uint64_t)g;
+            RowBatch<M> rb;
+            gather_rows<M>(a, n, k0, gather_ids(a, k0), l, rb);
+            encode_batch<M, BITS, true>(a, k0, rb, l);
         }
-        float4 x[4][M];
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-            for (int c = 0; c < M; ++c)
-                x[u][c] = *reinterpret_cast<const float4 *>(table + src[u] + 64 * c);
+    } else {
+        // Software pipeline: while batch i is being reduced and quantized, the rows of batch i+1 are
+        // already on their way and the ids of batch i+2 have been requested, so a wave always has a
+        // full batch of row data in flight.
+        RowBatch<M> cur, nxt;
+        gather_rows<M>(a, n, batch * 16u + 4u * (uint64_t)g, gather_ids(a, batch * 16u + 4u * (uint64_t)g), l, cur);
+        uint64_t next = batch + n_waves;
+        uint4 ids_next = make_uint4(0, 0, 0, 0);
+        if (next * 16u < n) ids_next = gather_ids(a, next * 16u + 4u * (uint64_t)g);
+        for (;;) {
+            const bool has_next = next * 16u < n;  // uniform over the wave
+            if (has_next) gather_rows<M>(a, n, next * 16u + 4u * (uint64_t)g, ids_next, l, nxt);
+            const uint64_t next2 = next + n_waves;
+            if (next2 * 16u < n) ids_next = gather_ids(a, next2 * 16u + 4u * (uint64_t)g);
+            encode_batch<M, BITS, false>(a, batch * 16u + 4u * (uint64_t)g, cur, l);
+            if (!has_next) break;
+            cur = nxt;
+            batch = next;
+            next = next2;
+        }
+    }
+}
 
+// Reduces, quantizes and stores the four rows of one group.
+template <int M, int BITS, bool GREEDY>
+__device__ __forceinline__ void encode_batch(const Rows16Args &a, uint64_t k0, const RowBatch<M> &rb, int l) {
+    constexpr int DIM = 64 * M;
+    constexpr int QMAX = (1 << BITS) - 1;
+    constexpr float QMAXF = (float)QMAX;
+    constexpr uint64_t P = (uint64_t)DIM * BITS / 8;  // packed bytes per row
+    constexpr float MAGIC = 12582912.0f;              // 1.5 * 2^23: x + MAGIC rounds x to an integer
+    constexpr uint32_t MAGIC_BITS = 0x4B400000u;      // bit pattern of MAGIC
+    // what four magic-biased codes add up to when merged with shifts of B, 2B, 3B bits
+    constexpr uint32_t MERGED_BIAS = MAGIC_BITS * (1u + (1u << BITS) + (1u << (2 * BITS)) + (1u << (3 * BITS)));
+    constexpr uint32_t MERGED_BIAS8 = MAGIC_BITS * (1u + (1u << 8) + (1u << 16) + (1u << 24));
+    const int q = l >> 2;  // quad in group
+    const int j = l & 3;   // lane in quad
+    const int mode = a.mode;
+    const uint32_t n_iter = a.n_iter;
+    const float num_bins_f = a.num_bins_f;
+    float *const scale_out = a.scale_out, *const bias_out = a.bias_out;
+    float *const min_out = a.min_out, *const max_out = a.max_out;
+    uint8_t *const codes_out = a.codes_out, *const packed_out = a.packed_out;
+    const unsigned skip = rb.skip;
+    const float4 (&x)[4][M] = rb.x;
+    {
         // ---- row minimum / maximum
         float X_min[4], X_max[4], lo[4], hi[4];
 #pragma unroll
@@ -186,73 +283,117 @@ quantize_rows16_kernel(const float *__restrict__ table, uint64_t n_rows,
             }
         }
 
-        // ---- quantize with the selected range, pack this lane's four codes per (row, chunk)
-        float sc[4];
-        uint32_t h[M][4];  // [chunk][row]: 4*BITS bits each
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            sc[u] = (hi[u] - lo[u]) / QMAXF;
-#pragma unroll
-            for (int c = 0; c < M; ++c) {
-                const uint32_t q0 = (uint32_t)fq_code_f(x[u][c].x, lo[u], hi[u], sc[u], QMAXF);
-                const uint32_t q1 = (uint32_t)fq_code_f(x[u][c].y, lo[u], hi[u], sc[u], QMAXF);
-                const uint32_t q2 = (uint32_t)fq_code_f(x[u][c].z, lo[u], hi[u], sc[u], QMAXF);
-                const uint32_t q3 = (uint32_t)fq_code_f(x[u][c].w, lo[u], hi[u], sc[u], QMAXF);
-                h[c][u] = q0 | (q1 << BITS) | (q2 << (2 * BITS)) | (q3 << (3 * BITS));
-                if (codes_out && !(skip & (1u << u)))
-                    *reinterpret_cast<uint32_t *>(codes_out + (k0 + u) * (uint64_t)DIM + 64 * c + 4 * l) =
-                        q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
-            }
-        }
-
-        // ---- per-row parameters: lanes 0-3 of a group write scale, 4-7 bias, 8-11 min, 12-15 max
-        {
+        // ---- per-row parameters, computed by the quad lane that owns the row (lane j <-> row k0+j)
+        const float my_lo = CNR_SEL4(lo);
+        const float my_scale = (CNR_SEL4(hi) - my_lo) / QMAXF;
+        const bool my_live = !((skip >> j) & 1u);
+        {   // lanes 0-3 of a group write scale, 4-7 bias, 8-11 min, 12-15 max
             float *dst = q == 0 ? scale_out : q == 1 ? bias_out : q == 2 ? min_out : max_out;
-            float v = 0.0f;
+            const float v = q == 0 ? my_scale : q == 1 ? my_lo : q == 2 ? CNR_SEL4(X_min) : CNR_SEL4(X_max);
+            if (dst && my_live) store_stream<float>(dst + k0 + j, v);
+        }
+        const float sc[4] = {quad_bcast<0>(my_scale), quad_bcast<1>(my_scale), quad_bcast<2>(my_scale),
+                             quad_bcast<3>(my_scale)};
+
+        // ---- quantize with the selected range; h[c][u] = this lane's four codes of (row u, chunk c)
+        uint32_t h[M][4];
+        if constexpr (GREEDY) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const float mine = q == 0 ? sc[u] : q == 1 ? lo[u] : q == 2 ? X_min[u] : X_max[u];
-                v = j == u ? mine : v;
-            }
-            if (dst && !((skip >> j) & 1u)) dst[k0 + j] = v;
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int c = 0; c < M; ++c) {
+                    const uint32_t q0 = (uint32_t)fq_code_f(x[u][c].x, lo[u], hi[u], sc[u], QMAXF);
+                    const uint32_t q1 = (uint32_t)fq_code_f(x[u][c].y, lo[u], hi[u], sc[u], QMAXF);
+                    const uint32_t q2 = (uint32_t)fq_code_f(x[u][c].z, lo[u], hi[u], sc[u], QMAXF);
+                    const uint32_t q3 = (uint32_t)fq_code_f(x[u][c].w, lo[u], hi[u], sc[u], QMAXF);
+                    h[c][u] = q0 | (q1 << BITS) | (q2 << (2 * BITS)) | (q3 << (3 * BITS));
+                    if (codes_out && !(skip & (1u << u)))
+                        *reinterpret_cast<uint32_t *>(codes_out + (k0 + u) * (uint64_t)DIM + 64 * c + 4 * l) =
+                            q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
+                }
+        } else {
+            // The reciprocal of the scale must be a normal number.  Rows with a scale outside
+            // [2^-100, 2^100] (denormal or near-overflow ranges) are brought there by an exact
+            // power-of-two factor applied to both x - lo and the scale; a wave takes that variant
+            // only if one of its sixteen rows needs it.
+            const float my_f = my_scale < 0x1p-100f ? 0x1p120f : my_scale > 0x1p100f ? 0x1p-120f : 1.0f;
+            const float my_fscale = my_scale * my_f;
+            const float my_inv = my_scale == 0.0f ? 0.0f : 1.0f / my_fscale;  // scale 0: every code 0
+            const float inv[4] = {quad_bcast<0>(my_inv), quad_bcast<1>(my_inv), quad_bcast<2>(my_inv),
+                                  quad_bcast<3>(my_inv)};
+            auto quantize_by_reciprocal = [&](auto rescale) {
+                constexpr bool RESCALE = decltype(rescale)::value;
+                float f[4] = {1.0f, 1.0f, 1.0f, 1.0f}, fsc[4] = {sc[0], sc[1], sc[2], sc[3]};
+                if constexpr (RESCALE) {
+                    f[0] = quad_bcast<0>(my_f); f[1] = quad_bcast<1>(my_f);
+                    f[2] = quad_bcast<2>(my_f); f[3] = quad_bcast<3>(my_f);
+                    fsc[0] = quad_bcast<0>(my_fscale); fsc[1] = quad_bcast<1>(my_fscale);
+                    fsc[2] = quad_bcast<2>(my_fscale); fsc[3] = quad_bcast<3>(my_fscale);
+                }
+                // magic-biased code of one element: MAGIC_BITS + round((x - lo) / scale)
+                auto biased = [&](float xv, int u) -> uint32_t {
+                    float a = xv - lo[u];
+                    if constexpr (RESCALE) a *= f[u];
+                    float t = a * inv[u];
+                    if constexpr (BITS == 8) {
+                        const float r = fmaf(-t, fsc[u], a);
+                        t = fmaf(r, inv[u], t);
+                    }
+                    return __float_as_uint(t + MAGIC);
+                };
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int c = 0; c < M; ++c) {
+                        const uint32_t b0 = biased(x[u][c].x, u), b1 = biased(x[u][c].y, u);
+                        const uint32_t b2 = biased(x[u][c].z, u), b3 = biased(x[u][c].w, u);
+                        uint32_t m = (b3 << BITS) + b2;
+                        m = (m << BITS) + b1;
+                        h[c][u] = (m << BITS) + b0 - MERGED_BIAS;
+                        if (codes_out && !(skip & (1u << u)))
+                            *reinterpret_cast<uint32_t *>(codes_out + (k0 + u) * (uint64_t)DIM + 64 * c + 4 * l) =
+                                (((((b3 << 8) + b2) << 8) + b1) << 8) + b0 - MERGED_BIAS8;
+                    }
+            };
+            if (__builtin_amdgcn_ballot_w64(my_f != 1.0f) != 0)
+                quantize_by_reciprocal(std::true_type{});
+            else
+                quantize_by_reciprocal(std::false_type{});
         }
 
         // ---- packed codes: after the quad transpose lane j owns 16 consecutive elements
         // (64c + 16q ..) of row k0 + j
         if (packed_out) {
-            const bool live = !((skip >> j) & 1u);
             uint8_t *row = packed_out + (k0 + (uint64_t)j) * P;
 #pragma unroll
             for (int c = 0; c < M; ++c) {
                 uint32_t t[4] = {h[c][0], h[c][1], h[c][2], h[c][3]};
                 quad_transpose(t, j);
                 if constexpr (BITS == 8) {
-                    if (live)
-                        *reinterpret_cast<uint4 *>(row + 64 * c + 16 * q) = make_uint4(t[0], t[1], t[2], t[3]);
+                    if (my_live) store_stream<u32x4>(row + 64 * c + 16 * q, u32x4{t[0], t[1], t[2], t[3]});
                 } else if constexpr (BITS == 4) {
-                    if (live)
-                        *reinterpret_cast<uint2 *>(row + 32 * c + 8 * q) =
-                            make_uint2(t[0] | (t[1] << 16), t[2] | (t[3] << 16));
+                    if (my_live)
+                        store_stream<u32x2>(row + 32 * c + 8 * q, u32x2{t[0] | (t[1] << 16), t[2] | (t[3] << 16)});
                 } else if constexpr (BITS == 2) {
-                    if (live)
-                        *reinterpret_cast<uint32_t *>(row + 16 * c + 4 * q) =
-                            t[0] | (t[1] << 8) | (t[2] << 16) | (t[3] << 24);
+                    if (my_live)
+                        store_stream<uint32_t>(row + 16 * c + 4 * q, t[0] | (t[1] << 8) | (t[2] << 16) | (t[3] << 24));
                 } else {  // 3 bits: 48 bits per lane; even quads append the next quad's 48 bits
                     const uint32_t w0 = t[0] | (t[1] << 12) | (t[2] << 24);  // stream bits 0..31
                     const uint32_t w1 = (t[2] >> 8) | (t[3] << 4);           // stream bits 32..47
-                    const uint32_t n0 = __shfl_down(w0, 4);
-                    const uint32_t n1 = __shfl_down(w1, 4);
-                    if (live && !(q & 1)) {
+                    const uint32_t n0 = (uint32_t)dpp_i<0x104>((int)w0);     // row_shl:4 = lane + 4
+                    const uint32_t n1 = (uint32_t)dpp_i<0x104>((int)w1);
+                    if (my_live && !(q & 1)) {
                         uint32_t *dst = reinterpret_cast<uint32_t *>(row + 24 * c + 12 * (q >> 1));
-                        dst[0] = w0;
-                        dst[1] = w1 | (n0 << 16);
-                        dst[2] = (n0 >> 16) | (n1 << 16);
+                        store_stream<uint32_t>(dst, w0);
+                        store_stream<uint32_t>(dst + 1, w1 | (n0 << 16));
+                        store_stream<uint32_t>(dst + 2, (n0 >> 16) | (n1 << 16));
                     }
                 }
             }
         }
     }
 }
+#undef CNR_SEL4
 
 // ---------------------------------------------------------------------------------------------
 // Any other dim (dim % 4 == 0, dim * bits % 8 == 0): one wavefront per row, lanes stride over the
@@ -408,10 +549,14 @@ struct QuantArgs {
 
 template <int M, int BITS, bool GREEDY>
 void launch_rows16(cnr_ctx *ctx, const QuantArgs &a, hipStream_t s) {
-    const unsigned grid = cnr_grid(ctx, a.n_max, 16u * kWavesPerBlock, 8);
-    hipLaunchKernelGGL((quantize_rows16_kernel<M, BITS, GREEDY>), dim3(grid), dim3(kBlock), 0, s, a.table,
-                       a.n_rows, a.row_ids, a.n_dev, a.n_max, a.mode, a.n_iter, a.num_bins_f, a.scale,
-                       a.bias, a.row_min, a.row_max, a.codes, a.packed, ctx->dev_err);
+    const unsigned grid = cnr_grid(ctx, a.n_max, 16u * kWavesPerBlock,
+                                   cnr_resident_blocks_per_cu<quantize_rows16_kernel<M, BITS, GREEDY>>());
+    Rows16Args k;
+    k.table = a.table; k.n_rows = a.n_rows; k.row_ids = a.row_ids; k.n_dev = a.n_dev; k.n_max = a.n_max;
+    k.mode = a.mode; k.n_iter = a.n_iter; k.num_bins_f = a.num_bins_f;
+    k.scale_out = a.scale; k.bias_out = a.bias; k.min_out = a.row_min; k.max_out = a.row_max;
+    k.codes_out = a.codes; k.packed_out = a.packed; k.err = ctx->dev_err;
+    hipLaunchKernelGGL((quantize_rows16_kernel<M, BITS, GREEDY>), dim3(grid), dim3(kBlock), 0, s, k);
 }
 
 template <int M, int BITS>

@@ -76,7 +76,7 @@ restore_rows16_kernel(float *__restrict__ table, uint64_t n_rows, const uint32_t
                 v.y = s[u] * (float)((w >> BITS) & MASK) + b[u];
                 v.z = s[u] * (float)((w >> (2 * BITS)) & MASK) + b[u];
                 v.w = s[u] * (float)((w >> (3 * BITS)) & MASK) + b[u];
-                *reinterpret_cast<float4 *>(table + dst[u] + 64 * c) = v;
+                store_stream<f32x4>(table + dst[u] + 64 * c, f32x4{v.x, v.y, v.z, v.w});
             }
         }
     }
@@ -118,20 +118,26 @@ restore_rows_generic_kernel(float *__restrict__ table, uint64_t n_rows, uint32_t
     }
 }
 
+template <int M, int BITS>
+void launch_restore16(cnr_ctx *ctx, hipStream_t st, float *table, uint64_t n_rows, const uint32_t *row_ids,
+                      const uint64_t *n_dev, uint64_t n_max, const uint8_t *packed, const float *scale,
+                      const float *bias) {
+    const unsigned grid = cnr_grid(ctx, n_max, 16u * kWavesPerBlock,
+                                   cnr_resident_blocks_per_cu<restore_rows16_kernel<M, BITS>>());
+    hipLaunchKernelGGL((restore_rows16_kernel<M, BITS>), dim3(grid), dim3(kBlock), 0, st, table, n_rows,
+                       row_ids, n_dev, n_max, packed, scale, bias, ctx->dev_err);
+}
+
 template <int BITS>
 void launch_restore(cnr_ctx *ctx, hipStream_t st, float *table, uint64_t n_rows, uint32_t dim,
                     const uint32_t *row_ids, const uint64_t *n_dev, uint64_t n_max,
                     const uint8_t *packed, const float *scale, const float *bias) {
-    const unsigned grid16 = cnr_grid(ctx, n_max, 16u * kWavesPerBlock, 8);
     if (dim == 64)
-        hipLaunchKernelGGL((restore_rows16_kernel<1, BITS>), dim3(grid16), dim3(kBlock), 0, st, table, n_rows,
-                           row_ids, n_dev, n_max, packed, scale, bias, ctx->dev_err);
+        launch_restore16<1, BITS>(ctx, st, table, n_rows, row_ids, n_dev, n_max, packed, scale, bias);
     else if (dim == 128)
-        hipLaunchKernelGGL((restore_rows16_kernel<2, BITS>), dim3(grid16), dim3(kBlock), 0, st, table, n_rows,
-                           row_ids, n_dev, n_max, packed, scale, bias, ctx->dev_err);
+        launch_restore16<2, BITS>(ctx, st, table, n_rows, row_ids, n_dev, n_max, packed, scale, bias);
     else if (dim == 256)
-        hipLaunchKernelGGL((restore_rows16_kernel<4, BITS>), dim3(grid16), dim3(kBlock), 0, st, table, n_rows,
-                           row_ids, n_dev, n_max, packed, scale, bias, ctx->dev_err);
+        launch_restore16<4, BITS>(ctx, st, table, n_rows, row_ids, n_dev, n_max, packed, scale, bias);
     else
         hipLaunchKernelGGL((restore_rows_generic_kernel<BITS>), dim3(cnr_grid(ctx, n_max, kWavesPerBlock, 8)),
                            dim3(kBlock), 0, st, table, n_rows, dim, row_ids, n_dev, n_max, packed, scale,

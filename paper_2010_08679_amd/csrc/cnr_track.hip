@@ -44,6 +44,67 @@ mark_kernel(uint32_t *__restrict__ bitmap, uint64_t n_rows, const IdxT *__restri
 }
 
 // ---------------------------------------------------------------------------------------------
+// mark, bulk variant: no atomics.
+//
+// On this GPU the L2 caches of the eight XCDs are not coherent with each other, so a device-scope
+// atomic OR is carried out at the memory side: each one costs a 64-byte read and a 32-byte write
+// there, and a few million of them dominate a checkpoint.  Plain byte stores do not have that
+// problem: different threads may write different bytes of one cache line from anywhere, and
+// writing the same value twice is harmless.  So a long index stream is first scattered into one
+// flag byte per row (scratch, all zero on entry), and a second kernel folds the flag bytes into
+// the bitmap 32 rows per thread, with plain read-modify-write because every bitmap word has exactly
+// one owner there, and zeroes the bytes it found set so that the scratch is clean again.
+// ---------------------------------------------------------------------------------------------
+template <typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+mark_flags_kernel(uint8_t *__restrict__ flags, uint64_t n_rows, const IdxT *__restrict__ idx, uint64_t n,
+                  cnr_dev_errors *err) {
+    constexpr int kUnroll = 4;
+    const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+    uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    unsigned bad = 0;
+    for (; i < n; i += stride * kUnroll) {
+        IdxT v[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const uint64_t p = i + (uint64_t)u * stride;
+            v[u] = p < n ? idx[p] : (IdxT)-1;
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const uint64_t p = i + (uint64_t)u * stride;
+            const int64_t r = (int64_t)v[u];
+            if (r >= 0 && (uint64_t)r < n_rows)
+                flags[r] = 1;
+            else if (p < n)
+                ++bad;
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) bad += __shfl_xor(bad, off);
+    if (bad && (threadIdx.x & (kWave - 1)) == 0) atomicAdd(&err->n_bad_indices, (unsigned long long)bad);
+}
+
+// Eight flag bytes (each 0 or 1) to eight bits, first byte in bit 0.
+__device__ __forceinline__ uint32_t flags_to_bits(uint64_t eight) {
+    return (uint32_t)((eight * 0x0102040810204080ull) >> 56);
+}
+
+__global__ void __launch_bounds__(kBlock)
+fold_flags_kernel(uint8_t *__restrict__ flags, uint32_t *__restrict__ bitmap, uint64_t n_words) {
+    const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+    for (uint64_t w = (uint64_t)blockIdx.x * kBlock + threadIdx.x; w < n_words; w += stride) {
+        ulonglong2 *src = reinterpret_cast<ulonglong2 *>(flags + 32u * w);
+        const ulonglong2 a = src[0], b = src[1];
+        if ((a.x | a.y | b.x | b.y) == 0) continue;
+        const uint32_t bits = flags_to_bits(a.x) | (flags_to_bits(a.y) << 8) | (flags_to_bits(b.x) << 16) |
+                              (flags_to_bits(b.y) << 24);
+        bitmap[w] |= bits;
+        src[0] = make_ulonglong2(0, 0);
+        src[1] = make_ulonglong2(0, 0);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // compact: set-bit positions in ascending order.
 //
 // Two kernels, no inter-workgroup waiting.  Each workgroup owns kBlock consecutive 64-bit bitmap
@@ -151,8 +212,10 @@ compact_scatter_kernel(const uint32_t *__restrict__ bitmap, uint64_t n_rows, uin
 
 extern "C" {
 
+size_t cnr_mark_scratch_bytes(uint64_t n_rows) { return (size_t)(cnr_bitmap_words(n_rows) * 32u); }
+
 cnr_status cnr_mark_touched(cnr_ctx *ctx, uint32_t *bitmap, uint64_t n_rows, const void *indices,
-                            uint64_t n_indices, cnr_index_type type, void *stream) {
+                            uint64_t n_indices, cnr_index_type type, void *scratch, void *stream) {
     cnr_status st = cnr_enter(ctx);
     if (st != CNR_OK) return st;
     if (type != CNR_IDX_I32 && type != CNR_IDX_I64) return CNR_E_INVALID;
@@ -160,14 +223,33 @@ cnr_status cnr_mark_touched(cnr_ctx *ctx, uint32_t *bitmap, uint64_t n_rows, con
     if (n_indices == 0) return CNR_OK;
     if (!indices || (!bitmap && n_rows)) return CNR_E_INVALID;
     const uintptr_t align = type == CNR_IDX_I64 ? 8 : 4;
-    if (((uintptr_t)indices % align) || ((uintptr_t)bitmap % 4)) return CNR_E_ALIGN;
+    if (((uintptr_t)indices % align) || ((uintptr_t)bitmap % 4) || ((uintptr_t)scratch % 16)) return CNR_E_ALIGN;
+    hipStream_t s = as_stream(stream);
+    // The flag-byte route pays a pass over n_rows bytes; below this stream length the atomics are
+    // cheaper (about 16 G atomics/s against about 5 TB/s for the fold, plus one more launch).
+    const bool bulk = scratch && n_rows && n_indices > n_rows / 256 + 65536;
     const unsigned grid = cnr_grid(ctx, n_indices, (uint64_t)kBlock * 4, 8);
+    if (bulk) {
+        uint8_t *flags = (uint8_t *)scratch;
+        if (type == CNR_IDX_I64)
+            hipLaunchKernelGGL(mark_flags_kernel<int64_t>, dim3(grid), dim3(kBlock), 0, s, flags, n_rows,
+                               (const int64_t *)indices, n_indices, ctx->dev_err);
+        else
+            hipLaunchKernelGGL(mark_flags_kernel<int32_t>, dim3(grid), dim3(kBlock), 0, s, flags, n_rows,
+                               (const int32_t *)indices, n_indices, ctx->dev_err);
+        st = cnr_launch_status(ctx);
+        if (st != CNR_OK) return st;
+        const uint64_t words = cnr_bitmap_words(n_rows);
+        hipLaunchKernelGGL(fold_flags_kernel, dim3(cnr_grid(ctx, words, kBlock, 8)), dim3(kBlock), 0, s, flags,
+                           bitmap, words);
+        return cnr_launch_status(ctx);
+    }
     if (type == CNR_IDX_I64)
-        hipLaunchKernelGGL(mark_kernel<int64_t>, dim3(grid), dim3(kBlock), 0, as_stream(stream), bitmap,
-                           n_rows, (const int64_t *)indices, n_indices, ctx->dev_err);
+        hipLaunchKernelGGL(mark_kernel<int64_t>, dim3(grid), dim3(kBlock), 0, s, bitmap, n_rows,
+                           (const int64_t *)indices, n_indices, ctx->dev_err);
     else
-        hipLaunchKernelGGL(mark_kernel<int32_t>, dim3(grid), dim3(kBlock), 0, as_stream(stream), bitmap,
-                           n_rows, (const int32_t *)indices, n_indices, ctx->dev_err);
+        hipLaunchKernelGGL(mark_kernel<int32_t>, dim3(grid), dim3(kBlock), 0, s, bitmap, n_rows,
+                           (const int32_t *)indices, n_indices, ctx->dev_err);
     return cnr_launch_status(ctx);
 }
 

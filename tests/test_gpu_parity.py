@@ -60,6 +60,32 @@ def test_mark_and_compact_bit_exact(ctx, n_rows, dtype):
     _poll_clean(ctx)
 
 
+@pytest.mark.parametrize("n_rows", [1, 33, 1000, 16385, 100_000, 1_000_003, 5_000_000])
+@pytest.mark.parametrize("dtype", [torch.int64, torch.int32])
+def test_bulk_mark_through_flag_bytes(ctx, n_rows, dtype):
+    # long streams with a scratch buffer take the flag-byte route; the bitmap must be the same, the
+    # scratch must come back zeroed, and marks must accumulate over calls and over both routes
+    print("case bulk n_rows=%d dtype=%s" % (n_rows, dtype), flush=True)
+    g = torch.Generator(device=DEV).manual_seed(n_rows + 1)
+    scratch = P.TableCheckpointer.new_mark_scratch(n_rows, DEV)
+    ck = P.TableCheckpointer(ctx, n_rows, 64, device=DEV, mark_scratch=scratch)
+    ck.clear()
+    batches = []
+    for n_idx in (300_000, 1000, 150_000):                     # bulk, atomic, bulk
+        idx = torch.randint(-2, n_rows + 2, (n_idx,), generator=g, device=DEV).to(dtype)
+        batches.append(idx)
+        ck.mark(idx)
+    ck.compact()
+    torch.cuda.synchronize()
+    bm, ids, n, skipped = _oracle_track(n_rows, [b.cpu().numpy() for b in batches])
+    assert np.array_equal(u32(ck.bitmap)[:bm.size], bm)
+    assert int(ck.n_dirty.item()) == n and np.array_equal(u32(ck.row_ids)[:n], ids)
+    assert not scratch.any()
+    st, bad, flags = P.cnr_poll_errors(ctx)
+    assert st == P.CNR_E_INDEX_RANGE and bad == skipped and flags == 0
+    _poll_clean(ctx)
+
+
 def test_mark_skips_and_counts_out_of_range(ctx):
     n_rows = 5000
     ck = P.TableCheckpointer(ctx, n_rows, 64, device=DEV)
@@ -214,7 +240,13 @@ def test_special_rows(ctx):
             ora = O.quantize_rows(rows, None, bits, mode=mode)
             for k in ("scale", "bias", "row_min", "row_max"):
                 assert np.array_equal(got[k].view(np.uint32), ora[k].view(np.uint32)), (bits, mode, k)
-            assert np.array_equal(got["codes"], ora["codes"]), (bits, mode)
+            # codes come from a reciprocal multiply on the GPU and a division in the oracle: they may
+            # differ by one step where the quotient falls within rounding distance of a half-integer
+            diff = np.abs(got["codes"].astype(np.int16) - ora["codes"].astype(np.int16))
+            assert diff.max() <= 1 and np.count_nonzero(diff) <= 2, (bits, mode, np.argwhere(diff))
+            for r, e in np.argwhere(diff):
+                t = (np.float64(rows[r, e]) - np.float64(ora["bias"][r])) / np.float64(ora["scale"][r])
+                assert abs(abs(t - np.floor(t)) - 0.5) < 1e-5, (bits, mode, r, e, t)
 
 
 @pytest.mark.parametrize("bits", (2, 3, 4))
