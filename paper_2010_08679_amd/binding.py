@@ -240,6 +240,35 @@ def cnr_poll_errors(ctx, stream=None):
     return st, int(bad.value), int(flags.value)
 
 
+def prepare(name: str, *args):
+    """A zero-argument callable that repeats one library call with fixed arguments.
+
+    ``args`` are given as for the binding function ``name`` except that every tensor is resolved to
+    its device pointer once, here, and ``stream`` (last argument, may be None = the current stream
+    at preparation time) to its handle.  The returned callable only crosses into C and checks the
+    status, so a tight loop of launches is not slowed down by per-call argument checks.  The caller
+    keeps the tensors alive and unchanged in place."""
+    fn = getattr(load(), name)
+    *body, stream = args
+    cargs = []
+    for a in body:
+        if isinstance(a, torch.Tensor):
+            if not a.is_cuda or not a.is_contiguous():
+                raise ValueError("prepared arguments must be contiguous GPU tensors")
+            cargs.append(ctypes.c_void_p(a.data_ptr()))
+        elif isinstance(a, tuple):                       # (num_bins, ratio)
+            cargs.append(ctypes.pointer(cnr_greedy_params(int(a[0]), float(a[1]))))
+        else:
+            cargs.append(a)
+    cargs.append(_stream(stream))
+
+    def call():
+        st = fn(*cargs)
+        if st != CNR_OK:
+            raise CnrError(st, name)
+    return call
+
+
 def cnr_last_hip_error(ctx) -> int:
     return int(load().cnr_last_hip_error(ctx))
 

@@ -89,3 +89,28 @@ class TableCheckpointer:
         """Writes the de-quantized rows of ``enc`` over the same rows of ``table`` in place."""
         B.cnr_restore_rows(self.ctx, table, self.n_rows, self.dim, enc.row_ids, enc.n_dev, self.capacity,
                            enc.bits, enc.packed, enc.scale, enc.bias, stream)
+
+    # -- repeated checkpoints of the same buffers ---------------------------------------------------
+    def prepare_step(self, indices: torch.Tensor, table: torch.Tensor, out: EncodedRows,
+                     restore_into: torch.Tensor | None = None, mode: int = B.CNR_RANGE_MINMAX,
+                     greedy=None, stream=None):
+        """The calls of one checkpoint of this table (clear, mark, compact, encode and, when
+        ``restore_into`` is given, restore) as a list of (label, zero-argument callable), with all
+        arguments resolved once (see :func:`binding.prepare`)."""
+        idx = indices.reshape(-1)
+        kind = B.CNR_IDX_I64 if idx.dtype == torch.int64 else B.CNR_IDX_I32
+        steps = [
+            ("clear", B.prepare("cnr_clear_bitmap", self.ctx, self.bitmap, self.n_rows, stream)),
+            ("mark", B.prepare("cnr_mark_touched", self.ctx, self.bitmap, self.n_rows, idx, idx.numel(), kind,
+                               self.mark_scratch, stream)),
+            ("compact", B.prepare("cnr_compact_dirty", self.ctx, self.bitmap, self.n_rows, self.row_ids,
+                                  self.capacity, self.n_dirty, self.scratch, stream)),
+            ("encode", B.prepare("cnr_quantize_rows", self.ctx, table, self.n_rows, self.dim, self.row_ids,
+                                 self.n_dirty, self.capacity, out.bits, mode, greedy, out.scale, out.bias,
+                                 out.row_min, out.row_max, None, out.packed, stream)),
+        ]
+        if restore_into is not None:
+            steps.append(("restore", B.prepare("cnr_restore_rows", self.ctx, restore_into, self.n_rows, self.dim,
+                                               out.row_ids, out.n_dev, self.capacity, out.bits, out.packed,
+                                               out.scale, out.bias, stream)))
+        return steps

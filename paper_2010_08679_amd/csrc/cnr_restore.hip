@@ -4,26 +4,87 @@
 
 namespace {
 
-// Bits [pos, pos + BITS*4) of a row's packed stream, pos = 4 * first_element * BITS, returned with
-// the first element's code in the low bits.  `p` points at the row's first packed byte.
-template <int BITS>
-__device__ __forceinline__ uint32_t load_four_codes(const uint8_t *__restrict__ p, uint32_t first_element) {
-    if constexpr (BITS == 8) {
-        return *reinterpret_cast<const uint32_t *>(p + first_element);
-    } else if constexpr (BITS == 4) {
-        return *reinterpret_cast<const uint16_t *>(p + first_element / 2);
-    } else if constexpr (BITS == 2) {
-        return p[first_element / 4];
-    } else {
-        const uint32_t bit = first_element * 3;  // multiple of 12: starts on a byte or a nibble
-        const uint32_t two = (uint32_t)p[bit >> 3] | ((uint32_t)p[(bit >> 3) + 1] << 8);
-        return (two >> (bit & 7u)) & 0xFFFu;
+// 4x4 transpose inside each quad of lanes: on return r[i] of quad lane j holds what r[j] of quad
+// lane i held.
+__device__ __forceinline__ void quad_transpose(uint32_t (&r)[4], int j) {
+#pragma unroll
+    for (int n = 0; n < 4; n += 2) {
+        const uint32_t send = (j & 1) ? r[n] : r[n + 1];
+        const uint32_t recv = (uint32_t)dpp_i<0xB1>((int)send);
+        if (j & 1) r[n] = recv; else r[n + 1] = recv;
+    }
+#pragma unroll
+    for (int n = 0; n < 2; ++n) {
+        const uint32_t send = (j & 2) ? r[n] : r[n + 2];
+        const uint32_t recv = (uint32_t)dpp_i<0x4E>((int)send);
+        if (j & 2) r[n] = recv; else r[n + 2] = recv;
     }
 }
 
-// Fast path, dim = 64 * M: same lane-to-element mapping as the encoder (sixteen lanes per row, lane
-// l owns elements 64c + 4l .. + 3 of every chunk c, four rows per group in flight), so the fp32
-// rows leave as 16-byte stores that cover 256 contiguous bytes per group.
+// What one group of sixteen lanes needs to restore its four rows k0 .. k0+3: ids, scales and biases
+// (the same 16 bytes for every lane of the group, one load each) and this lane's share of the packed
+// codes, fetched in the layout the encoder stored them in: quad lane j of quad q holds the codes of
+// the 16 consecutive elements 64c + 16q .. of row k0 + j (w[c][0..]: 16*BITS bits).
+template <int M, int BITS>
+struct RestoreInput {
+    uint4 ids;
+    float4 scale, bias;
+    uint32_t w[M][BITS == 8 ? 4 : BITS == 4 ? 2 : BITS == 3 ? 3 : 1];
+};
+
+template <int M, int BITS>
+__device__ __forceinline__ void fetch_restore_input(const uint32_t *__restrict__ row_ids,
+                                                    const uint8_t *__restrict__ packed,
+                                                    const float *__restrict__ scale,
+                                                    const float *__restrict__ bias, uint64_t n_max, uint64_t k0,
+                                                    int q, int j, RestoreInput<M, BITS> &in) {
+    constexpr uint64_t P = (uint64_t)(64 * M) * BITS / 8;
+    if (k0 + 3 < n_max) {  // every buffer holds n_max rows: whole 16-byte loads
+        in.ids = row_ids ? *reinterpret_cast<const uint4 *>(row_ids + k0)
+                         : make_uint4((uint32_t)k0, (uint32_t)k0 + 1, (uint32_t)k0 + 2, (uint32_t)k0 + 3);
+        in.scale = *reinterpret_cast<const float4 *>(scale + k0);
+        in.bias = *reinterpret_cast<const float4 *>(bias + k0);
+    } else {
+        uint32_t id[4] = {0, 0, 0, 0};
+        float sc[4] = {0, 0, 0, 0}, bi[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (k0 + u < n_max) {
+                id[u] = row_ids ? row_ids[k0 + u] : (uint32_t)(k0 + u);
+                sc[u] = scale[k0 + u];
+                bi[u] = bias[k0 + u];
+            }
+        in.ids = make_uint4(id[0], id[1], id[2], id[3]);
+        in.scale = make_float4(sc[0], sc[1], sc[2], sc[3]);
+        in.bias = make_float4(bi[0], bi[1], bi[2], bi[3]);
+    }
+    const bool row_in_buffer = k0 + (uint64_t)j < n_max;
+    const uint8_t *row = packed + (k0 + (uint64_t)j) * P;
+#pragma unroll
+    for (int c = 0; c < M; ++c) {
+        if constexpr (BITS == 8) {
+            const u32x4 v = row_in_buffer ? load_stream<u32x4>(row + 64 * c + 16 * q) : u32x4{0, 0, 0, 0};
+            in.w[c][0] = v.x; in.w[c][1] = v.y; in.w[c][2] = v.z; in.w[c][3] = v.w;
+        } else if constexpr (BITS == 4) {
+            const u32x2 v = row_in_buffer ? load_stream<u32x2>(row + 32 * c + 8 * q) : u32x2{0, 0};
+            in.w[c][0] = v.x; in.w[c][1] = v.y;
+        } else if constexpr (BITS == 2) {
+            in.w[c][0] = row_in_buffer ? load_stream<uint32_t>(row + 16 * c + 4 * q) : 0u;
+        } else {  // 3 bits: even quads fetch 12 bytes = their own 48 bits and the next quad's
+            const uint32_t *src = reinterpret_cast<const uint32_t *>(row + 24 * c + 12 * (q >> 1));
+            const bool fetch = row_in_buffer && !(q & 1);
+            in.w[c][0] = fetch ? load_stream<uint32_t>(src) : 0u;
+            in.w[c][1] = fetch ? load_stream<uint32_t>(src + 1) : 0u;
+            in.w[c][2] = fetch ? load_stream<uint32_t>(src + 2) : 0u;
+        }
+    }
+}
+
+// Fast path, dim = 64 * M: the mirror image of the encoder.  Sixteen lanes share a row, four rows
+// per group; packed codes arrive as whole words per lane and a 4x4 transpose inside each quad turns
+// them into "lane l owns elements 64c + 4l .. + 3 of each of the four rows", so the fp32 rows leave
+// as 16-byte streaming stores that cover 256 contiguous bytes per row.  The input of the next batch
+// is requested before the current batch is de-quantized and stored.
 template <int M, int BITS>
 __global__ void __launch_bounds__(kBlock)
 restore_rows16_kernel(float *__restrict__ table, uint64_t n_rows, const uint32_t *__restrict__ row_ids,
@@ -31,7 +92,6 @@ restore_rows16_kernel(float *__restrict__ table, uint64_t n_rows, const uint32_t
                       const uint8_t *__restrict__ packed, const float *__restrict__ scale,
                       const float *__restrict__ bias, cnr_dev_errors *err) {
     constexpr int DIM = 64 * M;
-    constexpr uint64_t P = (uint64_t)DIM * BITS / 8;
     constexpr uint32_t MASK = (1u << BITS) - 1u;
     uint64_t n = n_max;
     if (n_dev) {
@@ -41,44 +101,65 @@ restore_rows16_kernel(float *__restrict__ table, uint64_t n_rows, const uint32_t
     const int lane = threadIdx.x & (kWave - 1);
     const int g = lane >> 4;
     const int l = lane & 15;
+    const int q = l >> 2;
+    const int j = l & 3;
     const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
-    const uint64_t wave_id = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
-    for (uint64_t batch = wave_id; batch * 16u < n; batch += n_waves) {
+    uint64_t batch = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    if (batch * 16u >= n) return;
+    RestoreInput<M, BITS> cur, nxt;
+    fetch_restore_input<M, BITS>(row_ids, packed, scale, bias, n_max, batch * 16u + 4u * (uint64_t)g, q, j, cur);
+    for (;;) {
+        const uint64_t next = batch + n_waves;
+        const bool has_next = next * 16u < n;  // uniform over the wave
+        if (has_next)
+            fetch_restore_input<M, BITS>(row_ids, packed, scale, bias, n_max, next * 16u + 4u * (uint64_t)g, q, j, nxt);
+
         const uint64_t k0 = batch * 16u + 4u * (uint64_t)g;
-        uint32_t h[4][M];
-        float s[4], b[4];
-        uint64_t dst[4];
-        bool live[4];
+        const uint32_t rid[4] = {cur.ids.x, cur.ids.y, cur.ids.z, cur.ids.w};
+        const float s[4] = {cur.scale.x, cur.scale.y, cur.scale.z, cur.scale.w};
+        const float b[4] = {cur.bias.x, cur.bias.y, cur.bias.z, cur.bias.w};
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            uint64_t k = k0 + u;
-            live[u] = k < n;
-            if (!live[u]) k = n - 1;
-            const uint64_t r = row_ids ? (uint64_t)row_ids[k] : k;
-            if (r >= n_rows) {
-                if (live[u] && l == 0) raise_flag(err, CNR_FLAG_ROW_ID);
-                live[u] = false;
+        for (int c = 0; c < M; ++c) {
+            // t[i] = 4*BITS code bits of elements 64c + 16q + 4i .. + 3 of row k0 + j
+            uint32_t t[4];
+            if constexpr (BITS == 8) {
+                t[0] = cur.w[c][0]; t[1] = cur.w[c][1]; t[2] = cur.w[c][2]; t[3] = cur.w[c][3];
+            } else if constexpr (BITS == 4) {
+                t[0] = cur.w[c][0] & 0xFFFFu; t[1] = cur.w[c][0] >> 16;
+                t[2] = cur.w[c][1] & 0xFFFFu; t[3] = cur.w[c][1] >> 16;
+            } else if constexpr (BITS == 2) {
+                t[0] = cur.w[c][0] & 0xFFu; t[1] = (cur.w[c][0] >> 8) & 0xFFu;
+                t[2] = (cur.w[c][0] >> 16) & 0xFFu; t[3] = cur.w[c][0] >> 24;
+            } else {
+                // odd quads take bits 48..95 of the 96 their left neighbour quad fetched
+                const uint32_t p1 = (uint32_t)dpp_i<0x114>((int)cur.w[c][1]);  // row_shr:4 = lane - 4
+                const uint32_t p2 = (uint32_t)dpp_i<0x114>((int)cur.w[c][2]);
+                const uint32_t lo32 = (q & 1) ? ((p1 >> 16) | (p2 << 16)) : cur.w[c][0];
+                const uint32_t hi16 = (q & 1) ? (p2 >> 16) : (cur.w[c][1] & 0xFFFFu);
+                t[0] = lo32 & 0xFFFu; t[1] = (lo32 >> 12) & 0xFFFu;
+                t[2] = (lo32 >> 24) | ((hi16 & 0xFu) << 8); t[3] = hi16 >> 4;
             }
-            dst[u] = r * (uint64_t)DIM + 4u * (uint64_t)l;
-            s[u] = scale[k];
-            b[u] = bias[k];
+            quad_transpose(t, j);  // now t[u] = codes of elements 64c + 4l .. + 3 of row k0 + u
 #pragma unroll
-            for (int c = 0; c < M; ++c) h[u][c] = load_four_codes<BITS>(packed + k * P, 64 * c + 4 * l);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (!live[u]) continue;
-#pragma unroll
-            for (int c = 0; c < M; ++c) {
-                const uint32_t w = h[u][c];
-                float4 v;
+            for (int u = 0; u < 4; ++u) {
+                const bool live = k0 + u < n && rid[u] < n_rows;
+                if (!live) continue;
+                const uint32_t w = t[u];
+                f32x4 v;
                 v.x = s[u] * (float)(w & MASK) + b[u];
                 v.y = s[u] * (float)((w >> BITS) & MASK) + b[u];
                 v.z = s[u] * (float)((w >> (2 * BITS)) & MASK) + b[u];
                 v.w = s[u] * (float)((w >> (3 * BITS)) & MASK) + b[u];
-                store_stream<f32x4>(table + dst[u] + 64 * c, f32x4{v.x, v.y, v.z, v.w});
+                store_stream<f32x4>(table + (uint64_t)rid[u] * DIM + 64 * c + 4 * l, v);
             }
         }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (k0 + u < n && rid[u] >= n_rows && l == 0) raise_flag(err, CNR_FLAG_ROW_ID);
+
+        if (!has_next) break;
+        cur = nxt;
+        batch = next;
     }
 }
 
