@@ -229,58 +229,89 @@ __device__ __forceinline__ void encode_batch(const Rows16Args &a, uint64_t k0, c
         }
 
         // ---- greedy range search (Approach 3): shrink from whichever side hurts less, remember
-        // the best range seen
+        // the best range seen.  This loop is bound by vector-ALU issue, so a candidate's error is
+        // evaluated with the cheapest sequence that still reproduces F_Q's codes: the scale
+        // (range / (2^b - 1)) and the quotient (x - lo) / scale are formed by a reciprocal multiply
+        // followed by one FMA residual correction (q' = q + (a - q*b) * (1/b)), which yields the
+        // correctly rounded quotient except in cases far too rare to matter for ranking candidates.
+        // A wave holding a row whose scale lies outside [2^-100, 2^100] divides instead.
         if constexpr (GREEDY) {
-            float cur_lo[4], cur_hi[4], step[4];
-            double best[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                cur_lo[u] = lo[u];
-                cur_hi[u] = hi[u];
-                step[u] = (hi[u] - lo[u]) / num_bins_f;
-                const float s0 = (hi[u] - lo[u]) / QMAXF;
-                double e = 0.0;
-#pragma unroll
-                for (int c = 0; c < M; ++c) {
-                    e += fq_sq_err(x[u][c].x, lo[u], hi[u], s0, QMAXF);
-                    e += fq_sq_err(x[u][c].y, lo[u], hi[u], s0, QMAXF);
-                    e += fq_sq_err(x[u][c].z, lo[u], hi[u], s0, QMAXF);
-                    e += fq_sq_err(x[u][c].w, lo[u], hi[u], s0, QMAXF);
-                }
-                best[u] = row16_sum(e);
-            }
-            for (uint32_t it = 0; it < n_iter; ++it) {
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const float c_lo = cur_lo[u] + step[u];
-                    const float c_hi = cur_hi[u] - step[u];
-                    const float s_lo = (cur_hi[u] - c_lo) / QMAXF;
-                    const float s_hi = (c_hi - cur_lo[u]) / QMAXF;
-                    double e_lo = 0.0, e_hi = 0.0;
+            constexpr float INV_QMAX = 1.0f / QMAXF;
+            auto search = [&](auto fast_tag) {
+                constexpr bool FAST = decltype(fast_tag)::value;
+                // squared error of one element under F_Q(., c_lo, c_hi) added to acc
+                auto add_err = [&](double acc, float xv, float c_lo, float c_hi, float s, float inv) -> double {
+                    if constexpr (FAST) {
+                        const float c = __builtin_amdgcn_fmed3f(xv, c_lo, c_hi);
+                        const float a = c - c_lo;
+                        float t = a * inv;
+                        t = fmaf(fmaf(-t, s, a), inv, t);
+                        const float d = xv - fq_value(rintf(t), s, c_lo);
+                        return fma((double)d, (double)d, acc);  // d*d is exact in fp64: same as mul, add
+                    } else {
+                        return acc + fq_sq_err(xv, c_lo, c_hi, s, QMAXF);
+                    }
+                };
+                auto row_err = [&](int u, float c_lo, float c_hi) -> double {
+                    const float range = c_hi - c_lo;
+                    float s, inv = 0.0f;
+                    if constexpr (FAST) {
+                        const float q0 = range * INV_QMAX;
+                        s = fmaf(fmaf(-q0, QMAXF, range), INV_QMAX, q0);
+                        const float r0 = __builtin_amdgcn_rcpf(s);
+                        inv = s == 0.0f ? 0.0f : fmaf(fmaf(-s, r0, 1.0f), r0, r0);
+                    } else {
+                        s = range / QMAXF;
+                    }
+                    double e = 0.0;
 #pragma unroll
                     for (int c = 0; c < M; ++c) {
-                        e_lo += fq_sq_err(x[u][c].x, c_lo, cur_hi[u], s_lo, QMAXF);
-                        e_lo += fq_sq_err(x[u][c].y, c_lo, cur_hi[u], s_lo, QMAXF);
-                        e_lo += fq_sq_err(x[u][c].z, c_lo, cur_hi[u], s_lo, QMAXF);
-                        e_lo += fq_sq_err(x[u][c].w, c_lo, cur_hi[u], s_lo, QMAXF);
-                        e_hi += fq_sq_err(x[u][c].x, cur_lo[u], c_hi, s_hi, QMAXF);
-                        e_hi += fq_sq_err(x[u][c].y, cur_lo[u], c_hi, s_hi, QMAXF);
-                        e_hi += fq_sq_err(x[u][c].z, cur_lo[u], c_hi, s_hi, QMAXF);
-                        e_hi += fq_sq_err(x[u][c].w, cur_lo[u], c_hi, s_hi, QMAXF);
+                        e = add_err(e, x[u][c].x, c_lo, c_hi, s, inv);
+                        e = add_err(e, x[u][c].y, c_lo, c_hi, s, inv);
+                        e = add_err(e, x[u][c].z, c_lo, c_hi, s, inv);
+                        e = add_err(e, x[u][c].w, c_lo, c_hi, s, inv);
                     }
-                    e_lo = row16_sum(e_lo);
-                    e_hi = row16_sum(e_hi);
-                    const bool move_lo = e_lo < e_hi;
-                    cur_lo[u] = move_lo ? c_lo : cur_lo[u];
-                    cur_hi[u] = move_lo ? cur_hi[u] : c_hi;
-                    const double e = move_lo ? e_lo : e_hi;
-                    if (e < best[u]) {
-                        best[u] = e;
-                        lo[u] = cur_lo[u];
-                        hi[u] = cur_hi[u];
+                    return row16_sum(e);
+                };
+                float cur_lo[4], cur_hi[4], step[4];
+                double best[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    cur_lo[u] = lo[u];
+                    cur_hi[u] = hi[u];
+                    step[u] = (hi[u] - lo[u]) / num_bins_f;
+                    best[u] = row_err(u, lo[u], hi[u]);
+                }
+                for (uint32_t it = 0; it < n_iter; ++it) {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const float c_lo = cur_lo[u] + step[u];
+                        const float c_hi = cur_hi[u] - step[u];
+                        const double e_lo = row_err(u, c_lo, cur_hi[u]);
+                        const double e_hi = row_err(u, cur_lo[u], c_hi);
+                        const bool move_lo = e_lo < e_hi;
+                        cur_lo[u] = move_lo ? c_lo : cur_lo[u];
+                        cur_hi[u] = move_lo ? cur_hi[u] : c_hi;
+                        const double e = move_lo ? e_lo : e_hi;
+                        if (e < best[u]) {
+                            best[u] = e;
+                            lo[u] = cur_lo[u];
+                            hi[u] = cur_hi[u];
+                        }
                     }
                 }
+            };
+            bool odd_scale = false;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float s0 = (hi[u] - lo[u]) * INV_QMAX;
+                odd_scale |= s0 != 0.0f && !(s0 >= 0x1p-100f && s0 <= 0x1p100f);
             }
+            // the last candidates are up to num_bins times narrower than the first
+            if (__builtin_amdgcn_ballot_w64(odd_scale) != 0 || num_bins_f > 0x1p20f)
+                search(std::false_type{});
+            else
+                search(std::true_type{});
         }
 
         // ---- per-row parameters, computed by the quad lane that owns the row (lane j <-> row k0+j)
