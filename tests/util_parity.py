@@ -75,6 +75,9 @@ def compare_quantized(host_rows: np.ndarray, gpu: dict, ora: dict, bits: int, *,
     if greedy:
         rel = rel[same_range]
     assert rel.max(initial=0) <= L2_REL_TOL, "%s: per-row l2 error off by %.3g relative" % (what, rel.max())
+    print("%s: %d rows x %d, codes differing %.2e, rows off the oracle's greedy path %d, "
+          "max relative l2-error difference %.1e" % (what, n, dim, frac, int((~same_range).sum()),
+                                                     rel.max(initial=0)), flush=True)
     return frac
 
 
