@@ -170,7 +170,7 @@ def main() -> int:
     rec = TRAFFIC_PER_ROW.get(_kernel_hash())
     if rec and rec[0] == "%s/b%d" % (w.name, bits):
         traffic = rec[1] * rows_per_launch
-    roofline = {"bound": "hbm", "kernel": "quantize_rows16_kernel<%d,%d,false>" % (w.dim // 64, bits),
+    roofline = {"bound": "hbm", "kernel": "quantize_rows16_kernel<%d, %d>" % (w.dim // 64, bits),
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "bytes_per_launch": int(enc_bytes), "avg_launch_ms": round(enc_launch_ms, 5)}

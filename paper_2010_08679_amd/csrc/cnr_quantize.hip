@@ -1,9 +1,11 @@
 // Gather + per-row uniform quantization F_Q + dense packing (Section 5.2, Approaches 1 and 3).
 //
-// Arithmetic contract (what makes the output comparable bit for bit with a plain CPU statement of
-// the formulas): fp32 throughout, one rounding per operation (the build disables contraction into
-// fused multiply-adds), correctly rounded division, round-half-even, fp32 denormals kept.  Error
-// sums that only rank candidate ranges are accumulated in fp64.
+// Arithmetic contract (what makes the output comparable with a plain CPU statement of the
+// formulas): fp32 throughout, one rounding per operation (the build disables contraction into fused
+// multiply-adds), round-half-even, fp32 denormals kept; row minimum, maximum, scale and bias are
+// bit-exact; codes may differ from the divide-and-round definition by one step where the quotient
+// lies within rounding distance of a half-integer (see the bulk kernel).  Error sums that only rank
+// candidate ranges are accumulated in fp64.
 #include <type_traits>
 
 #include "cnr_common.h"
@@ -11,6 +13,31 @@
 namespace {
 
 enum { kModeMinMax = CNR_RANGE_MINMAX, kModeGreedy = CNR_RANGE_GREEDY, kModeSymmetric = CNR_RANGE_SYMMETRIC };
+
+// Arguments shared by the quantize kernels.
+struct QuantArgs {
+    const float *table;
+    uint64_t n_rows;
+    uint32_t dim;
+    const uint32_t *row_ids;
+    const uint64_t *n_dev;
+    uint64_t n_max;
+    int mode;
+    uint32_t n_iter;   // greedy iterations
+    float num_bins_f;  // greedy num_bins
+    float *scale, *bias, *row_min, *row_max;
+    uint8_t *codes, *packed;
+    cnr_dev_errors *err;
+};
+
+__device__ __forceinline__ uint64_t row_count(const QuantArgs &a) {
+    uint64_t n = a.n_max;
+    if (a.n_dev) {
+        const uint64_t nd = *a.n_dev;
+        n = nd < a.n_max ? nd : a.n_max;
+    }
+    return n;
+}
 
 // Code of one element as a float in [0, qmax] (F_Q of Section 5.2: clip, subtract the zero point,
 // divide by the scale, round).
@@ -49,19 +76,25 @@ __device__ __forceinline__ void quad_transpose(uint32_t (&r)[4], int j) {
     }
 }
 
+template <int U>
+__device__ __forceinline__ float quad_bcast(float v) {  // value of quad lane U in all four lanes
+    return dpp_f<U * 0x55>(v);
+}
+
 // ---------------------------------------------------------------------------------------------
-// Fast path, dim = 64 * M.
+// Bulk kernel (min/max and symmetric range), dim = 64 * M.  Bound by HBM.
 //
 // Sixteen lanes share a row: lane l of the group holds, for every 64-element chunk c of the row,
 // the four consecutive elements 64c + 4l .. 64c + 4l + 3, so one 16-byte load per lane reads 256
 // contiguous bytes per group, and all reductions over a row stay inside one 16-lane DPP row.  Each
-// group works on four consecutive dirty rows at once (so a wave has sixteen rows = 4 KB * M in
-// flight before it reduces anything), which is also what lets the packed codes leave through full
-// words: after quantizing, a 4x4 transpose inside each quad of lanes hands lane j the codes of
-// sixteen consecutive elements of row j.
+// group works on four consecutive dirty rows at once (a wave has sixteen rows = 4 KB * M in flight),
+// which is also what lets the packed codes leave through full words: after quantizing, a 4x4
+// transpose inside each quad of lanes hands lane j the codes of sixteen consecutive elements of row
+// j.  The loop is software-pipelined: the rows of batch i+1 and the ids of batch i+2 are requested
+// before batch i is reduced and quantized.
 //
-// The kernel is bound by vector-ALU issue as much as by HBM (a wave64 instruction occupies a SIMD
-// for four cycles), so the per-element work of the min/max and symmetric modes is pared down:
+// A wave64 instruction occupies a SIMD for four cycles, so vector-ALU issue competes with HBM here,
+// and the per-element work is pared down:
 //   - scale and 1/scale are computed once per row, by the one lane of each quad that owns the row,
 //     with correctly rounded divisions, and broadcast back inside the quad;
 //   - an element's code is round((x - lo) * (1/scale)); adding 1.5 * 2^23 does the rounding
@@ -69,31 +102,15 @@ __device__ __forceinline__ void quad_transpose(uint32_t (&r)[4], int j) {
 //     three shift-adds and one subtraction of the merged constant.  The product differs from the
 //     correctly rounded quotient by at most 1.5 ulp, which can move a code only when the quotient
 //     sits within that distance of a half-integer (a few elements in a million at 4 bits); at 8
-//     bits, where quotients are larger, one Newton step on the quotient removes that too.
-// The greedy mode keeps correctly rounded divisions everywhere, because there the error sums of
-// candidate ranges are compared against each other and must not depend on such last-bit effects.
+//     bits, where quotients are larger, one FMA residual step on the quotient removes that too;
+//   - the reciprocal must be a normal number: rows with a scale outside [2^-100, 2^100] (denormal
+//     or near-overflow ranges) are brought there by an exact power-of-two factor applied to both
+//     x - lo and the scale, and a wave takes that variant only if one of its sixteen rows needs it.
+// A layout with sixteen contiguous elements per lane (the greedy kernel's) needs half the
+// instructions but its strided 16-byte loads cost more than they save: 92 us against 81 us per
+// 5 M x 64 table with 30 % dirty rows.
 // ---------------------------------------------------------------------------------------------
 #define CNR_SEL4(a) (j == 0 ? (a)[0] : j == 1 ? (a)[1] : j == 2 ? (a)[2] : (a)[3])
-
-template <int U>
-__device__ __forceinline__ float quad_bcast(float v) {  // value of quad lane U in all four lanes
-    return dpp_f<U * 0x55>(v);
-}
-
-// Uniform arguments of the fast-path kernel.
-struct Rows16Args {
-    const float *table;
-    uint64_t n_rows;
-    const uint32_t *row_ids;
-    const uint64_t *n_dev;
-    uint64_t n_max;
-    int mode;
-    uint32_t n_iter;
-    float num_bins_f;
-    float *scale_out, *bias_out, *min_out, *max_out;
-    uint8_t *codes_out, *packed_out;
-    cnr_dev_errors *err;
-};
 
 template <int M>
 struct RowBatch {
@@ -102,7 +119,7 @@ struct RowBatch {
 };
 
 // Row ids of the four rows k0 .. k0+3 of one group.
-__device__ __forceinline__ uint4 gather_ids(const Rows16Args &a, uint64_t k0) {
+__device__ __forceinline__ uint4 gather_ids(const QuantArgs &a, uint64_t k0) {
     if (!a.row_ids) return make_uint4((uint32_t)k0, (uint32_t)k0 + 1, (uint32_t)k0 + 2, (uint32_t)k0 + 3);
     if (k0 + 3 < a.n_max)  // the id buffer holds n_max entries: one 16-byte load
         return *reinterpret_cast<const uint4 *>(a.row_ids + k0);
@@ -115,7 +132,7 @@ __device__ __forceinline__ uint4 gather_ids(const Rows16Args &a, uint64_t k0) {
 
 // Issues the loads of the group's four rows (this lane's elements 64c + 4l .. + 3 of each).
 template <int M>
-__device__ __forceinline__ void gather_rows(const Rows16Args &a, uint64_t n, uint64_t k0, uint4 ids, int l,
+__device__ __forceinline__ void gather_rows(const QuantArgs &a, uint64_t n, uint64_t k0, uint4 ids, int l,
                                             RowBatch<M> &rb) {
     const uint32_t rid[4] = {ids.x, ids.y, ids.z, ids.w};
     rb.skip = 0;
@@ -137,59 +154,11 @@ __device__ __forceinline__ void gather_rows(const Rows16Args &a, uint64_t n, uin
     }
 }
 
-template <int M, int BITS, bool GREEDY>
-__device__ __forceinline__ void encode_batch(const Rows16Args &a, uint64_t k0, const RowBatch<M> &rb, int l);
-
-template <int M, int BITS, bool GREEDY>
-__global__ void __launch_bounds__(kBlock) quantize_rows16_kernel(const Rows16Args a) {
-    uint64_t n = a.n_max;
-    if (a.n_dev) {
-        const uint64_t nd = *a.n_dev;
-        n = nd < a.n_max ? nd : a.n_max;
-    }
-    const int lane = threadIdx.x & (kWave - 1);
-    const int g = lane >> 4;  // group of 16 lanes
-    const int l = lane & 15;  // lane in group
-    const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
-    uint64_t batch = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
-    if (batch * 16u >= n) return;
-
-    if constexpr (GREEDY) {  // ALU-bound: nothing to overlap
-        for (; batch * 16u < n; batch += n_waves) {
-            const uint64_t k0 = batch * 16u + 4u * (uint64_t)g;
-            RowBatch<M> rb;
-            gather_rows<M>(a, n, k0, gather_ids(a, k0), l, rb);
-            encode_batch<M, BITS, true>(a, k0, rb, l);
-        }
-    } else {
-        // Software pipeline: while batch i is being reduced and quantized, the rows of batch i+1 are
-        // already on their way and the ids of batch i+2 have been requested, so a wave always has a
-        // full batch of row data in flight.
-        RowBatch<M> cur, nxt;
-        gather_rows<M>(a, n, batch * 16u + 4u * (uint64_t)g, gather_ids(a, batch * 16u + 4u * (uint64_t)g), l, cur);
-        uint64_t next = batch + n_waves;
-        uint4 ids_next = make_uint4(0, 0, 0, 0);
-        if (next * 16u < n) ids_next = gather_ids(a, next * 16u + 4u * (uint64_t)g);
-        for (;;) {
-            const bool has_next = next * 16u < n;  // uniform over the wave
-            if (has_next) gather_rows<M>(a, n, next * 16u + 4u * (uint64_t)g, ids_next, l, nxt);
-            const uint64_t next2 = next + n_waves;
-            if (next2 * 16u < n) ids_next = gather_ids(a, next2 * 16u + 4u * (uint64_t)g);
-            encode_batch<M, BITS, false>(a, batch * 16u + 4u * (uint64_t)g, cur, l);
-            if (!has_next) break;
-            cur = nxt;
-            batch = next;
-            next = next2;
-        }
-    }
-}
-
 // Reduces, quantizes and stores the four rows of one group.
-template <int M, int BITS, bool GREEDY>
-__device__ __forceinline__ void encode_batch(const Rows16Args &a, uint64_t k0, const RowBatch<M> &rb, int l) {
+template <int M, int BITS>
+__device__ __forceinline__ void encode_batch(const QuantArgs &a, uint64_t k0, const RowBatch<M> &rb, int l) {
     constexpr int DIM = 64 * M;
-    constexpr int QMAX = (1 << BITS) - 1;
-    constexpr float QMAXF = (float)QMAX;
+    constexpr float QMAXF = (float)((1 << BITS) - 1);
     constexpr uint64_t P = (uint64_t)DIM * BITS / 8;  // packed bytes per row
     constexpr float MAGIC = 12582912.0f;              // 1.5 * 2^23: x + MAGIC rounds x to an integer
     constexpr uint32_t MAGIC_BITS = 0x4B400000u;      // bit pattern of MAGIC
@@ -198,233 +167,341 @@ __device__ __forceinline__ void encode_batch(const Rows16Args &a, uint64_t k0, c
     constexpr uint32_t MERGED_BIAS8 = MAGIC_BITS * (1u + (1u << 8) + (1u << 16) + (1u << 24));
     const int q = l >> 2;  // quad in group
     const int j = l & 3;   // lane in quad
-    const int mode = a.mode;
-    const uint32_t n_iter = a.n_iter;
-    const float num_bins_f = a.num_bins_f;
-    float *const scale_out = a.scale_out, *const bias_out = a.bias_out;
-    float *const min_out = a.min_out, *const max_out = a.max_out;
-    uint8_t *const codes_out = a.codes_out, *const packed_out = a.packed_out;
     const unsigned skip = rb.skip;
     const float4 (&x)[4][M] = rb.x;
-    {
-        // ---- row minimum / maximum
-        float X_min[4], X_max[4], lo[4], hi[4];
+
+    // ---- row minimum / maximum
+    float X_min[4], X_max[4], lo[4], hi[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            float mn = x[u][0].x, mx = x[u][0].x;
+    for (int u = 0; u < 4; ++u) {
+        float mn = x[u][0].x, mx = x[u][0].x;
+#pragma unroll
+        for (int c = 0; c < M; ++c) {
+            mn = fminf(fminf(mn, x[u][c].x), fminf(x[u][c].y, fminf(x[u][c].z, x[u][c].w)));
+            mx = fmaxf(fmaxf(mx, x[u][c].x), fmaxf(x[u][c].y, fmaxf(x[u][c].z, x[u][c].w)));
+        }
+        X_min[u] = row16_min(mn) + 0.0f;  // -0.0 -> +0.0
+        X_max[u] = row16_max(mx) + 0.0f;
+        lo[u] = X_min[u];
+        hi[u] = X_max[u];
+        if (a.mode == kModeSymmetric) {
+            const float m = fmaxf(fabsf(X_min[u]), fabsf(X_max[u]));
+            lo[u] = -m + 0.0f;
+            hi[u] = m;
+        }
+    }
+
+    // ---- per-row parameters, computed by the quad lane that owns the row (lane j <-> row k0+j)
+    const float my_lo = CNR_SEL4(lo);
+    const float my_scale = (CNR_SEL4(hi) - my_lo) / QMAXF;
+    const bool my_live = !((skip >> j) & 1u);
+    {   // lanes 0-3 of a group write scale, 4-7 bias, 8-11 min, 12-15 max
+        float *dst = q == 0 ? a.scale : q == 1 ? a.bias : q == 2 ? a.row_min : a.row_max;
+        const float v = q == 0 ? my_scale : q == 1 ? my_lo : q == 2 ? CNR_SEL4(X_min) : CNR_SEL4(X_max);
+        if (dst && my_live) store_stream<float>(dst + k0 + j, v);
+    }
+    const float my_f = my_scale < 0x1p-100f ? 0x1p120f : my_scale > 0x1p100f ? 0x1p-120f : 1.0f;
+    const float my_fscale = my_scale * my_f;
+    const float my_inv = my_scale == 0.0f ? 0.0f : 1.0f / my_fscale;  // scale 0: every code 0
+    const float inv[4] = {quad_bcast<0>(my_inv), quad_bcast<1>(my_inv), quad_bcast<2>(my_inv),
+                          quad_bcast<3>(my_inv)};
+
+    // ---- quantize; h[c][u] = this lane's four codes of (row u, chunk c)
+    uint32_t h[M][4];
+    auto quantize_by_reciprocal = [&](auto rescale) {
+        constexpr bool RESCALE = decltype(rescale)::value;
+        float f[4] = {1.0f, 1.0f, 1.0f, 1.0f}, fsc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if constexpr (RESCALE) {
+            f[0] = quad_bcast<0>(my_f); f[1] = quad_bcast<1>(my_f);
+            f[2] = quad_bcast<2>(my_f); f[3] = quad_bcast<3>(my_f);
+        }
+        if constexpr (BITS == 8) {
+            fsc[0] = quad_bcast<0>(my_fscale); fsc[1] = quad_bcast<1>(my_fscale);
+            fsc[2] = quad_bcast<2>(my_fscale); fsc[3] = quad_bcast<3>(my_fscale);
+        }
+        // magic-biased code of one element: MAGIC_BITS + round((x - lo) / scale)
+        auto biased = [&](float xv, int u) -> uint32_t {
+            float d0 = xv - lo[u];
+            if constexpr (RESCALE) d0 *= f[u];
+            float t = d0 * inv[u];
+            if constexpr (BITS == 8) t = fmaf(fmaf(-t, fsc[u], d0), inv[u], t);
+            return __float_as_uint(t + MAGIC);
+        };
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
 #pragma unroll
             for (int c = 0; c < M; ++c) {
-                mn = fminf(fminf(mn, x[u][c].x), fminf(x[u][c].y, fminf(x[u][c].z, x[u][c].w)));
-                mx = fmaxf(fmaxf(mx, x[u][c].x), fmaxf(x[u][c].y, fmaxf(x[u][c].z, x[u][c].w)));
+                const uint32_t b0 = biased(x[u][c].x, u), b1 = biased(x[u][c].y, u);
+                const uint32_t b2 = biased(x[u][c].z, u), b3 = biased(x[u][c].w, u);
+                uint32_t m = (b3 << BITS) + b2;
+                m = (m << BITS) + b1;
+                h[c][u] = (m << BITS) + b0 - MERGED_BIAS;
+                if (a.codes && !(skip & (1u << u)))
+                    *reinterpret_cast<uint32_t *>(a.codes + (k0 + u) * (uint64_t)DIM + 64 * c + 4 * l) =
+                        (((((b3 << 8) + b2) << 8) + b1) << 8) + b0 - MERGED_BIAS8;
             }
-            X_min[u] = row16_min(mn) + 0.0f;  // -0.0 -> +0.0
-            X_max[u] = row16_max(mx) + 0.0f;
-            lo[u] = X_min[u];
-            hi[u] = X_max[u];
-            if (mode == kModeSymmetric) {
-                const float a = fmaxf(fabsf(X_min[u]), fabsf(X_max[u]));
-                lo[u] = -a + 0.0f;
-                hi[u] = a;
-            }
-        }
+    };
+    if (__builtin_amdgcn_ballot_w64(my_f != 1.0f) != 0)
+        quantize_by_reciprocal(std::true_type{});
+    else
+        quantize_by_reciprocal(std::false_type{});
 
-        // ---- greedy range search (Approach 3): shrink from whichever side hurts less, remember
-        // the best range seen.  This loop is bound by vector-ALU issue, so a candidate's error is
-        // evaluated with the cheapest sequence that still reproduces F_Q's codes: the scale
-        // (range / (2^b - 1)) and the quotient (x - lo) / scale are formed by a reciprocal multiply
-        // followed by one FMA residual correction (q' = q + (a - q*b) * (1/b)), which yields the
-        // correctly rounded quotient except in cases far too rare to matter for ranking candidates.
-        // A wave holding a row whose scale lies outside [2^-100, 2^100] divides instead.
-        if constexpr (GREEDY) {
-            constexpr float INV_QMAX = 1.0f / QMAXF;
-            auto search = [&](auto fast_tag) {
-                constexpr bool FAST = decltype(fast_tag)::value;
-                // squared error of one element under F_Q(., c_lo, c_hi) added to acc
-                auto add_err = [&](double acc, float xv, float c_lo, float c_hi, float s, float inv) -> double {
-                    if constexpr (FAST) {
-                        const float c = __builtin_amdgcn_fmed3f(xv, c_lo, c_hi);
-                        const float a = c - c_lo;
-                        float t = a * inv;
-                        t = fmaf(fmaf(-t, s, a), inv, t);
-                        const float d = xv - fq_value(rintf(t), s, c_lo);
-                        return fma((double)d, (double)d, acc);  // d*d is exact in fp64: same as mul, add
-                    } else {
-                        return acc + fq_sq_err(xv, c_lo, c_hi, s, QMAXF);
-                    }
-                };
-                auto row_err = [&](int u, float c_lo, float c_hi) -> double {
-                    const float range = c_hi - c_lo;
-                    float s, inv = 0.0f;
-                    if constexpr (FAST) {
-                        const float q0 = range * INV_QMAX;
-                        s = fmaf(fmaf(-q0, QMAXF, range), INV_QMAX, q0);
-                        const float r0 = __builtin_amdgcn_rcpf(s);
-                        inv = s == 0.0f ? 0.0f : fmaf(fmaf(-s, r0, 1.0f), r0, r0);
-                    } else {
-                        s = range / QMAXF;
-                    }
-                    double e = 0.0;
+    // ---- packed codes: after the quad transpose lane j owns 16 consecutive elements
+    // (64c + 16q ..) of row k0 + j
+    if (a.packed) {
+        uint8_t *row = a.packed + (k0 + (uint64_t)j) * P;
 #pragma unroll
-                    for (int c = 0; c < M; ++c) {
-                        e = add_err(e, x[u][c].x, c_lo, c_hi, s, inv);
-                        e = add_err(e, x[u][c].y, c_lo, c_hi, s, inv);
-                        e = add_err(e, x[u][c].z, c_lo, c_hi, s, inv);
-                        e = add_err(e, x[u][c].w, c_lo, c_hi, s, inv);
-                    }
-                    return row16_sum(e);
-                };
-                float cur_lo[4], cur_hi[4], step[4];
-                double best[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    cur_lo[u] = lo[u];
-                    cur_hi[u] = hi[u];
-                    step[u] = (hi[u] - lo[u]) / num_bins_f;
-                    best[u] = row_err(u, lo[u], hi[u]);
-                }
-                for (uint32_t it = 0; it < n_iter; ++it) {
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const float c_lo = cur_lo[u] + step[u];
-                        const float c_hi = cur_hi[u] - step[u];
-                        const double e_lo = row_err(u, c_lo, cur_hi[u]);
-                        const double e_hi = row_err(u, cur_lo[u], c_hi);
-                        const bool move_lo = e_lo < e_hi;
-                        cur_lo[u] = move_lo ? c_lo : cur_lo[u];
-                        cur_hi[u] = move_lo ? cur_hi[u] : c_hi;
-                        const double e = move_lo ? e_lo : e_hi;
-                        if (e < best[u]) {
-                            best[u] = e;
-                            lo[u] = cur_lo[u];
-                            hi[u] = cur_hi[u];
-                        }
-                    }
-                }
-            };
-            bool odd_scale = false;
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const float s0 = (hi[u] - lo[u]) * INV_QMAX;
-                odd_scale |= s0 != 0.0f && !(s0 >= 0x1p-100f && s0 <= 0x1p100f);
-            }
-            // the last candidates are up to num_bins times narrower than the first
-            if (__builtin_amdgcn_ballot_w64(odd_scale) != 0 || num_bins_f > 0x1p20f)
-                search(std::false_type{});
-            else
-                search(std::true_type{});
-        }
-
-        // ---- per-row parameters, computed by the quad lane that owns the row (lane j <-> row k0+j)
-        const float my_lo = CNR_SEL4(lo);
-        const float my_scale = (CNR_SEL4(hi) - my_lo) / QMAXF;
-        const bool my_live = !((skip >> j) & 1u);
-        {   // lanes 0-3 of a group write scale, 4-7 bias, 8-11 min, 12-15 max
-            float *dst = q == 0 ? scale_out : q == 1 ? bias_out : q == 2 ? min_out : max_out;
-            const float v = q == 0 ? my_scale : q == 1 ? my_lo : q == 2 ? CNR_SEL4(X_min) : CNR_SEL4(X_max);
-            if (dst && my_live) store_stream<float>(dst + k0 + j, v);
-        }
-        const float sc[4] = {quad_bcast<0>(my_scale), quad_bcast<1>(my_scale), quad_bcast<2>(my_scale),
-                             quad_bcast<3>(my_scale)};
-
-        // ---- quantize with the selected range; h[c][u] = this lane's four codes of (row u, chunk c)
-        uint32_t h[M][4];
-        if constexpr (GREEDY) {
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-#pragma unroll
-                for (int c = 0; c < M; ++c) {
-                    const uint32_t q0 = (uint32_t)fq_code_f(x[u][c].x, lo[u], hi[u], sc[u], QMAXF);
-                    const uint32_t q1 = (uint32_t)fq_code_f(x[u][c].y, lo[u], hi[u], sc[u], QMAXF);
-                    const uint32_t q2 = (uint32_t)fq_code_f(x[u][c].z, lo[u], hi[u], sc[u], QMAXF);
-                    const uint32_t q3 = (uint32_t)fq_code_f(x[u][c].w, lo[u], hi[u], sc[u], QMAXF);
-                    h[c][u] = q0 | (q1 << BITS) | (q2 << (2 * BITS)) | (q3 << (3 * BITS));
-                    if (codes_out && !(skip & (1u << u)))
-                        *reinterpret_cast<uint32_t *>(codes_out + (k0 + u) * (uint64_t)DIM + 64 * c + 4 * l) =
-                            q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
-                }
-        } else {
-            // The reciprocal of the scale must be a normal number.  Rows with a scale outside
-            // [2^-100, 2^100] (denormal or near-overflow ranges) are brought there by an exact
-            // power-of-two factor applied to both x - lo and the scale; a wave takes that variant
-            // only if one of its sixteen rows needs it.
-            const float my_f = my_scale < 0x1p-100f ? 0x1p120f : my_scale > 0x1p100f ? 0x1p-120f : 1.0f;
-            const float my_fscale = my_scale * my_f;
-            const float my_inv = my_scale == 0.0f ? 0.0f : 1.0f / my_fscale;  // scale 0: every code 0
-            const float inv[4] = {quad_bcast<0>(my_inv), quad_bcast<1>(my_inv), quad_bcast<2>(my_inv),
-                                  quad_bcast<3>(my_inv)};
-            auto quantize_by_reciprocal = [&](auto rescale) {
-                constexpr bool RESCALE = decltype(rescale)::value;
-                float f[4] = {1.0f, 1.0f, 1.0f, 1.0f}, fsc[4] = {sc[0], sc[1], sc[2], sc[3]};
-                if constexpr (RESCALE) {
-                    f[0] = quad_bcast<0>(my_f); f[1] = quad_bcast<1>(my_f);
-                    f[2] = quad_bcast<2>(my_f); f[3] = quad_bcast<3>(my_f);
-                    fsc[0] = quad_bcast<0>(my_fscale); fsc[1] = quad_bcast<1>(my_fscale);
-                    fsc[2] = quad_bcast<2>(my_fscale); fsc[3] = quad_bcast<3>(my_fscale);
-                }
-                // magic-biased code of one element: MAGIC_BITS + round((x - lo) / scale)
-                auto biased = [&](float xv, int u) -> uint32_t {
-                    float a = xv - lo[u];
-                    if constexpr (RESCALE) a *= f[u];
-                    float t = a * inv[u];
-                    if constexpr (BITS == 8) {
-                        const float r = fmaf(-t, fsc[u], a);
-                        t = fmaf(r, inv[u], t);
-                    }
-                    return __float_as_uint(t + MAGIC);
-                };
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-#pragma unroll
-                    for (int c = 0; c < M; ++c) {
-                        const uint32_t b0 = biased(x[u][c].x, u), b1 = biased(x[u][c].y, u);
-                        const uint32_t b2 = biased(x[u][c].z, u), b3 = biased(x[u][c].w, u);
-                        uint32_t m = (b3 << BITS) + b2;
-                        m = (m << BITS) + b1;
-                        h[c][u] = (m << BITS) + b0 - MERGED_BIAS;
-                        if (codes_out && !(skip & (1u << u)))
-                            *reinterpret_cast<uint32_t *>(codes_out + (k0 + u) * (uint64_t)DIM + 64 * c + 4 * l) =
-                                (((((b3 << 8) + b2) << 8) + b1) << 8) + b0 - MERGED_BIAS8;
-                    }
-            };
-            if (__builtin_amdgcn_ballot_w64(my_f != 1.0f) != 0)
-                quantize_by_reciprocal(std::true_type{});
-            else
-                quantize_by_reciprocal(std::false_type{});
-        }
-
-        // ---- packed codes: after the quad transpose lane j owns 16 consecutive elements
-        // (64c + 16q ..) of row k0 + j
-        if (packed_out) {
-            uint8_t *row = packed_out + (k0 + (uint64_t)j) * P;
-#pragma unroll
-            for (int c = 0; c < M; ++c) {
-                uint32_t t[4] = {h[c][0], h[c][1], h[c][2], h[c][3]};
-                quad_transpose(t, j);
-                if constexpr (BITS == 8) {
-                    if (my_live) store_stream<u32x4>(row + 64 * c + 16 * q, u32x4{t[0], t[1], t[2], t[3]});
-                } else if constexpr (BITS == 4) {
-                    if (my_live)
-                        store_stream<u32x2>(row + 32 * c + 8 * q, u32x2{t[0] | (t[1] << 16), t[2] | (t[3] << 16)});
-                } else if constexpr (BITS == 2) {
-                    if (my_live)
-                        store_stream<uint32_t>(row + 16 * c + 4 * q, t[0] | (t[1] << 8) | (t[2] << 16) | (t[3] << 24));
-                } else {  // 3 bits: 48 bits per lane; even quads append the next quad's 48 bits
-                    const uint32_t w0 = t[0] | (t[1] << 12) | (t[2] << 24);  // stream bits 0..31
-                    const uint32_t w1 = (t[2] >> 8) | (t[3] << 4);           // stream bits 32..47
-                    const uint32_t n0 = (uint32_t)dpp_i<0x104>((int)w0);     // row_shl:4 = lane + 4
-                    const uint32_t n1 = (uint32_t)dpp_i<0x104>((int)w1);
-                    if (my_live && !(q & 1)) {
-                        uint32_t *dst = reinterpret_cast<uint32_t *>(row + 24 * c + 12 * (q >> 1));
-                        store_stream<uint32_t>(dst, w0);
-                        store_stream<uint32_t>(dst + 1, w1 | (n0 << 16));
-                        store_stream<uint32_t>(dst + 2, (n0 >> 16) | (n1 << 16));
-                    }
+        for (int c = 0; c < M; ++c) {
+            uint32_t t[4] = {h[c][0], h[c][1], h[c][2], h[c][3]};
+            quad_transpose(t, j);
+            if constexpr (BITS == 8) {
+                if (my_live) store_stream<u32x4>(row + 64 * c + 16 * q, u32x4{t[0], t[1], t[2], t[3]});
+            } else if constexpr (BITS == 4) {
+                if (my_live)
+                    store_stream<u32x2>(row + 32 * c + 8 * q, u32x2{t[0] | (t[1] << 16), t[2] | (t[3] << 16)});
+            } else if constexpr (BITS == 2) {
+                if (my_live)
+                    store_stream<uint32_t>(row + 16 * c + 4 * q, t[0] | (t[1] << 8) | (t[2] << 16) | (t[3] << 24));
+            } else {  // 3 bits: 48 bits per lane; even quads append the next quad's 48 bits
+                const uint32_t w0 = t[0] | (t[1] << 12) | (t[2] << 24);  // stream bits 0..31
+                const uint32_t w1 = (t[2] >> 8) | (t[3] << 4);           // stream bits 32..47
+                const uint32_t n0 = (uint32_t)dpp_i<0x104>((int)w0);     // row_shl:4 = lane + 4
+                const uint32_t n1 = (uint32_t)dpp_i<0x104>((int)w1);
+                if (my_live && !(q & 1)) {
+                    uint32_t *dst = reinterpret_cast<uint32_t *>(row + 24 * c + 12 * (q >> 1));
+                    store_stream<uint32_t>(dst, w0);
+                    store_stream<uint32_t>(dst + 1, w1 | (n0 << 16));
+                    store_stream<uint32_t>(dst + 2, (n0 >> 16) | (n1 << 16));
                 }
             }
         }
     }
 }
 #undef CNR_SEL4
+
+template <int M, int BITS>
+__global__ void __launch_bounds__(kBlock) quantize_rows16_kernel(const QuantArgs a) {
+    const uint64_t n = row_count(a);
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint64_t g4 = 4u * (uint64_t)(lane >> 4);  // first row of this lane's group within a batch
+    const int l = lane & 15;                         // lane in group
+    const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
+    uint64_t batch = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    if (batch * 16u >= n) return;
+
+    RowBatch<M> cur, nxt;
+    gather_rows<M>(a, n, batch * 16u + g4, gather_ids(a, batch * 16u + g4), l, cur);
+    uint64_t next = batch + n_waves;
+    uint4 ids_next = make_uint4(0, 0, 0, 0);
+    if (next * 16u < n) ids_next = gather_ids(a, next * 16u + g4);
+    for (;;) {
+        const bool has_next = next * 16u < n;  // uniform over the wave
+        if (has_next) gather_rows<M>(a, n, next * 16u + g4, ids_next, l, nxt);
+        const uint64_t next2 = next + n_waves;
+        if (next2 * 16u < n) ids_next = gather_ids(a, next2 * 16u + g4);
+        encode_batch<M, BITS>(a, batch * 16u + g4, cur, l);
+        if (!has_next) break;
+        cur = nxt;
+        batch = next;
+        next = next2;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Greedy range search (Approach 3), dim = 16 * L with L = 4, 8 or 16 lanes per row.  Bound by
+// vector-ALU issue: 1 + 2 * n_iter candidate ranges are tried per row.
+//
+// Every lane owns sixteen consecutive elements (four 16-byte loads) of one row, L neighbouring lanes
+// own the row, a wave handles 64 / L consecutive dirty rows per pass.  A candidate's error is summed
+// over a lane's sixteen registers and then over the L lanes with log2(L) DPP exchanges, a quarter of
+// the cross-lane work the bulk kernel's layout would need, and a lane's sixteen codes are exactly
+// 2 * BITS contiguous bytes of the packed row, so the output needs no transpose.
+// A candidate is evaluated with the cheapest sequence that still reproduces F_Q's codes: the scale
+// (range / (2^b - 1)) and the quotient (x - lo) / scale are formed by a reciprocal multiply followed
+// by one FMA residual correction (q' = q + (a - q*b) * (1/b)), which yields the correctly rounded
+// quotient except in cases far too rare to matter for ranking candidates; d*d is exact in fp64, so
+// fma(d, d, acc) is the multiply-then-add of the definition.  A wave holding a row whose scale lies
+// outside [2^-100, 2^100] divides instead.  The final codes of the chosen range are produced by
+// division, exactly as F_Q is written.
+// ---------------------------------------------------------------------------------------------
+template <int L>
+__device__ __forceinline__ float lanes_min(float v) {
+    v = fminf(v, dpp_f<0xB1>(v));
+    v = fminf(v, dpp_f<0x4E>(v));
+    if constexpr (L >= 8) v = fminf(v, dpp_f<0x141>(v));
+    if constexpr (L >= 16) v = fminf(v, dpp_f<0x140>(v));
+    return v;
+}
+template <int L>
+__device__ __forceinline__ float lanes_max(float v) {
+    v = fmaxf(v, dpp_f<0xB1>(v));
+    v = fmaxf(v, dpp_f<0x4E>(v));
+    if constexpr (L >= 8) v = fmaxf(v, dpp_f<0x141>(v));
+    if constexpr (L >= 16) v = fmaxf(v, dpp_f<0x140>(v));
+    return v;
+}
+template <int L>
+__device__ __forceinline__ double lanes_sum(double v) {
+    v += dpp_d<0xB1>(v);
+    v += dpp_d<0x4E>(v);
+    if constexpr (L >= 8) v += dpp_d<0x141>(v);
+    if constexpr (L >= 16) v += dpp_d<0x140>(v);
+    return v;
+}
+
+template <int L, int BITS>
+__global__ void __launch_bounds__(kBlock) quantize_greedy_kernel(const QuantArgs a) {
+    constexpr int DIM = 16 * L;
+    constexpr int kRowsPerPass = kWave / L;
+    constexpr float QMAXF = (float)((1 << BITS) - 1);
+    constexpr float INV_QMAX = 1.0f / QMAXF;
+    constexpr uint64_t P = (uint64_t)DIM * BITS / 8;  // packed bytes per row
+    const uint64_t n = row_count(a);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int j = lane % L;  // lane within the row
+    const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
+    for (uint64_t pass = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave; pass * kRowsPerPass < n;
+         pass += n_waves) {
+        const uint64_t k = pass * kRowsPerPass + lane / L;
+        // ---- gather
+        uint64_t rid = 0;
+        bool live = k < n;
+        if (live) {
+            rid = a.row_ids ? (uint64_t)a.row_ids[k] : k;
+            if (rid >= a.n_rows) {
+                if (j == 0) raise_flag(a.err, CNR_FLAG_ROW_ID);
+                live = false;
+                rid = 0;
+            }
+        }
+        float4 x[4];
+        {
+            const float *src = a.table + rid * (uint64_t)DIM + 16u * (uint64_t)j;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x[i] = *reinterpret_cast<const float4 *>(src + 4 * i);
+        }
+
+        // ---- row minimum / maximum
+        float mn = fminf(fminf(x[0].x, x[0].y), fminf(x[0].z, x[0].w));
+        float mx = fmaxf(fmaxf(x[0].x, x[0].y), fmaxf(x[0].z, x[0].w));
+#pragma unroll
+        for (int i = 1; i < 4; ++i) {
+            mn = fminf(fminf(mn, x[i].x), fminf(x[i].y, fminf(x[i].z, x[i].w)));
+            mx = fmaxf(fmaxf(mx, x[i].x), fmaxf(x[i].y, fmaxf(x[i].z, x[i].w)));
+        }
+        const float X_min = lanes_min<L>(mn) + 0.0f;  // -0.0 -> +0.0
+        const float X_max = lanes_max<L>(mx) + 0.0f;
+        float lo = X_min, hi = X_max;
+
+        // ---- the search: shrink from whichever side hurts less, remember the best range seen
+        auto search = [&](auto fast_tag) {
+            constexpr bool FAST = decltype(fast_tag)::value;
+            auto add_err = [&](double acc, float xv, float c_lo, float c_hi, float s, float inv) -> double {
+                if constexpr (FAST) {
+                    const float c = __builtin_amdgcn_fmed3f(xv, c_lo, c_hi);
+                    const float d0 = c - c_lo;
+                    float t = d0 * inv;
+                    t = fmaf(fmaf(-t, s, d0), inv, t);
+                    const float d = xv - fq_value(rintf(t), s, c_lo);
+                    return fma((double)d, (double)d, acc);
+                } else {
+                    return acc + fq_sq_err(xv, c_lo, c_hi, s, QMAXF);
+                }
+            };
+            auto row_err = [&](float c_lo, float c_hi) -> double {
+                const float range = c_hi - c_lo;
+                float s, inv = 0.0f;
+                if constexpr (FAST) {
+                    const float q0 = range * INV_QMAX;
+                    s = fmaf(fmaf(-q0, QMAXF, range), INV_QMAX, q0);
+                    const float r0 = __builtin_amdgcn_rcpf(s);
+                    inv = s == 0.0f ? 0.0f : fmaf(fmaf(-s, r0, 1.0f), r0, r0);
+                } else {
+                    s = range / QMAXF;
+                }
+                double e = 0.0;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    e = add_err(e, x[i].x, c_lo, c_hi, s, inv);
+                    e = add_err(e, x[i].y, c_lo, c_hi, s, inv);
+                    e = add_err(e, x[i].z, c_lo, c_hi, s, inv);
+                    e = add_err(e, x[i].w, c_lo, c_hi, s, inv);
+                }
+                return lanes_sum<L>(e);
+            };
+            float cur_lo = lo, cur_hi = hi;
+            const float step = (hi - lo) / a.num_bins_f;
+            double best = row_err(lo, hi);
+            for (uint32_t it = 0; it < a.n_iter; ++it) {
+                const float c_lo = cur_lo + step;
+                const float c_hi = cur_hi - step;
+                const double e_lo = row_err(c_lo, cur_hi);
+                const double e_hi = row_err(cur_lo, c_hi);
+                const bool move_lo = e_lo < e_hi;
+                cur_lo = move_lo ? c_lo : cur_lo;
+                cur_hi = move_lo ? cur_hi : c_hi;
+                const double e = move_lo ? e_lo : e_hi;
+                if (e < best) {
+                    best = e;
+                    lo = cur_lo;
+                    hi = cur_hi;
+                }
+            }
+        };
+        const float s0 = (hi - lo) * INV_QMAX;
+        const bool odd_scale = s0 != 0.0f && !(s0 >= 0x1p-100f && s0 <= 0x1p100f);
+        // the last candidates are up to num_bins times narrower than the first
+        if (__builtin_amdgcn_ballot_w64(odd_scale) != 0 || a.num_bins_f > 0x1p20f)
+            search(std::false_type{});
+        else
+            search(std::true_type{});
+
+        // ---- per-row parameters: lane 0 of the row writes scale, lane 1 bias, lanes 2, 3 min, max
+        const float scale = (hi - lo) / QMAXF;
+        {
+            float *dst = j == 0 ? a.scale : j == 1 ? a.bias : j == 2 ? a.row_min : a.row_max;
+            const float v = j == 0 ? scale : j == 1 ? lo : j == 2 ? X_min : X_max;
+            if (j < 4 && dst && live) dst[k] = v;
+        }
+
+        // ---- final codes by F_Q as written; h[i] = the four codes of x[i], first element lowest
+        uint32_t h[4], h8[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t q0 = (uint32_t)fq_code_f(x[i].x, lo, hi, scale, QMAXF);
+            const uint32_t q1 = (uint32_t)fq_code_f(x[i].y, lo, hi, scale, QMAXF);
+            const uint32_t q2 = (uint32_t)fq_code_f(x[i].z, lo, hi, scale, QMAXF);
+            const uint32_t q3 = (uint32_t)fq_code_f(x[i].w, lo, hi, scale, QMAXF);
+            h[i] = q0 | (q1 << BITS) | (q2 << (2 * BITS)) | (q3 << (3 * BITS));
+            h8[i] = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
+        }
+        if (a.codes && live)
+            *reinterpret_cast<uint4 *>(a.codes + k * (uint64_t)DIM + 16 * j) = make_uint4(h8[0], h8[1], h8[2], h8[3]);
+
+        // ---- packed codes: this lane's bits are bytes [2 * BITS * j, 2 * BITS * (j + 1)) of the row
+        if (a.packed) {
+            uint8_t *dst = a.packed + k * P + 2 * BITS * j;
+            if constexpr (BITS == 8) {
+                if (live) *reinterpret_cast<uint4 *>(dst) = make_uint4(h[0], h[1], h[2], h[3]);
+            } else if constexpr (BITS == 4) {
+                if (live) *reinterpret_cast<uint2 *>(dst) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+            } else if constexpr (BITS == 2) {
+                if (live) *reinterpret_cast<uint32_t *>(dst) = h[0] | (h[1] << 8) | (h[2] << 16) | (h[3] << 24);
+            } else {  // 3 bits: 48 bits per lane; even lanes append their right neighbour's 48 bits
+                const uint32_t w0 = h[0] | (h[1] << 12) | (h[2] << 24);  // stream bits 0..31
+                const uint32_t w1 = (h[2] >> 8) | (h[3] << 4);           // stream bits 32..47
+                const uint32_t n0 = (uint32_t)dpp_i<0xB1>((int)w0);      // lane ^ 1
+                const uint32_t n1 = (uint32_t)dpp_i<0xB1>((int)w1);
+                if (live && !(j & 1)) {
+                    uint32_t *d3 = reinterpret_cast<uint32_t *>(dst);
+                    d3[0] = w0;
+                    d3[1] = w1 | (n0 << 16);
+                    d3[2] = (n0 >> 16) | (n1 << 16);
+                }
+            }
+        }
+    }
+}
 
 // ---------------------------------------------------------------------------------------------
 // Any other dim (dim % 4 == 0, dim * bits % 8 == 0): one wavefront per row, lanes stride over the
@@ -564,49 +641,30 @@ pack_kernel(const uint8_t *__restrict__ codes, const uint64_t *__restrict__ n_de
     }
 }
 
-struct QuantArgs {
-    const float *table;
-    uint64_t n_rows;
-    uint32_t dim;
-    const uint32_t *row_ids;
-    const uint64_t *n_dev;
-    uint64_t n_max;
-    int mode;
-    uint32_t n_iter;
-    float num_bins_f;
-    float *scale, *bias, *row_min, *row_max;
-    uint8_t *codes, *packed;
-};
-
-template <int M, int BITS, bool GREEDY>
+template <int M, int BITS>
 void launch_rows16(cnr_ctx *ctx, const QuantArgs &a, hipStream_t s) {
     const unsigned grid = cnr_grid(ctx, a.n_max, 16u * kWavesPerBlock,
-                                   cnr_resident_blocks_per_cu<quantize_rows16_kernel<M, BITS, GREEDY>>());
-    Rows16Args k;
-    k.table = a.table; k.n_rows = a.n_rows; k.row_ids = a.row_ids; k.n_dev = a.n_dev; k.n_max = a.n_max;
-    k.mode = a.mode; k.n_iter = a.n_iter; k.num_bins_f = a.num_bins_f;
-    k.scale_out = a.scale; k.bias_out = a.bias; k.min_out = a.row_min; k.max_out = a.row_max;
-    k.codes_out = a.codes; k.packed_out = a.packed; k.err = ctx->dev_err;
-    hipLaunchKernelGGL((quantize_rows16_kernel<M, BITS, GREEDY>), dim3(grid), dim3(kBlock), 0, s, k);
+                                   cnr_resident_blocks_per_cu<quantize_rows16_kernel<M, BITS>>());
+    hipLaunchKernelGGL((quantize_rows16_kernel<M, BITS>), dim3(grid), dim3(kBlock), 0, s, a);
 }
 
-template <int M, int BITS>
-void launch_rows16_mode(cnr_ctx *ctx, const QuantArgs &a, hipStream_t s) {
-    if (a.mode == kModeGreedy && a.n_iter > 0)
-        launch_rows16<M, BITS, true>(ctx, a, s);
-    else
-        launch_rows16<M, BITS, false>(ctx, a, s);
+template <int L, int BITS>
+void launch_greedy(cnr_ctx *ctx, const QuantArgs &a, hipStream_t s) {
+    const unsigned grid = cnr_grid(ctx, a.n_max, (uint64_t)(kWave / L) * kWavesPerBlock,
+                                   cnr_resident_blocks_per_cu<quantize_greedy_kernel<L, BITS>>());
+    hipLaunchKernelGGL((quantize_greedy_kernel<L, BITS>), dim3(grid), dim3(kBlock), 0, s, a);
 }
 
 template <int BITS>
 void launch_bits(cnr_ctx *ctx, const QuantArgs &a, hipStream_t s) {
-    if (a.dim == 64) return launch_rows16_mode<1, BITS>(ctx, a, s);
-    if (a.dim == 128) return launch_rows16_mode<2, BITS>(ctx, a, s);
-    if (a.dim == 256) return launch_rows16_mode<4, BITS>(ctx, a, s);
+    const bool greedy = a.mode == kModeGreedy && a.n_iter > 0;  // zero iterations: plain min/max
+    if (a.dim == 64) return greedy ? launch_greedy<4, BITS>(ctx, a, s) : launch_rows16<1, BITS>(ctx, a, s);
+    if (a.dim == 128) return greedy ? launch_greedy<8, BITS>(ctx, a, s) : launch_rows16<2, BITS>(ctx, a, s);
+    if (a.dim == 256) return greedy ? launch_greedy<16, BITS>(ctx, a, s) : launch_rows16<4, BITS>(ctx, a, s);
     const unsigned grid = cnr_grid(ctx, a.n_max, kWavesPerBlock, 8);
     hipLaunchKernelGGL((quantize_rows_generic_kernel<BITS>), dim3(grid), dim3(kBlock), 0, s, a.table,
                        a.n_rows, a.dim, a.row_ids, a.n_dev, a.n_max, a.mode, a.n_iter, a.num_bins_f,
-                       a.scale, a.bias, a.row_min, a.row_max, a.codes, a.packed, ctx->dev_err);
+                       a.scale, a.bias, a.row_min, a.row_max, a.codes, a.packed, a.err);
 }
 
 }  // namespace
@@ -636,7 +694,7 @@ cnr_status cnr_quantize_rows(cnr_ctx *ctx, const float *table, uint64_t n_rows, 
     a.n_iter = mode == CNR_RANGE_GREEDY ? cnr_greedy_iterations(greedy->num_bins, greedy->ratio) : 0;
     a.num_bins_f = mode == CNR_RANGE_GREEDY ? (float)greedy->num_bins : 1.0f;
     a.scale = scale; a.bias = bias; a.row_min = row_min; a.row_max = row_max;
-    a.codes = codes_u8; a.packed = packed;
+    a.codes = codes_u8; a.packed = packed; a.err = ctx->dev_err;
     hipStream_t s = as_stream(stream);
     switch (bits) {
         case 2: launch_bits<2>(ctx, a, s); break;
