@@ -179,6 +179,20 @@ cnr_status cnr_restore_rows(cnr_ctx *ctx, float *table, uint64_t n_rows, uint32_
                             int bits, const uint8_t *packed, const float *scale,
                             const float *bias, void *stream);
 
+/* ---- error metric (Section 5.2: l2 error of a quantized vector, mean l2 error of a checkpoint) - */
+
+/* For k < n = min(*n_dev, n_max): err[k] = || X_k - Q_k ||_2, where X_k is row row_ids[k] (row k
+ * when row_ids is NULL) of `table` and Q_k the same row as cnr_restore_rows would write it from
+ * (packed, scale, bias); element differences, their squares and the sum are taken in fp64.  When
+ * mean_out is not NULL, *mean_out receives (1/n) * sum_k err[k], added up in a fixed order (0 when
+ * n == 0).  Rows with an id >= n_rows get err 0 and raise CNR_FLAG_ROW_ID.
+ *   err       double [n_max], required
+ *   mean_out  double [1] (device) or NULL */
+cnr_status cnr_quant_error(cnr_ctx *ctx, const float *table, uint64_t n_rows, uint32_t dim,
+                           const uint32_t *row_ids, const uint64_t *n_dev, uint64_t n_max, int bits,
+                           const uint8_t *packed, const float *scale, const float *bias, double *err,
+                           double *mean_out, void *stream);
+
 /* ---- device-side conditions ---------------------------------------------------------------- */
 
 /* Waits for `stream`, then reports and resets what the kernels recorded since the last poll.

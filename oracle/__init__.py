@@ -5,3 +5,4 @@ the benchmark.  Nothing in the GPU library imports this package, and this packag
 from the GPU library.
 """
 from .cnr_oracle import *  # noqa: F401,F403
+from .selection import mean_l2, select_greedy_params, taper_choice  # noqa: F401

@@ -235,3 +235,4 @@ def full_checkpoint_due(sizes) -> bool:
     """Intermittent-incremental predictor: ``sizes`` = [S_1, ..., S_i] as fractions of a full one."""
     s = _c(np.asarray(sizes, dtype=np.float64), np.float64).reshape(-1)
     return bool(_load().cnro_full_checkpoint_due(_ptr(s), s.size))
+

@@ -30,7 +30,7 @@ EXPORTS = (
     "cnr_create", "cnr_destroy", "cnr_bitmap_words", "cnr_packed_row_bytes", "cnr_scratch_bytes",
     "cnr_mark_scratch_bytes",
     "cnr_greedy_iterations", "cnr_clear_bitmap", "cnr_mark_touched", "cnr_compact_dirty",
-    "cnr_quantize_rows", "cnr_pack", "cnr_restore_rows", "cnr_poll_errors", "cnr_status_str",
+    "cnr_quantize_rows", "cnr_pack", "cnr_restore_rows", "cnr_quant_error", "cnr_poll_errors", "cnr_status_str",
     "cnr_last_hip_error", "cnr_full_checkpoint_due",
 )
 
@@ -76,6 +76,7 @@ def load() -> ctypes.CDLL:
                                         ctypes.POINTER(cnr_greedy_params), vp, vp, vp, vp, vp, vp, vp]),
             "cnr_pack": (i32, [vp, vp, vp, u64, u32, i32, vp, vp]),
             "cnr_restore_rows": (i32, [vp, vp, u64, u32, vp, vp, u64, i32, vp, vp, vp, vp]),
+            "cnr_quant_error": (i32, [vp, vp, u64, u32, vp, vp, u64, i32, vp, vp, vp, vp, vp, vp]),
             "cnr_poll_errors": (i32, [vp, vp, ctypes.POINTER(u64), ctypes.POINTER(u32)]),
             "cnr_status_str": (ctypes.c_char_p, [i32]),
             "cnr_last_hip_error": (i32, [vp]),
@@ -229,6 +230,18 @@ def cnr_restore_rows(ctx, table, n_rows: int, dim: int, row_ids, n_dev, n_max: i
                                    _dev(row_ids, U32, "row_ids"), _dev(n_dev, U64, "n_dev"), n_max,
                                    bits, _dev(packed, U8, "packed"), _dev(scale, F32, "scale"),
                                    _dev(bias, F32, "bias"), _stream(stream)), "cnr_restore_rows")
+
+
+def cnr_quant_error(ctx, table, n_rows: int, dim: int, row_ids, n_dev, n_max: int, bits: int, packed,
+                    scale, bias, err, mean_out=None, stream=None) -> None:
+    if (packed.numel() < n_max * cnr_packed_row_bytes(dim, bits) or scale.numel() < n_max
+            or bias.numel() < n_max or err.numel() < n_max or (row_ids is not None and row_ids.numel() < n_max)):
+        raise ValueError("buffer too small for n_max rows")
+    _check(load().cnr_quant_error(ctx, _dev(table, F32, "table"), n_rows, dim, _dev(row_ids, U32, "row_ids"),
+                                  _dev(n_dev, U64, "n_dev"), n_max, bits, _dev(packed, U8, "packed"),
+                                  _dev(scale, F32, "scale"), _dev(bias, F32, "bias"),
+                                  _dev(err, torch.float64, "err"), _dev(mean_out, torch.float64, "mean_out"),
+                                  _stream(stream)), "cnr_quant_error")
 
 
 def cnr_poll_errors(ctx, stream=None):

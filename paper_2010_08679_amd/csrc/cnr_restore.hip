@@ -225,7 +225,103 @@ void launch_restore(cnr_ctx *ctx, hipStream_t st, float *table, uint64_t n_rows,
                            bias, ctx->dev_err);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Error metric: || X - Q ||_2 per row in fp64, one wavefront per row, any dim; and its mean, added
+// up by one workgroup in a fixed order so that the result does not depend on scheduling.
+// ---------------------------------------------------------------------------------------------
+template <int BITS>
+__global__ void __launch_bounds__(kBlock)
+quant_error_kernel(const float *__restrict__ table, uint64_t n_rows, uint32_t dim,
+                   const uint32_t *__restrict__ row_ids, const uint64_t *__restrict__ n_dev, uint64_t n_max,
+                   const uint8_t *__restrict__ packed, const float *__restrict__ scale,
+                   const float *__restrict__ bias, double *__restrict__ err_out, cnr_dev_errors *err) {
+    constexpr uint32_t MASK = (1u << BITS) - 1u;
+    uint64_t n = n_max;
+    if (n_dev) {
+        const uint64_t nd = *n_dev;
+        n = nd < n_max ? nd : n_max;
+    }
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
+    const uint64_t P = (uint64_t)dim * BITS / 8;
+    for (uint64_t k = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave; k < n; k += n_waves) {
+        const uint64_t r = row_ids ? (uint64_t)row_ids[k] : k;
+        if (r >= n_rows) {
+            if (lane == 0) {
+                raise_flag(err, CNR_FLAG_ROW_ID);
+                err_out[k] = 0.0;
+            }
+            continue;
+        }
+        const uint8_t *__restrict__ in = packed + k * P;
+        const float s = scale[k], b = bias[k];
+        const float *__restrict__ x = table + r * (uint64_t)dim;
+        double acc = 0.0;
+        for (uint32_t e = lane; e < dim; e += kWave) {
+            const uint64_t bit = (uint64_t)e * BITS;
+            uint32_t two = in[bit >> 3];
+            if (((bit & 7u) + BITS) > 8u) two |= (uint32_t)in[(bit >> 3) + 1] << 8;
+            const float q = s * (float)((two >> (bit & 7u)) & MASK) + b;
+            const double d = (double)x[e] - (double)q;
+            acc += d * d;
+        }
+        for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+        if (lane == 0) err_out[k] = sqrt(acc);
+    }
+}
+
+__global__ void __launch_bounds__(kBlock)
+mean_kernel(const double *__restrict__ v, const uint64_t *__restrict__ n_dev, uint64_t n_max,
+            double *__restrict__ mean_out) {
+    __shared__ double part[kBlock];
+    uint64_t n = n_max;
+    if (n_dev) {
+        const uint64_t nd = *n_dev;
+        n = nd < n_max ? nd : n_max;
+    }
+    double acc = 0.0;
+    for (uint64_t i = threadIdx.x; i < n; i += kBlock) acc += v[i];
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    for (int half = kBlock / 2; half > 0; half >>= 1) {
+        if ((int)threadIdx.x < half) part[threadIdx.x] += part[threadIdx.x + half];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *mean_out = n ? part[0] / (double)n : 0.0;
+}
+
 }  // namespace
+
+extern "C" cnr_status cnr_quant_error(cnr_ctx *ctx, const float *table, uint64_t n_rows, uint32_t dim,
+                                      const uint32_t *row_ids, const uint64_t *n_dev, uint64_t n_max,
+                                      int bits, const uint8_t *packed, const float *scale,
+                                      const float *bias, double *err, double *mean_out, void *stream) {
+    cnr_status st = cnr_enter(ctx);
+    if (st != CNR_OK) return st;
+    if (!cnr_valid_bits(bits)) return CNR_E_BITS;
+    if (dim == 0 || dim > CNR_MAX_DIM || ((uint64_t)dim * (uint64_t)bits) % 8) return CNR_E_DIM;
+    if (((uintptr_t)err % 8) || ((uintptr_t)mean_out % 8) || ((uintptr_t)n_dev % 8) || ((uintptr_t)table % 4) ||
+        ((uintptr_t)scale % 4) || ((uintptr_t)bias % 4) || ((uintptr_t)row_ids % 4))
+        return CNR_E_ALIGN;
+    hipStream_t s = as_stream(stream);
+    if (n_max > 0) {
+        if (!table || !packed || !scale || !bias || !err || n_rows == 0 || n_rows >= (1ull << 32)) return CNR_E_INVALID;
+        const unsigned grid = cnr_grid(ctx, n_max, kWavesPerBlock, 8);
+        switch (bits) {
+            case 2: hipLaunchKernelGGL(quant_error_kernel<2>, dim3(grid), dim3(kBlock), 0, s, table, n_rows, dim, row_ids, n_dev, n_max, packed, scale, bias, err, ctx->dev_err); break;
+            case 3: hipLaunchKernelGGL(quant_error_kernel<3>, dim3(grid), dim3(kBlock), 0, s, table, n_rows, dim, row_ids, n_dev, n_max, packed, scale, bias, err, ctx->dev_err); break;
+            case 4: hipLaunchKernelGGL(quant_error_kernel<4>, dim3(grid), dim3(kBlock), 0, s, table, n_rows, dim, row_ids, n_dev, n_max, packed, scale, bias, err, ctx->dev_err); break;
+            default: hipLaunchKernelGGL(quant_error_kernel<8>, dim3(grid), dim3(kBlock), 0, s, table, n_rows, dim, row_ids, n_dev, n_max, packed, scale, bias, err, ctx->dev_err); break;
+        }
+        st = cnr_launch_status(ctx);
+        if (st != CNR_OK) return st;
+    }
+    if (mean_out) {
+        hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(kBlock), 0, s, err, n_dev, n_max, mean_out);
+        st = cnr_launch_status(ctx);
+    }
+    return st;
+}
 
 extern "C" cnr_status cnr_restore_rows(cnr_ctx *ctx, float *table, uint64_t n_rows, uint32_t dim,
                                        const uint32_t *row_ids, const uint64_t *n_dev, uint64_t n_max,

@@ -184,3 +184,11 @@ def lookup_batches(w: Workload, table_index: int, seed: int, device="cpu",
             n += 1
         return
     raise ValueError(w.lookups)
+
+
+def sample_positions(n: int, fraction: float, seed: int, device="cpu", min_rows: int = 256) -> torch.Tensor:
+    """Uniform sample (with replacement, sorted) of positions in [0, n): max(min_rows, fraction * n)
+    draws; the input of the greedy-parameter profiling (Section 5.2: 0.001 % of the checkpoint)."""
+    m = max(min_rows, int(math.ceil(fraction * n)))
+    g = _gen(seed, device)
+    return torch.sort((torch.rand(m, dtype=torch.float64, device=device, generator=g) * n).long().clamp_(max=n - 1)).values

@@ -368,3 +368,47 @@ def test_cfg2_two_tables_accumulated_tracking(ctx):
         compare_quantized(gt.host[ids], got, ora, 4, what="cfg2 table %d" % ti)
         assert np.array_equal(got["packed"], O.pack(got["codes"], 4))
     _poll_clean(ctx)
+
+
+# ------------------------------------------------------------------ error metric and parameter selection
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("dim", [64, 128, 40])
+def test_quant_error_matches_oracle_l2(ctx, bits, dim):
+    n_rows = 2000
+    gt = GpuTable(ctx, _table(n_rows, dim, 50 + bits, kind="outlier"))
+    idx = _dirty(gt, 0.4, 9)
+    got = gpu_encode_all_outputs(gt, bits)
+    n, d = got["n"], got["dev"]
+    err = torch.full((max(1, d["n_max"]),), -1.0, dtype=torch.float64, device=DEV)
+    mean = torch.full((1,), -1.0, dtype=torch.float64, device=DEV)
+    P.cnr_quant_error(ctx, gt.table, n_rows, dim, d["row_ids"], d["n_dev"], d["n_max"], bits, d["packed"],
+                      d["scale"], d["bias"], err, mean)
+    torch.cuda.synchronize()
+    ids = u32(d["row_ids"])[:n]
+    want, want_mean = O.row_l2(gt.host[ids], O.dequantize(got["codes"], got["scale"], got["bias"]))
+    e = err.cpu().numpy()
+    assert np.allclose(e[:n], want, rtol=1e-12, atol=0) and np.all(e[n:] == -1.0)
+    assert float(mean.item()) == pytest.approx(want_mean, rel=1e-12)
+    _poll_clean(ctx)
+
+
+def test_greedy_parameter_selection_matches_oracle(ctx):
+    # Section 5.2 "Parameter selection": profile a uniform sample of the dirty rows over a grid of
+    # num_bins and ratio values; both sides must see the same error curves and make the same choice
+    n_rows, dim, bits = 200_000, 64, 3
+    gt = GpuTable(ctx, _table(n_rows, dim, 21, kind="outlier"))
+    _dirty(gt, 0.3, 2)
+    n = int(gt.ck.n_dirty.item())
+    pos = synth.sample_positions(n, 0.005, 7, DEV, min_rows=256)
+    sample_ids = gt.ck.row_ids[pos].contiguous()
+    bins, ratios = (5, 10, 20, 30, 40, 50), (0.25, 0.5, 0.75, 1.0)
+    choice, report = P.select_greedy_params(ctx, gt.table, n_rows, dim, sample_ids, bits, bins, ratios)
+    rows = gt.host[u32(sample_ids)]
+    want_choice, want_report = O.select_greedy_params(rows, bits, bins, ratios, n_threads=8)
+    assert set(report) == set(want_report)
+    for key in want_report:
+        assert report[key] == pytest.approx(want_report[key], rel=1e-9), key
+    assert choice == want_choice
+    assert report[("bins", choice[0])] < report["naive"]
+    _poll_clean(ctx)

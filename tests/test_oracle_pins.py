@@ -480,3 +480,36 @@ def test_intermittent_policy_switches_at_interval_eight_on_paper_like_growth():
     S = [0.25 + 0.03 * k for k in range(12)]
     first = next(i for i in range(1, 12) if O.full_checkpoint_due(S[:i]))
     assert first + 1 == 8 and S[first - 1] < 0.5
+
+
+# ------------------------------------------------------------------ parameter selection (Section 5.2)
+
+def test_taper_rule_keeps_the_smallest_value_near_the_best():
+    grid = [5, 10, 15, 20, 25]
+    naive = 1.0
+    errs = [0.90, 0.80, 0.712, 0.70, 0.70]                 # improvements .10 .20 .288 .30 .30
+    assert O.taper_choice(grid, errs, naive, 0.05) == 15   # .288 >= .95 * .30
+    assert O.taper_choice(grid, errs, naive, 0.0) == 20
+    assert O.taper_choice(grid, [1.0] * 5, naive, 0.05) == 5    # no improvement at all
+
+
+def test_selection_never_worse_than_naive_and_sample_agrees_with_full():
+    # Section 5.2: the error of the adaptive range is never above the naive one, and the choice made
+    # on a small uniform sample matched the choice made on the full checkpoint.
+    rng = np.random.default_rng(11)
+    t = rng.normal(0, 0.02, size=(6000, 64)).astype(np.float32)
+    mask = rng.random(t.shape) < 0.01
+    t[mask] = rng.laplace(0, 0.2, size=int(mask.sum())).astype(np.float32)
+    bins, ratios = (5, 15, 25, 35, 45), (0.2, 0.4, 0.6, 0.8, 1.0)
+    full, rep_full = O.select_greedy_params(t, 4, bins, ratios, n_threads=8)
+    for key, e in rep_full.items():
+        assert e <= rep_full["naive"] * (1 + 1e-12), key
+    sample = t[np.sort(rng.integers(0, t.shape[0], 1500))]
+    small, rep_small = O.select_greedy_params(sample, 4, bins, ratios, n_threads=8)
+    # the sampled error curve tracks the full one, so the choice lands on the same plateau: at most
+    # one grid step away, and as good on the full data as the taper rule demands
+    for key in rep_full:
+        assert rep_small[key] == pytest.approx(rep_full[key], rel=0.05)
+    assert abs(bins.index(small[0]) - bins.index(full[0])) <= 1
+    gain = lambda nb: 1.0 - rep_full[("bins", nb)] / rep_full["naive"]  # noqa: E731
+    assert gain(small[0]) >= 0.9 * max(gain(nb) for nb in bins)
