@@ -206,12 +206,45 @@ const char *cnr_status_str(cnr_status s);
 /* hipError_t of the last failed HIP call on this context (0 if none), as an int. */
 int cnr_last_hip_error(const cnr_ctx *ctx);
 
-/* ---- checkpoint policy (Section 5.1, intermittent incremental checkpoint; host only) -------- */
+/* ---- checkpoint policy (Section 5.1; host only, no GPU involved) --------------------------------- */
 
 /* sizes[0..i) = S_1..S_i, the sizes of the incremental checkpoints since the last full one as
  * fractions of a full checkpoint.  Returns 1 when a full checkpoint should be taken at interval
  * i+1, i.e. when F_c = 1 + S_1 + ... + S_i <= I_c = (i + 1) * S_i, else 0 (also for i == 0). */
 int cnr_full_checkpoint_due(const double *sizes /* host */, uint32_t i);
+
+/* The three incremental policies of Section 5.1 as a small state machine the trainer consults at
+ * the end of every checkpoint interval.
+ *   one-shot      every incremental checkpoint holds the rows modified since the baseline: the
+ *                 tracking bitmap is never cleared; resume = baseline + latest incremental
+ *   consecutive   every incremental checkpoint holds the rows modified in the last interval: the
+ *                 bitmap is cleared after each checkpoint; resume = baseline + all incrementals in
+ *                 order
+ *   intermittent  one-shot, but a new full baseline is taken when cnr_full_checkpoint_due says so
+ *                 on the history S_1..S_i of incremental sizes since the last full one (the
+ *                 decision at interval i+1 uses the history only, as in the paper; the size measured
+ *                 at interval i+1 is recorded afterwards when the checkpoint is incremental)
+ * The struct is plain data owned by the caller (host). */
+typedef enum { CNR_POLICY_ONE_SHOT = 0, CNR_POLICY_CONSECUTIVE = 1, CNR_POLICY_INTERMITTENT = 2 } cnr_policy_kind;
+
+#define CNR_POLICY_MAX_HISTORY 256u
+
+typedef struct {
+    int kind;                               /* cnr_policy_kind */
+    uint32_t n_history;                     /* i: incremental checkpoints since the last full one */
+    double history[CNR_POLICY_MAX_HISTORY]; /* S_1 .. S_i */
+} cnr_policy;
+
+typedef struct {
+    int take_full;    /* 1: write a full checkpoint (new baseline) now; 0: write the dirty rows */
+    int clear_bitmap; /* 1: clear the tracking bitmap after this checkpoint */
+} cnr_policy_decision;
+
+cnr_status cnr_policy_init(cnr_policy *p /* host */, cnr_policy_kind kind);
+/* dirty_fraction = n_dirty / n_rows as cnr_compact_dirty just measured it (the size the incremental
+ * checkpoint would have, as a fraction of a full one).  When the history is full the intermittent
+ * policy takes a full checkpoint. */
+cnr_policy_decision cnr_policy_next(cnr_policy *p /* host */, double dirty_fraction);
 
 #ifdef __cplusplus
 }

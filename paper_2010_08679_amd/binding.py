@@ -31,7 +31,7 @@ EXPORTS = (
     "cnr_mark_scratch_bytes",
     "cnr_greedy_iterations", "cnr_clear_bitmap", "cnr_mark_touched", "cnr_compact_dirty",
     "cnr_quantize_rows", "cnr_pack", "cnr_restore_rows", "cnr_quant_error", "cnr_poll_errors", "cnr_status_str",
-    "cnr_last_hip_error", "cnr_full_checkpoint_due",
+    "cnr_last_hip_error", "cnr_full_checkpoint_due", "cnr_policy_init", "cnr_policy_next",
 )
 
 
@@ -39,6 +39,19 @@ class CnrError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
         super().__init__("%s: %s (status %d)" % (where, status_str(status), status))
+
+
+CNR_POLICY_ONE_SHOT, CNR_POLICY_CONSECUTIVE, CNR_POLICY_INTERMITTENT = 0, 1, 2
+CNR_POLICY_MAX_HISTORY = 256
+
+
+class cnr_policy(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int), ("n_history", ctypes.c_uint32),
+                ("history", ctypes.c_double * CNR_POLICY_MAX_HISTORY)]
+
+
+class cnr_policy_decision(ctypes.Structure):
+    _fields_ = [("take_full", ctypes.c_int), ("clear_bitmap", ctypes.c_int)]
 
 
 class cnr_greedy_params(ctypes.Structure):
@@ -81,6 +94,8 @@ def load() -> ctypes.CDLL:
             "cnr_status_str": (ctypes.c_char_p, [i32]),
             "cnr_last_hip_error": (i32, [vp]),
             "cnr_full_checkpoint_due": (i32, [ctypes.POINTER(ctypes.c_double), u32]),
+            "cnr_policy_init": (i32, [ctypes.POINTER(cnr_policy), i32]),
+            "cnr_policy_next": (cnr_policy_decision, [ctypes.POINTER(cnr_policy), ctypes.c_double]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(lib, name)
@@ -289,3 +304,15 @@ def cnr_last_hip_error(ctx) -> int:
 def cnr_full_checkpoint_due(sizes) -> bool:
     arr = (ctypes.c_double * len(sizes))(*[float(s) for s in sizes])
     return bool(load().cnr_full_checkpoint_due(arr, len(sizes)))
+
+
+def cnr_policy_init(kind: int) -> cnr_policy:
+    p = cnr_policy()
+    _check(load().cnr_policy_init(ctypes.byref(p), int(kind)), "cnr_policy_init")
+    return p
+
+
+def cnr_policy_next(policy: cnr_policy, dirty_fraction: float):
+    """Returns (take_full, clear_bitmap) for the checkpoint at the end of this interval."""
+    d = load().cnr_policy_next(ctypes.byref(policy), float(dirty_fraction))
+    return bool(d.take_full), bool(d.clear_bitmap)

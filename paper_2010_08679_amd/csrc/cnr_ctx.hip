@@ -148,4 +148,34 @@ int cnr_full_checkpoint_due(const double *sizes, uint32_t i) {
     return future_if_full <= future_if_incremental ? 1 : 0;
 }
 
+cnr_status cnr_policy_init(cnr_policy *p, cnr_policy_kind kind) {
+    if (!p || (kind != CNR_POLICY_ONE_SHOT && kind != CNR_POLICY_CONSECUTIVE && kind != CNR_POLICY_INTERMITTENT))
+        return CNR_E_INVALID;
+    p->kind = (int)kind;
+    p->n_history = 0;
+    for (uint32_t t = 0; t < CNR_POLICY_MAX_HISTORY; ++t) p->history[t] = 0.0;
+    return CNR_OK;
+}
+
+cnr_policy_decision cnr_policy_next(cnr_policy *p, double dirty_fraction) {
+    cnr_policy_decision d = {0, 0};
+    if (!p) return d;
+    switch (p->kind) {
+        case CNR_POLICY_CONSECUTIVE:
+            d.clear_bitmap = 1;
+            return d;
+        case CNR_POLICY_INTERMITTENT:
+            if (p->n_history >= CNR_POLICY_MAX_HISTORY || cnr_full_checkpoint_due(p->history, p->n_history)) {
+                d.take_full = 1;
+                d.clear_bitmap = 1;
+                p->n_history = 0;
+            } else {
+                p->history[p->n_history++] = dirty_fraction;
+            }
+            return d;
+        default:  // one-shot: the bitmap keeps accumulating since the baseline
+            return d;
+    }
+}
+
 }  // extern "C"
