@@ -37,9 +37,10 @@
  *   table     float [n_rows][dim], row-major, 16-byte aligned base, dim % 4 == 0
  *   bitmap    uint32 [cnr_bitmap_words(n_rows)]; row i is bit (i & 31) of word (i >> 5);
  *             8-byte aligned base; bits at positions >= n_rows are ignored
- *   row_ids   uint32 [n], strictly ascending when produced by cnr_compact_dirty
+ *   row_ids   uint32 [n], strictly ascending when produced by cnr_compact_dirty; 16-byte aligned
+ *             base where cnr_quantize_rows or cnr_restore_rows reads it
  *   scale,    float [n]: scale = (hi - lo) / (2^bits - 1) and bias = lo (the zero_point) of
- *   bias      row_ids[k]'s range [lo, hi]
+ *   bias      row_ids[k]'s range [lo, hi]; 16-byte aligned base where cnr_restore_rows reads them
  *   packed    uint8 [n][cnr_packed_row_bytes(dim, bits)], rows back to back without padding; per
  *             row one little-endian bit stream in which element j occupies stream bits
  *             [j*bits, (j+1)*bits), least-significant code bit first (stream bit t is bit

@@ -114,3 +114,66 @@ class TableCheckpointer:
                                                out.row_ids, out.n_dev, self.capacity, out.bits, out.packed,
                                                out.scale, out.bias, stream)))
         return steps
+
+
+class HostCheckpointWriter:
+    """Chunked encode with the device-to-host copy of chunk c overlapping the encode of chunk c+1
+    (Section 4.4 and 5.2: the optimized checkpoint is built chunk by chunk and every finished chunk
+    is handed on while the next one is being quantized).
+
+    Two device staging buffers of ``chunk_rows`` rows take the encoder's output in turn; a copy
+    stream moves each finished chunk into pinned host memory (where a storage writer would pick it
+    up).  Streams have the default priority.  Plumbing only: the encode itself is
+    ``cnr_quantize_rows`` on a slice of the dirty-row list."""
+
+    def __init__(self, ctx, dim: int, bits: int, capacity: int, chunk_rows: int = 1 << 18, device="cuda:0"):
+        if chunk_rows % 16:
+            raise ValueError("chunk_rows must be a multiple of 16 (keeps every slice 16-byte aligned)")
+        self.ctx, self.dim, self.bits, self.capacity, self.chunk = ctx, dim, bits, int(capacity), int(chunk_rows)
+        self.prb = B.cnr_packed_row_bytes(dim, bits)
+        dev = torch.device(device)
+        self.stage = [dict(scale=torch.empty(self.chunk, dtype=torch.float32, device=dev),
+                           bias=torch.empty(self.chunk, dtype=torch.float32, device=dev),
+                           packed=torch.empty(self.chunk * self.prb, dtype=torch.uint8, device=dev))
+                      for _ in range(2)]
+        cap = max(1, self.capacity)
+        self.host = dict(row_ids=torch.empty(cap, dtype=torch.int32, pin_memory=True),
+                         scale=torch.empty(cap, dtype=torch.float32, pin_memory=True),
+                         bias=torch.empty(cap, dtype=torch.float32, pin_memory=True),
+                         packed=torch.empty(cap * self.prb, dtype=torch.uint8, pin_memory=True))
+        self.copy_stream = torch.cuda.Stream(device=dev)
+        self.n_host = torch.zeros(1, dtype=torch.int64, pin_memory=True)
+
+    def encode_to_host(self, ck: TableCheckpointer, table: torch.Tensor, mode: int = B.CNR_RANGE_MINMAX,
+                       greedy=None, overlap: bool = True) -> int:
+        """Encodes the rows listed by ``ck.compact()`` and leaves ids, scale, bias and packed codes in
+        the pinned host buffers; returns the number of rows.  Synchronises at the start (the row
+        count has to reach the host to size the copies) and at the end."""
+        main = torch.cuda.current_stream()
+        self.n_host.copy_(ck.n_dirty, non_blocking=True)
+        main.synchronize()
+        n = min(int(self.n_host.item()), ck.capacity, self.capacity)
+        copied = [None, None]                                    # event: staging buffer free again
+        copier = self.copy_stream if overlap else main
+        for c, k0 in enumerate(range(0, n, self.chunk)):
+            m = min(self.chunk, n - k0)
+            st = self.stage[c & 1]
+            if copied[c & 1] is not None:
+                main.wait_event(copied[c & 1])
+            B.cnr_quantize_rows(self.ctx, table, ck.n_rows, self.dim, ck.row_ids[k0:k0 + m], None, m, self.bits,
+                                mode, greedy, st["scale"], st["bias"], packed=st["packed"], stream=main)
+            ready = torch.cuda.Event()
+            ready.record(main)
+            copier.wait_event(ready)
+            with torch.cuda.stream(copier):
+                self.host["row_ids"][k0:k0 + m].copy_(ck.row_ids[k0:k0 + m], non_blocking=True)
+                self.host["scale"][k0:k0 + m].copy_(st["scale"][:m], non_blocking=True)
+                self.host["bias"][k0:k0 + m].copy_(st["bias"][:m], non_blocking=True)
+                self.host["packed"][k0 * self.prb:(k0 + m) * self.prb].copy_(st["packed"][:m * self.prb],
+                                                                            non_blocking=True)
+                done = torch.cuda.Event()
+                done.record(copier)
+            copied[c & 1] = done
+        copier.synchronize()
+        main.synchronize()
+        return n

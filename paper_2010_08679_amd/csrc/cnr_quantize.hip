@@ -686,7 +686,7 @@ cnr_status cnr_quantize_rows(cnr_ctx *ctx, const float *table, uint64_t n_rows, 
     if (!table || !scale || !bias || n_rows == 0 || n_rows >= (1ull << 32)) return CNR_E_INVALID;
     if (((uintptr_t)table % 16) || ((uintptr_t)packed % 16) || ((uintptr_t)codes_u8 % 4) ||
         ((uintptr_t)scale % 4) || ((uintptr_t)bias % 4) || ((uintptr_t)row_min % 4) ||
-        ((uintptr_t)row_max % 4) || ((uintptr_t)row_ids % 4) || ((uintptr_t)n_dev % 8))
+        ((uintptr_t)row_max % 4) || ((uintptr_t)row_ids % 16) || ((uintptr_t)n_dev % 8))
         return CNR_E_ALIGN;
     QuantArgs a;
     a.table = table; a.n_rows = n_rows; a.dim = dim; a.row_ids = row_ids; a.n_dev = n_dev; a.n_max = n_max;

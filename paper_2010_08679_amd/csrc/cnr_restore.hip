@@ -333,8 +333,8 @@ extern "C" cnr_status cnr_restore_rows(cnr_ctx *ctx, float *table, uint64_t n_ro
     if (dim == 0 || dim % 4 || dim > CNR_MAX_DIM || ((uint64_t)dim * (uint64_t)bits) % 8) return CNR_E_DIM;
     if (n_max == 0) return CNR_OK;
     if (!table || !packed || !scale || !bias || n_rows == 0 || n_rows >= (1ull << 32)) return CNR_E_INVALID;
-    if (((uintptr_t)table % 16) || ((uintptr_t)packed % 16) || ((uintptr_t)scale % 4) ||
-        ((uintptr_t)bias % 4) || ((uintptr_t)row_ids % 4) || ((uintptr_t)n_dev % 8))
+    if (((uintptr_t)table % 16) || ((uintptr_t)packed % 16) || ((uintptr_t)scale % 16) ||
+        ((uintptr_t)bias % 16) || ((uintptr_t)row_ids % 16) || ((uintptr_t)n_dev % 8))
         return CNR_E_ALIGN;
     hipStream_t s = as_stream(stream);
     switch (bits) {

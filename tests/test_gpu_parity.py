@@ -412,3 +412,39 @@ def test_greedy_parameter_selection_matches_oracle(ctx):
     assert choice == want_choice
     assert report[("bins", choice[0])] < report["naive"]
     _poll_clean(ctx)
+
+
+# ------------------------------------------------------------------ chunked encode with overlapped copies
+
+@pytest.mark.parametrize("overlap", [True, False])
+def test_chunked_encode_to_host_equals_one_shot_encode(ctx, overlap):
+    # Sections 4.4 / 5.2: the checkpoint is built chunk by chunk, each chunk handed on while the next
+    # is quantized.  The chunks must add up to exactly the unchunked result.
+    n_rows, dim, bits = 300_000, 64, 4
+    gt = GpuTable(ctx, _table(n_rows, dim, 8))
+    _dirty(gt, 0.3, 4)
+    enc = gt.ck.alloc_output(bits)
+    gt.ck.encode(gt.table, enc)
+    n = enc.count()
+    writer = P.HostCheckpointWriter(ctx, dim, bits, capacity=n_rows, chunk_rows=16 * 1000, device=DEV)
+    for _ in range(2):                                          # staging buffers are reused across calls
+        got_n = writer.encode_to_host(gt.ck, gt.table, overlap=overlap)
+        assert got_n == n and n > 5 * writer.chunk and n % writer.chunk != 0
+        prb = P.cnr_packed_row_bytes(dim, bits)
+        assert torch.equal(writer.host["row_ids"][:n], enc.row_ids[:n].cpu())
+        assert torch.equal(writer.host["scale"][:n], enc.scale[:n].cpu())
+        assert torch.equal(writer.host["bias"][:n], enc.bias[:n].cpu())
+        assert torch.equal(writer.host["packed"][:n * prb], enc.packed[:n * prb].cpu())
+    ora = O.quantize_rows(gt.host, u32(enc.row_ids)[:n], bits, n_threads=8)
+    assert np.array_equal(writer.host["scale"][:n].numpy(), ora["scale"])
+    assert np.mean(O.unpack(writer.host["packed"][:n * prb].numpy(), dim, bits) != ora["codes"]) <= 1e-4
+    _poll_clean(ctx)
+
+
+def test_misaligned_row_id_slice_is_refused(ctx):
+    t = torch.zeros((64, 64), device=DEV)
+    ids = torch.arange(64, dtype=torch.int32, device=DEV)
+    s = torch.zeros(64, device=DEV)
+    with pytest.raises(P.CnrError) as e:
+        P.cnr_quantize_rows(ctx, t, 64, 64, ids[1:], None, 32, 4, P.CNR_RANGE_MINMAX, None, s, s)
+    assert e.value.status == P.CNR_E_ALIGN
