@@ -448,3 +448,59 @@ def test_misaligned_row_id_slice_is_refused(ctx):
     with pytest.raises(P.CnrError) as e:
         P.cnr_quantize_rows(ctx, t, 64, 64, ids[1:], None, 32, 4, P.CNR_RANGE_MINMAX, None, s, s)
     assert e.value.status == P.CNR_E_ALIGN
+
+
+# ------------------------------------------------------------------ graph capture
+
+def test_checkpoint_step_replays_from_a_hip_graph(ctx):
+    # the whole step (clear, mark, compact, encode, restore) only enqueues kernels on the caller's
+    # stream, allocates nothing and never synchronises, so it can be captured once and replayed; the
+    # inputs are refreshed in place between replays and every replay is checked against the oracle
+    n_rows, dim, bits = 120_000, 64, 4
+    gt = GpuTable(ctx, _table(n_rows, dim, 40))
+    scratch = P.TableCheckpointer.new_mark_scratch(n_rows, DEV)
+    ck = P.TableCheckpointer(ctx, n_rows, dim, device=DEV, mark_scratch=scratch)
+    enc = ck.alloc_output(bits)
+    idx = synth.bernoulli_lookup_stream(n_rows, 0.25, 1, DEV)
+    n_idx = idx.numel()
+    stale = torch.zeros_like(gt.table)
+
+    def step():
+        ck.clear()
+        ck.mark(idx)
+        ck.compact()
+        ck.encode(gt.table, enc)
+        ck.restore(stale, enc)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                                  # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        # eager work between replays: new look-ups (same length), new table values, a dirtied target
+        fresh = synth.bernoulli_lookup_stream(n_rows, 0.25, 10 + rep, DEV)
+        m = min(n_idx, fresh.numel())
+        idx[:m].copy_(fresh[:m])
+        idx[m:] = fresh[0]
+        gt.table.mul_(1.0 + 0.1 * (rep + 1))
+        stale.fill_(float(rep))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        host = gt.table.cpu().numpy()
+        bm, ids, n, _ = _oracle_track(n_rows, [idx.cpu().numpy()])
+        assert int(ck.n_dirty.item()) == n and np.array_equal(u32(ck.row_ids)[:n], ids)
+        ora = O.quantize_rows(host, ids, bits, n_threads=8)
+        assert np.array_equal(enc.scale.cpu().numpy()[:n], ora["scale"])
+        packed = enc.packed.cpu().numpy()[:n * 32].reshape(n, 32)
+        assert np.mean(O.unpack(packed, dim, bits) != ora["codes"]) <= 1e-4
+        want = np.full_like(host, float(rep))
+        O.restore_rows(want, ids, bits, packed, ora["scale"], ora["bias"])
+        assert np.array_equal(stale.cpu().numpy(), want)
+        assert not scratch.any()
+    _poll_clean(ctx)
