@@ -114,3 +114,17 @@ def test_synthetic_inputs_are_seeded_and_shaped():
     w2 = synth.WORKLOADS["cfg2"]
     it = list(synth.lookup_batches(w2, 0, 1, "cpu", n_rows=10_000, iterations=3))
     assert len(it) == 3 and it[0].numel() == 2048 * 20
+
+
+def test_header_is_plain_c_and_every_export_links(tmp_path):
+    import subprocess
+    P.load()
+    exe = str(tmp_path / "abi_check")
+    pkg = os.path.join(ROOT, "paper_2010_08679_amd")
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                           os.path.join(ROOT, "tests", "c", "abi_check.c"), "-o", exe, "-L", pkg, "-lcnr",
+                           "-Wl,-rpath," + pkg, "-Wl,-rpath,/opt/rocm/lib", "-L/opt/rocm/lib"])
+    out = subprocess.run([exe], capture_output=True, text=True)
+    assert out.returncode == 0, (out.returncode, out.stdout, out.stderr)
+    n = int(out.stdout.split(":")[1].split()[0])
+    assert n == len(binding.EXPORTS)
