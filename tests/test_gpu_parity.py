@@ -504,3 +504,53 @@ def test_checkpoint_step_replays_from_a_hip_graph(ctx):
         assert np.array_equal(stale.cpu().numpy(), want)
         assert not scratch.any()
     _poll_clean(ctx)
+
+
+# ------------------------------------------------------------------ further edges
+
+@pytest.mark.parametrize("bits", BITS)
+def test_largest_supported_row_dimension(ctx, bits):
+    dim, n_rows = P.CNR_MAX_DIM, 300
+    gt = GpuTable(ctx, _table(n_rows, dim, 60 + bits))
+    got = gpu_encode_all_outputs(gt, bits, row_ids=None, n=n_rows)
+    ora = O.quantize_rows(gt.host, None, bits, n_threads=8)
+    for k in ("scale", "bias", "row_min", "row_max"):
+        assert np.array_equal(got[k], ora[k])
+    assert np.array_equal(got["codes"], ora["codes"])          # the generic kernel divides like F_Q
+    assert np.array_equal(got["packed"], O.pack(ora["codes"], bits))
+    d = got["dev"]
+    stale = torch.zeros_like(gt.table)
+    P.cnr_restore_rows(ctx, stale, n_rows, dim, None, None, n_rows, bits, d["packed"], d["scale"], d["bias"])
+    assert np.array_equal(stale.cpu().numpy(), O.dequantize(ora["codes"], ora["scale"], ora["bias"]))
+    t = torch.zeros((4, dim + 4), device=DEV)
+    s = torch.zeros(4, device=DEV)
+    with pytest.raises(P.CnrError) as e:
+        P.cnr_quantize_rows(ctx, t, 4, dim + 4, None, None, 4, bits, P.CNR_RANGE_MINMAX, None, s, s)
+    assert e.value.status == P.CNR_E_DIM
+    _poll_clean(ctx)
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("dim", [64, 128, 256, 24])
+def test_symmetric_range(ctx, bits, dim):
+    n_rows = 2500
+    t = _table(n_rows, dim, 70 + bits) + 0.02                  # shifted: the symmetric range wastes codes
+    gt = GpuTable(ctx, t)
+    got = gpu_encode_all_outputs(gt, bits, mode=P.CNR_RANGE_SYMMETRIC, row_ids=None, n=n_rows)
+    ora = O.quantize_rows(gt.host, None, bits, mode=O.RANGE_SYMMETRIC, n_threads=8)
+    compare_quantized(gt.host, got, ora, bits, what="symmetric b%d d%d" % (bits, dim))
+    assert np.array_equal(got["bias"], -np.abs(gt.host).max(axis=1))
+    assert np.array_equal(got["packed"], O.pack(got["codes"], bits))
+
+
+def test_row_count_limit_is_checked_on_the_host(ctx):
+    bm = torch.zeros(4, dtype=torch.int32, device=DEV)
+    idx = torch.zeros(4, dtype=torch.int64, device=DEV)
+    with pytest.raises(P.CnrError) as e:
+        P.cnr_mark_touched(ctx, bm, 1 << 32, idx)
+    assert e.value.status == P.CNR_E_INVALID
+    t = torch.zeros((4, 64), device=DEV)
+    s = torch.zeros(4, device=DEV)
+    with pytest.raises(ValueError):                            # the binding's own size check comes first
+        P.cnr_quantize_rows(ctx, t, 1 << 32, 64, None, None, 4, 4, P.CNR_RANGE_MINMAX, None, s, s)
+    _poll_clean(ctx)
