@@ -41,8 +41,8 @@ ISSUE_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # one vector instruction per lane
 # per dirty row, valid only for the kernel source whose hash is recorded with it.
 TRAFFIC_PER_ROW = {
     # sha256 of csrc/cnr_quantize.hip : (workload, bytes per dirty row)
-    # (2.000 * 190509.7 KiB FETCH_SIZE + 1.000 * 59390.9 KiB WRITE_SIZE) / 1,500,122 rows
-    "92df14c799119a13681fbee14933773da8e8e2c4d75fcf69e9da00a998eeebed": ("cfg4/b4", 300.63),
+    # (2.000 * 190509.1 KiB FETCH_SIZE + 1.000 * 59280.8 KiB WRITE_SIZE) / 1,500,122 rows
+    "9a8c00bbb087e21e32103e1e1414955c8945a7d3247ec8494706fcbe66460e37": ("cfg4/b4", 300.55),
 }
 
 
@@ -166,6 +166,15 @@ def main() -> int:
         step(stage_timer, stage_labels)
     torch.cuda.synchronize()
 
+    # what an event pair around nothing reads: the part of avg_launch_ms that is not the kernel
+    null_timer = Timer(("null",), 64)
+    for _ in range(64):
+        a, b = null_timer.span("null")
+        a.record()
+        b.record()
+    torch.cuda.synchronize()
+    null_ms = null_timer.totals_ms()["null"] / 64
+
     ms_per_step = wall * 1e3 / args.steps
     table_bytes = sum(n_dirty) * w.dim * 4
     value = table_bytes / (ms_per_step * 1e-3) / 1e9
@@ -184,7 +193,8 @@ def main() -> int:
     roofline = {"bound": "hbm", "kernel": "quantize_rows16_kernel<%d, %d>" % (w.dim // 64, bits),
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                "bytes_per_launch": int(enc_bytes), "avg_launch_ms": round(enc_launch_ms, 5)}
+                "bytes_per_launch": int(enc_bytes), "avg_launch_ms": round(enc_launch_ms, 5),
+                "empty_event_pair_ms": round(null_ms, 5)}
     res_ms = stage_timer.totals_ms()["restore"] / stage_timer.counts()["restore"]
     res_bytes = restore_bytes_per_row(w.dim, bits) * rows_per_launch
     stages = {k: round(v, 4) for k, v in stage_ms.items()}
