@@ -41,8 +41,8 @@ ISSUE_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # one vector instruction per lane
 # per dirty row, valid only for the kernel source whose hash is recorded with it.
 TRAFFIC_PER_ROW = {
     # sha256 of csrc/cnr_quantize.hip : (workload, bytes per dirty row)
-    # (2.000 * 190509.1 KiB FETCH_SIZE + 1.000 * 59280.8 KiB WRITE_SIZE) / 1,500,122 rows
-    "9a8c00bbb087e21e32103e1e1414955c8945a7d3247ec8494706fcbe66460e37": ("cfg4/b4", 300.55),
+    # (2.000 * 1529513.9 KiB FETCH_SIZE + 1.000 * 472806.4 KiB WRITE_SIZE) / 12,000,978 rows of one launch
+    "51a81e26dda74ed3af26f841305040cc5bb4f1892c2a6c73d307dc33550e7d63": ("cfg4/b4", 301.36),
 }
 
 
@@ -90,6 +90,8 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg4", choices=sorted(synth.WORKLOADS))
     ap.add_argument("--tables", type=int, default=0, help="use only the first N tables (0 = all)")
     ap.add_argument("--bits", type=int, default=4)
+    ap.add_argument("--per-table", action="store_true",
+                    help="one library call per table and stage instead of one batched call per stage")
     ap.add_argument("--no-greedy", action="store_true", help="skip the greedy-range extra")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--no-host-copy", action="store_true", help="skip the chunked encode-to-host extra")
@@ -112,7 +114,10 @@ def main() -> int:
 
     # ---- resident inputs ------------------------------------------------------------------------
     tables, streams, cks, encs = [], [], [], []
-    mark_scratch = P.TableCheckpointer.new_mark_scratch(w.n_rows, dev)   # shared by all tables
+    batched = not args.per_table
+    # per-table calls run one after the other and can share the flag-byte scratch of the bulk mark
+    # and the stale table that restore writes into; batched calls work on all tables at once
+    shared_scratch = None if batched else P.TableCheckpointer.new_mark_scratch(w.n_rows, dev)
     for ti in range(n_tables):
         tables.append(synth.make_table(w, ti, args.seed, dev))
         if w.lookups == "bernoulli":
@@ -120,17 +125,23 @@ def main() -> int:
         else:
             batches = list(synth.lookup_batches(w, ti, args.seed, dev, iterations=min(w.iterations or 8, 64)))
         streams.append(torch.cat([b.reshape(-1) for b in batches]))
-        ck = P.TableCheckpointer(ctx, w.n_rows, w.dim, device=dev, mark_scratch=mark_scratch)
+        scratch = P.TableCheckpointer.new_mark_scratch(w.n_rows, dev) if batched else shared_scratch
+        ck = P.TableCheckpointer(ctx, w.n_rows, w.dim, device=dev, mark_scratch=scratch)
         cks.append(ck)
         encs.append(ck.alloc_output(bits))
-    stale = torch.zeros((w.n_rows, w.dim), dtype=torch.float32, device=dev)
+    stale = [torch.zeros((w.n_rows, w.dim), dtype=torch.float32, device=dev) for _ in range(n_tables if batched else 1)]
     torch.cuda.synchronize()
 
     # one checkpoint of every table as a flat list of prepared launches (arguments resolved once, so
     # that the host keeps ahead of the GPU)
-    calls = []
-    for ti in range(n_tables):
-        calls += cks[ti].prepare_step(streams[ti], tables[ti], encs[ti], restore_into=stale)
+    if batched:
+        batch = P.BatchCheckpointer(ctx, cks)
+        calls = batch.prepare_step(streams, tables, encs, restore_into=stale)
+    else:
+        calls = []
+        for ti in range(n_tables):
+            calls += cks[ti].prepare_step(streams[ti], tables[ti], encs[ti], restore_into=stale[0])
+    launches_per_stage = 1 if batched else n_tables
 
     def step(timer, bracket):
         for label, fn in calls:
@@ -149,9 +160,9 @@ def main() -> int:
     assert (st, bad, flags) == (P.CNR_OK, 0, 0), (st, bad, flags)
     n_dirty = [int(c.n_dirty.item()) for c in cks]
 
-    # timed region: only the dominant kernel is bracketed by events (two event records per table),
-    # so that the host issues the 56 launches of a step faster than the GPU runs them
-    timer = Timer(("encode",), args.steps * n_tables)
+    # timed region: only the dominant kernel is bracketed by events, so that the host issues the
+    # launches of a step faster than the GPU runs them
+    timer = Timer(("encode",), args.steps * launches_per_stage)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -161,7 +172,7 @@ def main() -> int:
 
     # per-stage split from a second, untimed run of the same steps with every launch bracketed
     stage_labels = ("clear", "mark", "compact", "encode", "restore")
-    stage_timer = Timer(stage_labels, args.steps * n_tables)
+    stage_timer = Timer(stage_labels, args.steps * launches_per_stage)
     for _ in range(args.steps):
         step(stage_timer, stage_labels)
     torch.cuda.synchronize()
@@ -183,7 +194,7 @@ def main() -> int:
 
     # dominant kernel: the fused gather + quantize + pack
     enc_launch_ms = timer.totals_ms()["encode"] / launches["encode"]
-    rows_per_launch = sum(n_dirty) / n_tables
+    rows_per_launch = sum(n_dirty) / launches_per_stage
     enc_bytes = encode_bytes_per_row(w.dim, bits) * rows_per_launch
     achieved = enc_bytes / (enc_launch_ms * 1e-3) / 1e9
     traffic = None
@@ -208,9 +219,10 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": "%s: %d tables x %d rows x dim %d, %s values, %.1f%% dirty, %d-bit min/max "
-                               "range, step = clear+mark+compact+encode+restore per table"
+                               "range, step = clear+mark+compact+encode+restore of all tables, %s"
                                % (w.name, n_tables, w.n_rows, w.dim, w.values,
-                                  100.0 * sum(n_dirty) / (n_tables * w.n_rows), bits),
+                                  100.0 * sum(n_dirty) / (n_tables * w.n_rows), bits,
+                                  "one batched call per stage" if batched else "one call per table and stage"),
                    "dirty_rows": sum(n_dirty), "lookups_per_step": int(sum(s.numel() for s in streams)),
                    "index_dtype": "int64"},
         "roofline": roofline,
@@ -224,8 +236,11 @@ def main() -> int:
             a = torch.cuda.Event(enable_timing=True)
             b = torch.cuda.Event(enable_timing=True)
             a.record()
-            for ti in range(n_tables):
-                cks[ti].encode(tables[ti], encs[ti], mode=P.CNR_RANGE_GREEDY, greedy=(w.num_bins, w.ratio))
+            if batched:
+                batch.encode(tables, encs, mode=P.CNR_RANGE_GREEDY, greedy=(w.num_bins, w.ratio))
+            else:
+                for ti in range(n_tables):
+                    cks[ti].encode(tables[ti], encs[ti], mode=P.CNR_RANGE_GREEDY, greedy=(w.num_bins, w.ratio))
             b.record()
             torch.cuda.synchronize()
             g_ms.append(a.elapsed_time(b))

@@ -194,6 +194,56 @@ cnr_status cnr_quant_error(cnr_ctx *ctx, const float *table, uint64_t n_rows, ui
                            const uint8_t *packed, const float *scale, const float *bias, double *err,
                            double *mean_out, void *stream);
 
+/* ---- several tables per launch (Section 2.1: a GPU holds many embedding tables; Section 4.1: a
+ *      checkpoint covers every table of the GPU's shard) ------------------------------------------
+ *
+ * One cnr_table_job describes the buffers of one table; the *_batch calls take a host array of
+ * them (read during the call) and do for every job what the single-table call of the same name
+ * does, with the jobs of a call running side by side in as few launches as possible (one per
+ * CNR_MAX_BATCH jobs and kernel).  This matters where a call is short: the per-iteration mark of a
+ * few ten thousand indices, the clear, the compaction; and it lets the encode and restore kernels
+ * move from one table to the next without draining the GPU in between.  Results are identical to
+ * those of the single-table calls.  Buffers of different jobs of one call must not overlap (mark
+ * scratch included: one per job).  Every field has the meaning, layout and alignment of the
+ * argument of the same name of the single-table call; a call reads only the fields listed for it.
+ *   cnr_clear_bitmap_batch    bitmap, n_rows
+ *   cnr_mark_touched_batch    bitmap, n_rows, indices, n_indices, mark_scratch (all jobs one index type)
+ *   cnr_compact_dirty_batch   bitmap, n_rows, row_ids, capacity, n_dirty_dev, compact_scratch
+ *   cnr_quantize_rows_batch   table, n_rows, row_ids, n_dirty_dev (as n_dev, may be NULL), capacity
+ *                             (as n_max), scale, bias, row_min, row_max, codes_u8, packed; all jobs
+ *                             share dim, bits, mode and the greedy parameters
+ *   cnr_restore_rows_batch    table (written), n_rows, row_ids, n_dirty_dev, capacity, packed, scale,
+ *                             bias; all jobs share dim and bits
+ * Argument errors are reported for the whole call before anything is launched. */
+#define CNR_MAX_BATCH 16u
+
+typedef struct {
+    float *table;
+    uint64_t n_rows;
+    uint32_t *bitmap;
+    const void *indices;
+    uint64_t n_indices;
+    void *mark_scratch;
+    uint32_t *row_ids;
+    uint64_t capacity;
+    uint64_t *n_dirty_dev;
+    void *compact_scratch;
+    float *scale, *bias, *row_min, *row_max;
+    uint8_t *codes_u8, *packed;
+} cnr_table_job;
+
+cnr_status cnr_clear_bitmap_batch(cnr_ctx *ctx, const cnr_table_job *jobs /* host */, uint32_t n_jobs,
+                                  void *stream);
+cnr_status cnr_mark_touched_batch(cnr_ctx *ctx, const cnr_table_job *jobs /* host */, uint32_t n_jobs,
+                                  cnr_index_type type, void *stream);
+cnr_status cnr_compact_dirty_batch(cnr_ctx *ctx, const cnr_table_job *jobs /* host */, uint32_t n_jobs,
+                                   void *stream);
+cnr_status cnr_quantize_rows_batch(cnr_ctx *ctx, const cnr_table_job *jobs /* host */, uint32_t n_jobs,
+                                   uint32_t dim, int bits, cnr_range_mode mode,
+                                   const cnr_greedy_params *greedy /* host */, void *stream);
+cnr_status cnr_restore_rows_batch(cnr_ctx *ctx, const cnr_table_job *jobs /* host */, uint32_t n_jobs,
+                                  uint32_t dim, int bits, void *stream);
+
 /* ---- device-side conditions ---------------------------------------------------------------- */
 
 /* Waits for `stream`, then reports and resets what the kernels recorded since the last poll.

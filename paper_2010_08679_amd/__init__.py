@@ -8,5 +8,5 @@ The compute lives in ``csrc/`` (HIP, gfx950) and is reached only through ``libcn
 """
 from .binding import *  # noqa: F401,F403
 from .binding import CnrError, load  # noqa: F401
-from .checkpoint import EncodedRows, HostCheckpointWriter, TableCheckpointer  # noqa: F401
+from .checkpoint import BatchCheckpointer, EncodedRows, HostCheckpointWriter, TableCheckpointer  # noqa: F401
 from .autotune import select_greedy_params  # noqa: F401

@@ -24,6 +24,7 @@ CNR_IDX_I32, CNR_IDX_I64 = 0, 1
 CNR_RANGE_MINMAX, CNR_RANGE_GREEDY, CNR_RANGE_SYMMETRIC = 0, 1, 2
 CNR_FLAG_CAPACITY, CNR_FLAG_ROW_ID = 1, 2
 CNR_MAX_DIM = 4096
+CNR_MAX_BATCH = 16
 
 # Every symbol include/cnr.h declares.
 EXPORTS = (
@@ -32,6 +33,8 @@ EXPORTS = (
     "cnr_greedy_iterations", "cnr_clear_bitmap", "cnr_mark_touched", "cnr_compact_dirty",
     "cnr_quantize_rows", "cnr_pack", "cnr_restore_rows", "cnr_quant_error", "cnr_poll_errors", "cnr_status_str",
     "cnr_last_hip_error", "cnr_full_checkpoint_due", "cnr_policy_init", "cnr_policy_next",
+    "cnr_clear_bitmap_batch", "cnr_mark_touched_batch", "cnr_compact_dirty_batch", "cnr_quantize_rows_batch",
+    "cnr_restore_rows_batch",
 )
 
 
@@ -56,6 +59,16 @@ class cnr_policy_decision(ctypes.Structure):
 
 class cnr_greedy_params(ctypes.Structure):
     _fields_ = [("num_bins", ctypes.c_uint32), ("ratio", ctypes.c_float)]
+
+
+class cnr_table_job(ctypes.Structure):
+    """One table's buffers for the ``*_batch`` calls (field for field the C struct)."""
+    _fields_ = [("table", ctypes.c_void_p), ("n_rows", ctypes.c_uint64), ("bitmap", ctypes.c_void_p),
+                ("indices", ctypes.c_void_p), ("n_indices", ctypes.c_uint64), ("mark_scratch", ctypes.c_void_p),
+                ("row_ids", ctypes.c_void_p), ("capacity", ctypes.c_uint64), ("n_dirty_dev", ctypes.c_void_p),
+                ("compact_scratch", ctypes.c_void_p), ("scale", ctypes.c_void_p), ("bias", ctypes.c_void_p),
+                ("row_min", ctypes.c_void_p), ("row_max", ctypes.c_void_p), ("codes_u8", ctypes.c_void_p),
+                ("packed", ctypes.c_void_p)]
 
 
 _lock = threading.Lock()
@@ -96,6 +109,12 @@ def load() -> ctypes.CDLL:
             "cnr_full_checkpoint_due": (i32, [ctypes.POINTER(ctypes.c_double), u32]),
             "cnr_policy_init": (i32, [ctypes.POINTER(cnr_policy), i32]),
             "cnr_policy_next": (cnr_policy_decision, [ctypes.POINTER(cnr_policy), ctypes.c_double]),
+            "cnr_clear_bitmap_batch": (i32, [vp, ctypes.POINTER(cnr_table_job), u32, vp]),
+            "cnr_mark_touched_batch": (i32, [vp, ctypes.POINTER(cnr_table_job), u32, i32, vp]),
+            "cnr_compact_dirty_batch": (i32, [vp, ctypes.POINTER(cnr_table_job), u32, vp]),
+            "cnr_quantize_rows_batch": (i32, [vp, ctypes.POINTER(cnr_table_job), u32, u32, i32, i32,
+                                              ctypes.POINTER(cnr_greedy_params), vp]),
+            "cnr_restore_rows_batch": (i32, [vp, ctypes.POINTER(cnr_table_job), u32, u32, i32, vp]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(lib, name)
@@ -257,6 +276,70 @@ def cnr_quant_error(ctx, table, n_rows: int, dim: int, row_ids, n_dev, n_max: in
                                   _dev(scale, F32, "scale"), _dev(bias, F32, "bias"),
                                   _dev(err, torch.float64, "err"), _dev(mean_out, torch.float64, "mean_out"),
                                   _stream(stream)), "cnr_quant_error")
+
+
+# ---- several tables per launch -------------------------------------------------------------------
+
+_JOB_TENSORS = {"table": F32, "bitmap": U32, "indices": None, "mark_scratch": None, "row_ids": U32,
+                "n_dirty_dev": U64, "compact_scratch": None, "scale": F32, "bias": F32, "row_min": F32,
+                "row_max": F32, "codes_u8": U8, "packed": U8}
+
+
+def make_jobs(jobs):
+    """A ctypes array of ``cnr_table_job`` from a list of dicts.  Keys are the struct's field names;
+    tensor-valued fields take GPU tensors (checked for dtype and contiguity, resolved to device
+    pointers here), ``n_rows`` / ``n_indices`` / ``capacity`` take ints; ``n_indices`` defaults to the
+    length of ``indices``.  The caller keeps the tensors alive while the array is in use."""
+    arr = (cnr_table_job * max(1, len(jobs)))()
+    for j, d in zip(arr, jobs):
+        unknown = set(d) - {f for f, _ in cnr_table_job._fields_}
+        if unknown:
+            raise KeyError("unknown cnr_table_job fields: %s" % sorted(unknown))
+        for name, dtype in _JOB_TENSORS.items():
+            t = d.get(name)
+            if t is not None:
+                p = _dev(t, t.dtype if dtype is None else dtype, name)
+                setattr(j, name, p.value)
+        j.n_rows = int(d.get("n_rows", 0))
+        j.capacity = int(d.get("capacity", 0))
+        idx = d.get("indices")
+        j.n_indices = int(d.get("n_indices", idx.numel() if idx is not None else 0))
+    return arr
+
+
+def _jobs_arg(jobs):
+    if isinstance(jobs, (list, tuple)):
+        return make_jobs(jobs), len(jobs)
+    return jobs, len(jobs)
+
+
+def cnr_clear_bitmap_batch(ctx, jobs, stream=None) -> None:
+    arr, n = _jobs_arg(jobs)
+    _check(load().cnr_clear_bitmap_batch(ctx, arr, n, _stream(stream)), "cnr_clear_bitmap_batch")
+
+
+def cnr_mark_touched_batch(ctx, jobs, index_type: int, stream=None) -> None:
+    arr, n = _jobs_arg(jobs)
+    _check(load().cnr_mark_touched_batch(ctx, arr, n, index_type, _stream(stream)), "cnr_mark_touched_batch")
+
+
+def cnr_compact_dirty_batch(ctx, jobs, stream=None) -> None:
+    arr, n = _jobs_arg(jobs)
+    _check(load().cnr_compact_dirty_batch(ctx, arr, n, _stream(stream)), "cnr_compact_dirty_batch")
+
+
+def cnr_quantize_rows_batch(ctx, jobs, dim: int, bits: int, mode: int, greedy=None, stream=None) -> None:
+    arr, n = _jobs_arg(jobs)
+    gp = None
+    if greedy is not None:
+        gp = ctypes.pointer(cnr_greedy_params(int(greedy[0]), float(greedy[1])))
+    _check(load().cnr_quantize_rows_batch(ctx, arr, n, dim, bits, mode, gp, _stream(stream)),
+           "cnr_quantize_rows_batch")
+
+
+def cnr_restore_rows_batch(ctx, jobs, dim: int, bits: int, stream=None) -> None:
+    arr, n = _jobs_arg(jobs)
+    _check(load().cnr_restore_rows_batch(ctx, arr, n, dim, bits, _stream(stream)), "cnr_restore_rows_batch")
 
 
 def cnr_poll_errors(ctx, stream=None):

@@ -116,6 +116,101 @@ class TableCheckpointer:
         return steps
 
 
+class BatchCheckpointer:
+    """Several tables of one row length checkpointed together: every stage is one ``*_batch`` call
+    (one launch per kernel for up to ``CNR_MAX_BATCH`` tables) instead of one call per table.
+
+    Built from per-table :class:`TableCheckpointer` objects, which keep owning the buffers; each
+    needs a mark scratch of its own if the bulk marking route is wanted (the tables of a batch are
+    marked side by side)."""
+
+    def __init__(self, ctx, checkpointers):
+        self.ctx = ctx
+        self.cks = list(checkpointers)
+        if not self.cks:
+            raise ValueError("no tables")
+        if len({c.dim for c in self.cks}) != 1:
+            raise ValueError("the tables of a batch share one row length")
+        self.dim = self.cks[0].dim
+        scratches = [c.mark_scratch.data_ptr() for c in self.cks if c.mark_scratch is not None]
+        if len(set(scratches)) != len(scratches):
+            raise ValueError("tables of a batch must not share a mark scratch")
+
+    def _track_fields(self, c):
+        return dict(n_rows=c.n_rows, bitmap=c.bitmap, mark_scratch=c.mark_scratch, row_ids=c.row_ids,
+                    capacity=c.capacity, n_dirty_dev=c.n_dirty, compact_scratch=c.scratch)
+
+    def jobs(self, indices=None, tables=None, outs=None):
+        """The job array for these tables; ``indices`` / ``tables`` / ``outs`` are per-table lists
+        (look-up tensors, fp32 tables, :class:`EncodedRows`) or None where a call does not need them."""
+        jobs = []
+        for i, c in enumerate(self.cks):
+            d = self._track_fields(c)
+            if indices is not None and indices[i] is not None:
+                d["indices"] = indices[i].reshape(-1)
+            if tables is not None:
+                if tables[i].numel() < c.n_rows * c.dim:
+                    raise ValueError("table %d smaller than n_rows * dim" % i)
+                d["table"] = tables[i]
+            if outs is not None:
+                o = outs[i]
+                cap = max(1, c.capacity)
+                if (o.scale.numel() < cap or o.bias.numel() < cap
+                        or o.packed.numel() < cap * B.cnr_packed_row_bytes(c.dim, o.bits)):
+                    raise ValueError("output %d too small for the table's capacity" % i)
+                d.update(scale=o.scale, bias=o.bias, row_min=o.row_min, row_max=o.row_max, packed=o.packed)
+            jobs.append(d)
+        return B.make_jobs(jobs)
+
+    @staticmethod
+    def _index_type(indices):
+        kinds = {t.dtype for t in indices if t is not None}
+        if len(kinds) > 1:
+            raise TypeError("the index streams of a batch share one dtype")
+        return B.CNR_IDX_I32 if kinds == {torch.int32} else B.CNR_IDX_I64
+
+    def clear(self, stream=None) -> None:
+        B.cnr_clear_bitmap_batch(self.ctx, self.jobs(), stream)
+
+    def mark(self, indices, stream=None) -> None:
+        B.cnr_mark_touched_batch(self.ctx, self.jobs(indices=indices), self._index_type(indices), stream)
+
+    def compact(self, stream=None) -> None:
+        B.cnr_compact_dirty_batch(self.ctx, self.jobs(), stream)
+
+    def encode(self, tables, outs, mode: int = B.CNR_RANGE_MINMAX, greedy=None, stream=None) -> None:
+        bits = outs[0].bits
+        if any(o.bits != bits for o in outs):
+            raise ValueError("the outputs of a batch share one bit-width")
+        B.cnr_quantize_rows_batch(self.ctx, self.jobs(tables=tables, outs=outs), self.dim, bits, mode, greedy,
+                                  stream)
+
+    def restore(self, tables, encs, stream=None) -> None:
+        """Writes the rows of ``encs[i]`` over the same rows of ``tables[i]``."""
+        B.cnr_restore_rows_batch(self.ctx, self.jobs(tables=tables, outs=encs), self.dim, encs[0].bits, stream)
+
+    def prepare_step(self, indices, tables, outs, restore_into=None, mode: int = B.CNR_RANGE_MINMAX,
+                     greedy=None, stream=None):
+        """One checkpoint of all tables (clear, mark, compact, encode and, when ``restore_into`` lists
+        one destination table per table, restore) as (label, zero-argument callable) pairs with the
+        job arrays built once."""
+        n = len(self.cks)
+        track = self.jobs(indices=indices)
+        enc = self.jobs(tables=tables, outs=outs)
+        kind = self._index_type(indices)
+        bits = outs[0].bits
+        steps = [
+            ("clear", B.prepare("cnr_clear_bitmap_batch", self.ctx, track, n, stream)),
+            ("mark", B.prepare("cnr_mark_touched_batch", self.ctx, track, n, kind, stream)),
+            ("compact", B.prepare("cnr_compact_dirty_batch", self.ctx, track, n, stream)),
+            ("encode", B.prepare("cnr_quantize_rows_batch", self.ctx, enc, n, self.dim, bits, mode, greedy, stream)),
+        ]
+        if restore_into is not None:
+            back = self.jobs(tables=restore_into, outs=outs)
+            steps.append(("restore", B.prepare("cnr_restore_rows_batch", self.ctx, back, n, self.dim, bits, stream)))
+        return steps
+
+
 class HostCheckpointWriter:
     """Chunked encode with the device-to-host copy of chunk c overlapping the encode of chunk c+1
     (Section 4.4 and 5.2: the optimized checkpoint is built chunk by chunk and every finished chunk

@@ -120,6 +120,41 @@ __device__ __forceinline__ double row16_sum(double v) {
     return v;
 }
 
+// Launch coordinates read from the hardware registers: the workgroup id arrives in a scalar
+// register, so everything derived from it stays out of the vector registers.
+__device__ __forceinline__ uint32_t wg_x() { return __builtin_amdgcn_workgroup_id_x(); }
+__device__ __forceinline__ uint32_t wg_y() { return __builtin_amdgcn_workgroup_id_y(); }
+__device__ __forceinline__ uint32_t tid_x() { return __builtin_amdgcn_workitem_id_x(); }
+// Workgroups along x of a grid of kBlock-thread workgroups.
+__device__ __forceinline__ uint32_t grid_x() { return __builtin_amdgcn_grid_size_x() / (uint32_t)kBlock; }
+// Index of this wave in a one-dimensional grid of kBlock-thread workgroups, in a scalar register.
+__device__ __forceinline__ uint32_t wave_in_grid() {
+    return wg_x() * kWavesPerBlock + (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid_x() / kWave));
+}
+
+// min(*n_dev, n_max) (n_max when n_dev is NULL), in scalar registers: the number of rows a kernel
+// works on when the count is only known on the device.
+__device__ __forceinline__ uint64_t live_rows(const uint64_t *n_dev, uint64_t n_max) {
+    uint64_t n = n_max;
+    if (n_dev) {
+        const uint64_t nd = *n_dev;
+        n = nd < n_max ? nd : n_max;
+    }
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)n);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(n >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// Work units (passes of one wave) of a persistent kernel are dealt out round-robin over the waves
+// of the grid, and the deal continues across the tables of a batch instead of starting again at
+// wave 0 for each: `carry` is the wave the next table's first unit goes to.  Returns this wave's
+// first unit of a table with `n_units` units (fewer than 2^32) and moves the carry on.
+__device__ __forceinline__ uint32_t first_unit(uint32_t wave, uint32_t n_waves, uint32_t n_units, uint32_t &carry) {
+    const uint32_t first = wave >= carry ? wave - carry : wave + n_waves - carry;
+    carry = (carry + n_units % n_waves) % n_waves;
+    return first;
+}
+
 __device__ __forceinline__ void raise_flag(cnr_dev_errors *err, unsigned flag) {
     atomicOr(&err->flags, flag);
 }

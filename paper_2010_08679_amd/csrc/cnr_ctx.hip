@@ -20,8 +20,8 @@ cnr_status cnr_enter(cnr_ctx *ctx) {
 }
 
 __global__ void __launch_bounds__(kBlock) fill_u32_kernel(uint32_t *p, uint64_t n, uint32_t v) {
-    uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+    uint64_t i = (uint64_t)wg_x() * kBlock + tid_x();
+    const uint64_t stride = (uint64_t)grid_x() * kBlock;
     for (; i < n; i += stride) p[i] = v;
 }
 
@@ -87,17 +87,6 @@ uint32_t cnr_greedy_iterations(uint32_t num_bins, float ratio) {
     if (!(want > 0.0)) return 0;
     double cap = (double)(num_bins - 1);
     return (uint32_t)(want < cap ? want : cap);
-}
-
-cnr_status cnr_clear_bitmap(cnr_ctx *ctx, uint32_t *bitmap, uint64_t n_rows, void *stream) {
-    cnr_status st = cnr_enter(ctx);
-    if (st != CNR_OK) return st;
-    if (n_rows == 0) return CNR_OK;
-    if (!bitmap || n_rows >= (1ull << 32)) return CNR_E_INVALID;
-    const uint64_t words = cnr_bitmap_words(n_rows);
-    hipLaunchKernelGGL(fill_u32_kernel, dim3(cnr_grid(ctx, words, kBlock * 4, 4)), dim3(kBlock), 0,
-                       as_stream(stream), bitmap, words, 0u);
-    return cnr_launch_status(ctx);
 }
 
 cnr_status cnr_poll_errors(cnr_ctx *ctx, void *stream, uint64_t *n_bad_indices, uint32_t *flags) {

@@ -30,14 +30,16 @@ struct QuantArgs {
     cnr_dev_errors *err;
 };
 
-__device__ __forceinline__ uint64_t row_count(const QuantArgs &a) {
-    uint64_t n = a.n_max;
-    if (a.n_dev) {
-        const uint64_t nd = *a.n_dev;
-        n = nd < a.n_max ? nd : a.n_max;
-    }
-    return n;
-}
+// The tables of one launch.  A persistent kernel works through them in order: a workgroup that has
+// run out of rows in one table goes on to the next at once, so the GPU is not drained and refilled
+// between tables.
+struct QuantBatch {
+    QuantArgs job[CNR_MAX_BATCH];
+    uint32_t n_jobs;
+    uint32_t n_waves;  // waves of the grid
+};
+
+__device__ __forceinline__ uint64_t row_count(const QuantArgs &a) { return live_rows(a.n_dev, a.n_max); }
 
 // Code of one element as a float in [0, qmax] (F_Q of Section 5.2: clip, subtract the zero point,
 // divide by the scale, round).
@@ -280,13 +282,12 @@ __device__ __forceinline__ void encode_batch(const QuantArgs &a, uint64_t k0, co
 #undef CNR_SEL4
 
 template <int M, int BITS>
-__global__ void __launch_bounds__(kBlock) quantize_rows16_kernel(const QuantArgs a) {
+__device__ __forceinline__ void encode_table(const QuantArgs &a, uint32_t n_waves, uint32_t &carry) {
     const uint64_t n = row_count(a);
-    const int lane = threadIdx.x & (kWave - 1);
+    const int lane = tid_x() & (kWave - 1);
     const uint64_t g4 = 4u * (uint64_t)(lane >> 4);  // first row of this lane's group within a batch
     const int l = lane & 15;                         // lane in group
-    const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
-    uint64_t batch = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    uint64_t batch = first_unit(wave_in_grid(), n_waves, (uint32_t)((n + 15u) / 16u), carry);
     if (batch * 16u >= n) return;
 
     RowBatch<M> cur, nxt;
@@ -305,6 +306,12 @@ __global__ void __launch_bounds__(kBlock) quantize_rows16_kernel(const QuantArgs
         batch = next;
         next = next2;
     }
+}
+
+template <int M, int BITS>
+__global__ void __launch_bounds__(kBlock) quantize_rows16_kernel(const QuantBatch b) {
+    uint32_t carry = 0;
+    for (uint32_t t = 0; t < b.n_jobs; ++t) encode_table<M, BITS>(b.job[t], b.n_waves, carry);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -350,18 +357,17 @@ __device__ __forceinline__ double lanes_sum(double v) {
 }
 
 template <int L, int BITS>
-__global__ void __launch_bounds__(kBlock) quantize_greedy_kernel(const QuantArgs a) {
+__device__ __forceinline__ void greedy_table(const QuantArgs &a, uint32_t n_waves, uint32_t &carry) {
     constexpr int DIM = 16 * L;
     constexpr int kRowsPerPass = kWave / L;
     constexpr float QMAXF = (float)((1 << BITS) - 1);
     constexpr float INV_QMAX = 1.0f / QMAXF;
     constexpr uint64_t P = (uint64_t)DIM * BITS / 8;  // packed bytes per row
     const uint64_t n = row_count(a);
-    const int lane = threadIdx.x & (kWave - 1);
+    const int lane = tid_x() & (kWave - 1);
     const int j = lane % L;  // lane within the row
-    const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
-    for (uint64_t pass = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave; pass * kRowsPerPass < n;
-         pass += n_waves) {
+    for (uint64_t pass = first_unit(wave_in_grid(), n_waves, (uint32_t)((n + kRowsPerPass - 1) / kRowsPerPass), carry);
+         pass * kRowsPerPass < n; pass += n_waves) {
         const uint64_t k = pass * kRowsPerPass + lane / L;
         // ---- gather
         uint64_t rid = 0;
@@ -503,6 +509,12 @@ __global__ void __launch_bounds__(kBlock) quantize_greedy_kernel(const QuantArgs
     }
 }
 
+template <int L, int BITS>
+__global__ void __launch_bounds__(kBlock) quantize_greedy_kernel(const QuantBatch b) {
+    uint32_t carry = 0;
+    for (uint32_t t = 0; t < b.n_jobs; ++t) greedy_table<L, BITS>(b.job[t], b.n_waves, carry);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Any other dim (dim % 4 == 0, dim * bits % 8 == 0): one wavefront per row, lanes stride over the
 // row, which is re-read from cache for each pass.  Output bytes are produced one per lane-visit
@@ -545,10 +557,10 @@ quantize_rows_generic_kernel(const float *__restrict__ table, uint64_t n_rows, u
         const uint64_t nd = *n_dev;
         n = nd < n_max ? nd : n_max;
     }
-    const int lane = threadIdx.x & (kWave - 1);
-    const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
+    const int lane = tid_x() & (kWave - 1);
+    const uint64_t n_waves = (uint64_t)grid_x() * kWavesPerBlock;
     const uint64_t P = (uint64_t)dim * BITS / 8;
-    for (uint64_t k = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave; k < n; k += n_waves) {
+    for (uint64_t k = (uint64_t)wg_x() * kWavesPerBlock + tid_x() / kWave; k < n; k += n_waves) {
         const uint64_t r = row_ids ? (uint64_t)row_ids[k] : k;
         if (r >= n_rows) {  // uniform over the wave
             if (lane == 0) raise_flag(err, CNR_FLAG_ROW_ID);
@@ -625,8 +637,8 @@ pack_kernel(const uint8_t *__restrict__ codes, const uint64_t *__restrict__ n_de
     }
     const uint64_t P = (uint64_t)dim * BITS / 8;
     const uint64_t total = n * P;
-    const uint64_t stride = (uint64_t)gridDim.x * kBlock;
-    for (uint64_t o = (uint64_t)blockIdx.x * kBlock + threadIdx.x; o < total; o += stride) {
+    const uint64_t stride = (uint64_t)grid_x() * kBlock;
+    for (uint64_t o = (uint64_t)wg_x() * kBlock + tid_x(); o < total; o += stride) {
         const uint64_t k = o / P, b = o - k * P;
         const uint8_t *row = codes + k * (uint64_t)dim;
         const uint32_t first = (uint32_t)((8 * b) / BITS);
@@ -641,68 +653,109 @@ pack_kernel(const uint8_t *__restrict__ codes, const uint64_t *__restrict__ n_de
     }
 }
 
+uint64_t most_rows(const QuantBatch &b) {
+    uint64_t m = 0;
+    for (uint32_t t = 0; t < b.n_jobs; ++t)
+        if (b.job[t].n_max > m) m = b.job[t].n_max;
+    return m;
+}
+
 template <int M, int BITS>
-void launch_rows16(cnr_ctx *ctx, const QuantArgs &a, hipStream_t s) {
-    const unsigned grid = cnr_grid(ctx, a.n_max, 16u * kWavesPerBlock,
+void launch_rows16(cnr_ctx *ctx, QuantBatch &b, hipStream_t s) {
+    const unsigned grid = cnr_grid(ctx, most_rows(b), 16u * kWavesPerBlock,
                                    cnr_resident_blocks_per_cu<quantize_rows16_kernel<M, BITS>>());
-    hipLaunchKernelGGL((quantize_rows16_kernel<M, BITS>), dim3(grid), dim3(kBlock), 0, s, a);
+    b.n_waves = grid * kWavesPerBlock;
+    hipLaunchKernelGGL((quantize_rows16_kernel<M, BITS>), dim3(grid), dim3(kBlock), 0, s, b);
 }
 
 template <int L, int BITS>
-void launch_greedy(cnr_ctx *ctx, const QuantArgs &a, hipStream_t s) {
-    const unsigned grid = cnr_grid(ctx, a.n_max, (uint64_t)(kWave / L) * kWavesPerBlock,
+void launch_greedy(cnr_ctx *ctx, QuantBatch &b, hipStream_t s) {
+    const unsigned grid = cnr_grid(ctx, most_rows(b), (uint64_t)(kWave / L) * kWavesPerBlock,
                                    cnr_resident_blocks_per_cu<quantize_greedy_kernel<L, BITS>>());
-    hipLaunchKernelGGL((quantize_greedy_kernel<L, BITS>), dim3(grid), dim3(kBlock), 0, s, a);
+    b.n_waves = grid * kWavesPerBlock;
+    hipLaunchKernelGGL((quantize_greedy_kernel<L, BITS>), dim3(grid), dim3(kBlock), 0, s, b);
 }
 
 template <int BITS>
-void launch_bits(cnr_ctx *ctx, const QuantArgs &a, hipStream_t s) {
-    const bool greedy = a.mode == kModeGreedy && a.n_iter > 0;  // zero iterations: plain min/max
-    if (a.dim == 64) return greedy ? launch_greedy<4, BITS>(ctx, a, s) : launch_rows16<1, BITS>(ctx, a, s);
-    if (a.dim == 128) return greedy ? launch_greedy<8, BITS>(ctx, a, s) : launch_rows16<2, BITS>(ctx, a, s);
-    if (a.dim == 256) return greedy ? launch_greedy<16, BITS>(ctx, a, s) : launch_rows16<4, BITS>(ctx, a, s);
-    const unsigned grid = cnr_grid(ctx, a.n_max, kWavesPerBlock, 8);
-    hipLaunchKernelGGL((quantize_rows_generic_kernel<BITS>), dim3(grid), dim3(kBlock), 0, s, a.table,
-                       a.n_rows, a.dim, a.row_ids, a.n_dev, a.n_max, a.mode, a.n_iter, a.num_bins_f,
-                       a.scale, a.bias, a.row_min, a.row_max, a.codes, a.packed, a.err);
+void launch_bits(cnr_ctx *ctx, QuantBatch &b, hipStream_t s) {
+    const QuantArgs &c = b.job[0];                              // dim, mode, n_iter are common to the batch
+    const bool greedy = c.mode == kModeGreedy && c.n_iter > 0;  // zero iterations: plain min/max
+    if (c.dim == 64) return greedy ? launch_greedy<4, BITS>(ctx, b, s) : launch_rows16<1, BITS>(ctx, b, s);
+    if (c.dim == 128) return greedy ? launch_greedy<8, BITS>(ctx, b, s) : launch_rows16<2, BITS>(ctx, b, s);
+    if (c.dim == 256) return greedy ? launch_greedy<16, BITS>(ctx, b, s) : launch_rows16<4, BITS>(ctx, b, s);
+    for (uint32_t t = 0; t < b.n_jobs; ++t) {  // other row lengths: one launch per table
+        const QuantArgs &a = b.job[t];
+        const unsigned grid = cnr_grid(ctx, a.n_max, kWavesPerBlock, 8);
+        hipLaunchKernelGGL((quantize_rows_generic_kernel<BITS>), dim3(grid), dim3(kBlock), 0, s, a.table,
+                           a.n_rows, a.dim, a.row_ids, a.n_dev, a.n_max, a.mode, a.n_iter, a.num_bins_f,
+                           a.scale, a.bias, a.row_min, a.row_max, a.codes, a.packed, a.err);
+    }
 }
 
 }  // namespace
 
 extern "C" {
 
-cnr_status cnr_quantize_rows(cnr_ctx *ctx, const float *table, uint64_t n_rows, uint32_t dim,
-                             const uint32_t *row_ids, const uint64_t *n_dev, uint64_t n_max,
-                             int bits, cnr_range_mode mode, const cnr_greedy_params *greedy,
-                             float *scale, float *bias, float *row_min, float *row_max,
-                             uint8_t *codes_u8, uint8_t *packed, void *stream) {
+cnr_status cnr_quantize_rows_batch(cnr_ctx *ctx, const cnr_table_job *jobs, uint32_t n_jobs, uint32_t dim,
+                                   int bits, cnr_range_mode mode, const cnr_greedy_params *greedy,
+                                   void *stream) {
     cnr_status st = cnr_enter(ctx);
     if (st != CNR_OK) return st;
     if (!cnr_valid_bits(bits)) return CNR_E_BITS;
     if (dim == 0 || dim % 4 || dim > CNR_MAX_DIM || ((uint64_t)dim * (uint64_t)bits) % 8) return CNR_E_DIM;
     if (mode != CNR_RANGE_MINMAX && mode != CNR_RANGE_GREEDY && mode != CNR_RANGE_SYMMETRIC) return CNR_E_INVALID;
     if (mode == CNR_RANGE_GREEDY && !greedy) return CNR_E_INVALID;
-    if (n_max == 0) return CNR_OK;
-    if (!table || !scale || !bias || n_rows == 0 || n_rows >= (1ull << 32)) return CNR_E_INVALID;
-    if (((uintptr_t)table % 16) || ((uintptr_t)packed % 16) || ((uintptr_t)codes_u8 % 4) ||
-        ((uintptr_t)scale % 4) || ((uintptr_t)bias % 4) || ((uintptr_t)row_min % 4) ||
-        ((uintptr_t)row_max % 4) || ((uintptr_t)row_ids % 16) || ((uintptr_t)n_dev % 8))
-        return CNR_E_ALIGN;
-    QuantArgs a;
-    a.table = table; a.n_rows = n_rows; a.dim = dim; a.row_ids = row_ids; a.n_dev = n_dev; a.n_max = n_max;
-    a.mode = (int)mode;
-    a.n_iter = mode == CNR_RANGE_GREEDY ? cnr_greedy_iterations(greedy->num_bins, greedy->ratio) : 0;
-    a.num_bins_f = mode == CNR_RANGE_GREEDY ? (float)greedy->num_bins : 1.0f;
-    a.scale = scale; a.bias = bias; a.row_min = row_min; a.row_max = row_max;
-    a.codes = codes_u8; a.packed = packed; a.err = ctx->dev_err;
-    hipStream_t s = as_stream(stream);
-    switch (bits) {
-        case 2: launch_bits<2>(ctx, a, s); break;
-        case 3: launch_bits<3>(ctx, a, s); break;
-        case 4: launch_bits<4>(ctx, a, s); break;
-        default: launch_bits<8>(ctx, a, s); break;
+    if (n_jobs && !jobs) return CNR_E_INVALID;
+    for (uint32_t i = 0; i < n_jobs; ++i) {
+        const cnr_table_job &j = jobs[i];
+        if (j.capacity == 0) continue;
+        if (!j.table || !j.scale || !j.bias || j.n_rows == 0 || j.n_rows >= (1ull << 32)) return CNR_E_INVALID;
+        if (((uintptr_t)j.table % 16) || ((uintptr_t)j.packed % 16) || ((uintptr_t)j.codes_u8 % 4) ||
+            ((uintptr_t)j.scale % 4) || ((uintptr_t)j.bias % 4) || ((uintptr_t)j.row_min % 4) ||
+            ((uintptr_t)j.row_max % 4) || ((uintptr_t)j.row_ids % 16) || ((uintptr_t)j.n_dirty_dev % 8))
+            return CNR_E_ALIGN;
     }
-    return cnr_launch_status(ctx);
+    hipStream_t s = as_stream(stream);
+    for (uint32_t first = 0; first < n_jobs; first += CNR_MAX_BATCH) {
+        QuantBatch b = {};
+        for (uint32_t i = first; i < n_jobs && i < first + CNR_MAX_BATCH; ++i) {
+            const cnr_table_job &j = jobs[i];
+            if (j.capacity == 0) continue;
+            QuantArgs &a = b.job[b.n_jobs++];
+            a.table = j.table; a.n_rows = j.n_rows; a.dim = dim; a.row_ids = j.row_ids;
+            a.n_dev = j.n_dirty_dev; a.n_max = j.capacity;
+            a.mode = (int)mode;
+            a.n_iter = mode == CNR_RANGE_GREEDY ? cnr_greedy_iterations(greedy->num_bins, greedy->ratio) : 0;
+            a.num_bins_f = mode == CNR_RANGE_GREEDY ? (float)greedy->num_bins : 1.0f;
+            a.scale = j.scale; a.bias = j.bias; a.row_min = j.row_min; a.row_max = j.row_max;
+            a.codes = j.codes_u8; a.packed = j.packed; a.err = ctx->dev_err;
+        }
+        if (b.n_jobs == 0) continue;
+        switch (bits) {
+            case 2: launch_bits<2>(ctx, b, s); break;
+            case 3: launch_bits<3>(ctx, b, s); break;
+            case 4: launch_bits<4>(ctx, b, s); break;
+            default: launch_bits<8>(ctx, b, s); break;
+        }
+        if ((st = cnr_launch_status(ctx)) != CNR_OK) return st;
+    }
+    return CNR_OK;
+}
+
+cnr_status cnr_quantize_rows(cnr_ctx *ctx, const float *table, uint64_t n_rows, uint32_t dim,
+                             const uint32_t *row_ids, const uint64_t *n_dev, uint64_t n_max,
+                             int bits, cnr_range_mode mode, const cnr_greedy_params *greedy,
+                             float *scale, float *bias, float *row_min, float *row_max,
+                             uint8_t *codes_u8, uint8_t *packed, void *stream) {
+    cnr_table_job j = {};
+    j.table = const_cast<float *>(table);
+    j.n_rows = n_rows;
+    j.row_ids = const_cast<uint32_t *>(row_ids);
+    j.n_dirty_dev = const_cast<uint64_t *>(n_dev);
+    j.capacity = n_max;
+    j.scale = scale; j.bias = bias; j.row_min = row_min; j.row_max = row_max;
+    j.codes_u8 = codes_u8; j.packed = packed;
+    return cnr_quantize_rows_batch(ctx, &j, 1, dim, bits, mode, greedy, stream);
 }
 
 cnr_status cnr_pack(cnr_ctx *ctx, const uint8_t *codes_u8, const uint64_t *n_dev, uint64_t n_max,

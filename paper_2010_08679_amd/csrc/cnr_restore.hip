@@ -85,26 +85,40 @@ __device__ __forceinline__ void fetch_restore_input(const uint32_t *__restrict__
 // them into "lane l owns elements 64c + 4l .. + 3 of each of the four rows", so the fp32 rows leave
 // as 16-byte streaming stores that cover 256 contiguous bytes per row.  The input of the next batch
 // is requested before the current batch is de-quantized and stored.
+struct RestoreJob {
+    float *table;
+    uint64_t n_rows;
+    const uint32_t *row_ids;
+    const uint64_t *n_dev;
+    uint64_t n_max;
+    const uint8_t *packed;
+    const float *scale, *bias;
+};
+// The tables of one launch; a workgroup that has run out of rows in one goes on to the next.
+struct RestoreBatch {
+    RestoreJob job[CNR_MAX_BATCH];
+    uint32_t n_jobs;
+    uint32_t n_waves;  // waves of the grid
+};
+
 template <int M, int BITS>
-__global__ void __launch_bounds__(kBlock)
-restore_rows16_kernel(float *__restrict__ table, uint64_t n_rows, const uint32_t *__restrict__ row_ids,
-                      const uint64_t *__restrict__ n_dev, uint64_t n_max,
-                      const uint8_t *__restrict__ packed, const float *__restrict__ scale,
-                      const float *__restrict__ bias, cnr_dev_errors *err) {
+__device__ __forceinline__ void restore_table(const RestoreJob &a, uint32_t n_waves, uint32_t &carry,
+                                              cnr_dev_errors *err) {
     constexpr int DIM = 64 * M;
     constexpr uint32_t MASK = (1u << BITS) - 1u;
-    uint64_t n = n_max;
-    if (n_dev) {
-        const uint64_t nd = *n_dev;
-        n = nd < n_max ? nd : n_max;
-    }
-    const int lane = threadIdx.x & (kWave - 1);
+    float *__restrict__ table = a.table;
+    const uint32_t *__restrict__ row_ids = a.row_ids;
+    const uint64_t *__restrict__ n_dev = a.n_dev;
+    const uint8_t *__restrict__ packed = a.packed;
+    const float *__restrict__ scale = a.scale, *__restrict__ bias = a.bias;
+    const uint64_t n_rows = a.n_rows, n_max = a.n_max;
+    const uint64_t n = live_rows(n_dev, n_max);
+    const int lane = tid_x() & (kWave - 1);
     const int g = lane >> 4;
     const int l = lane & 15;
     const int q = l >> 2;
     const int j = l & 3;
-    const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
-    uint64_t batch = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    uint64_t batch = first_unit(wave_in_grid(), n_waves, (uint32_t)((n + 15u) / 16u), carry);
     if (batch * 16u >= n) return;
     RestoreInput<M, BITS> cur, nxt;
     fetch_restore_input<M, BITS>(row_ids, packed, scale, bias, n_max, batch * 16u + 4u * (uint64_t)g, q, j, cur);
@@ -163,6 +177,12 @@ restore_rows16_kernel(float *__restrict__ table, uint64_t n_rows, const uint32_t
     }
 }
 
+template <int M, int BITS>
+__global__ void __launch_bounds__(kBlock) restore_rows16_kernel(const RestoreBatch b, cnr_dev_errors *err) {
+    uint32_t carry = 0;
+    for (uint32_t t = 0; t < b.n_jobs; ++t) restore_table<M, BITS>(b.job[t], b.n_waves, carry, err);
+}
+
 // Any other dim: one wavefront per row, lanes stride over the elements.
 template <int BITS>
 __global__ void __launch_bounds__(kBlock)
@@ -177,10 +197,10 @@ restore_rows_generic_kernel(float *__restrict__ table, uint64_t n_rows, uint32_t
         const uint64_t nd = *n_dev;
         n = nd < n_max ? nd : n_max;
     }
-    const int lane = threadIdx.x & (kWave - 1);
-    const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
+    const int lane = tid_x() & (kWave - 1);
+    const uint64_t n_waves = (uint64_t)grid_x() * kWavesPerBlock;
     const uint64_t P = (uint64_t)dim * BITS / 8;
-    for (uint64_t k = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave; k < n; k += n_waves) {
+    for (uint64_t k = (uint64_t)wg_x() * kWavesPerBlock + tid_x() / kWave; k < n; k += n_waves) {
         const uint64_t r = row_ids ? (uint64_t)row_ids[k] : k;
         if (r >= n_rows) {
             if (lane == 0) raise_flag(err, CNR_FLAG_ROW_ID);
@@ -200,29 +220,27 @@ restore_rows_generic_kernel(float *__restrict__ table, uint64_t n_rows, uint32_t
 }
 
 template <int M, int BITS>
-void launch_restore16(cnr_ctx *ctx, hipStream_t st, float *table, uint64_t n_rows, const uint32_t *row_ids,
-                      const uint64_t *n_dev, uint64_t n_max, const uint8_t *packed, const float *scale,
-                      const float *bias) {
-    const unsigned grid = cnr_grid(ctx, n_max, 16u * kWavesPerBlock,
+void launch_restore16(cnr_ctx *ctx, hipStream_t st, RestoreBatch &b) {
+    uint64_t most = 0;
+    for (uint32_t t = 0; t < b.n_jobs; ++t)
+        if (b.job[t].n_max > most) most = b.job[t].n_max;
+    const unsigned grid = cnr_grid(ctx, most, 16u * kWavesPerBlock,
                                    cnr_resident_blocks_per_cu<restore_rows16_kernel<M, BITS>>());
-    hipLaunchKernelGGL((restore_rows16_kernel<M, BITS>), dim3(grid), dim3(kBlock), 0, st, table, n_rows,
-                       row_ids, n_dev, n_max, packed, scale, bias, ctx->dev_err);
+    b.n_waves = grid * kWavesPerBlock;
+    hipLaunchKernelGGL((restore_rows16_kernel<M, BITS>), dim3(grid), dim3(kBlock), 0, st, b, ctx->dev_err);
 }
 
 template <int BITS>
-void launch_restore(cnr_ctx *ctx, hipStream_t st, float *table, uint64_t n_rows, uint32_t dim,
-                    const uint32_t *row_ids, const uint64_t *n_dev, uint64_t n_max,
-                    const uint8_t *packed, const float *scale, const float *bias) {
-    if (dim == 64)
-        launch_restore16<1, BITS>(ctx, st, table, n_rows, row_ids, n_dev, n_max, packed, scale, bias);
-    else if (dim == 128)
-        launch_restore16<2, BITS>(ctx, st, table, n_rows, row_ids, n_dev, n_max, packed, scale, bias);
-    else if (dim == 256)
-        launch_restore16<4, BITS>(ctx, st, table, n_rows, row_ids, n_dev, n_max, packed, scale, bias);
-    else
-        hipLaunchKernelGGL((restore_rows_generic_kernel<BITS>), dim3(cnr_grid(ctx, n_max, kWavesPerBlock, 8)),
-                           dim3(kBlock), 0, st, table, n_rows, dim, row_ids, n_dev, n_max, packed, scale,
-                           bias, ctx->dev_err);
+void launch_restore(cnr_ctx *ctx, hipStream_t st, uint32_t dim, RestoreBatch &b) {
+    if (dim == 64) return launch_restore16<1, BITS>(ctx, st, b);
+    if (dim == 128) return launch_restore16<2, BITS>(ctx, st, b);
+    if (dim == 256) return launch_restore16<4, BITS>(ctx, st, b);
+    for (uint32_t t = 0; t < b.n_jobs; ++t) {  // other row lengths: one launch per table
+        const RestoreJob &a = b.job[t];
+        hipLaunchKernelGGL((restore_rows_generic_kernel<BITS>), dim3(cnr_grid(ctx, a.n_max, kWavesPerBlock, 8)),
+                           dim3(kBlock), 0, st, a.table, a.n_rows, dim, a.row_ids, a.n_dev, a.n_max, a.packed,
+                           a.scale, a.bias, ctx->dev_err);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -241,10 +259,10 @@ quant_error_kernel(const float *__restrict__ table, uint64_t n_rows, uint32_t di
         const uint64_t nd = *n_dev;
         n = nd < n_max ? nd : n_max;
     }
-    const int lane = threadIdx.x & (kWave - 1);
-    const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
+    const int lane = tid_x() & (kWave - 1);
+    const uint64_t n_waves = (uint64_t)grid_x() * kWavesPerBlock;
     const uint64_t P = (uint64_t)dim * BITS / 8;
-    for (uint64_t k = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave; k < n; k += n_waves) {
+    for (uint64_t k = (uint64_t)wg_x() * kWavesPerBlock + tid_x() / kWave; k < n; k += n_waves) {
         const uint64_t r = row_ids ? (uint64_t)row_ids[k] : k;
         if (r >= n_rows) {
             if (lane == 0) {
@@ -280,14 +298,14 @@ mean_kernel(const double *__restrict__ v, const uint64_t *__restrict__ n_dev, ui
         n = nd < n_max ? nd : n_max;
     }
     double acc = 0.0;
-    for (uint64_t i = threadIdx.x; i < n; i += kBlock) acc += v[i];
-    part[threadIdx.x] = acc;
+    for (uint64_t i = tid_x(); i < n; i += kBlock) acc += v[i];
+    part[tid_x()] = acc;
     __syncthreads();
     for (int half = kBlock / 2; half > 0; half >>= 1) {
-        if ((int)threadIdx.x < half) part[threadIdx.x] += part[threadIdx.x + half];
+        if ((int)tid_x() < half) part[tid_x()] += part[tid_x() + half];
         __syncthreads();
     }
-    if (threadIdx.x == 0) *mean_out = n ? part[0] / (double)n : 0.0;
+    if (tid_x() == 0) *mean_out = n ? part[0] / (double)n : 0.0;
 }
 
 }  // namespace
@@ -323,25 +341,56 @@ extern "C" cnr_status cnr_quant_error(cnr_ctx *ctx, const float *table, uint64_t
     return st;
 }
 
-extern "C" cnr_status cnr_restore_rows(cnr_ctx *ctx, float *table, uint64_t n_rows, uint32_t dim,
-                                       const uint32_t *row_ids, const uint64_t *n_dev, uint64_t n_max,
-                                       int bits, const uint8_t *packed, const float *scale,
-                                       const float *bias, void *stream) {
+extern "C" cnr_status cnr_restore_rows_batch(cnr_ctx *ctx, const cnr_table_job *jobs, uint32_t n_jobs,
+                                             uint32_t dim, int bits, void *stream) {
     cnr_status st = cnr_enter(ctx);
     if (st != CNR_OK) return st;
     if (!cnr_valid_bits(bits)) return CNR_E_BITS;
     if (dim == 0 || dim % 4 || dim > CNR_MAX_DIM || ((uint64_t)dim * (uint64_t)bits) % 8) return CNR_E_DIM;
-    if (n_max == 0) return CNR_OK;
-    if (!table || !packed || !scale || !bias || n_rows == 0 || n_rows >= (1ull << 32)) return CNR_E_INVALID;
-    if (((uintptr_t)table % 16) || ((uintptr_t)packed % 16) || ((uintptr_t)scale % 16) ||
-        ((uintptr_t)bias % 16) || ((uintptr_t)row_ids % 16) || ((uintptr_t)n_dev % 8))
-        return CNR_E_ALIGN;
-    hipStream_t s = as_stream(stream);
-    switch (bits) {
-        case 2: launch_restore<2>(ctx, s, table, n_rows, dim, row_ids, n_dev, n_max, packed, scale, bias); break;
-        case 3: launch_restore<3>(ctx, s, table, n_rows, dim, row_ids, n_dev, n_max, packed, scale, bias); break;
-        case 4: launch_restore<4>(ctx, s, table, n_rows, dim, row_ids, n_dev, n_max, packed, scale, bias); break;
-        default: launch_restore<8>(ctx, s, table, n_rows, dim, row_ids, n_dev, n_max, packed, scale, bias); break;
+    if (n_jobs && !jobs) return CNR_E_INVALID;
+    for (uint32_t i = 0; i < n_jobs; ++i) {
+        const cnr_table_job &j = jobs[i];
+        if (j.capacity == 0) continue;
+        if (!j.table || !j.packed || !j.scale || !j.bias || j.n_rows == 0 || j.n_rows >= (1ull << 32))
+            return CNR_E_INVALID;
+        if (((uintptr_t)j.table % 16) || ((uintptr_t)j.packed % 16) || ((uintptr_t)j.scale % 16) ||
+            ((uintptr_t)j.bias % 16) || ((uintptr_t)j.row_ids % 16) || ((uintptr_t)j.n_dirty_dev % 8))
+            return CNR_E_ALIGN;
     }
-    return cnr_launch_status(ctx);
+    hipStream_t s = as_stream(stream);
+    for (uint32_t first = 0; first < n_jobs; first += CNR_MAX_BATCH) {
+        RestoreBatch b = {};
+        for (uint32_t i = first; i < n_jobs && i < first + CNR_MAX_BATCH; ++i) {
+            const cnr_table_job &j = jobs[i];
+            if (j.capacity == 0) continue;
+            RestoreJob &a = b.job[b.n_jobs++];
+            a.table = j.table; a.n_rows = j.n_rows; a.row_ids = j.row_ids; a.n_dev = j.n_dirty_dev;
+            a.n_max = j.capacity; a.packed = j.packed; a.scale = j.scale; a.bias = j.bias;
+        }
+        if (b.n_jobs == 0) continue;
+        switch (bits) {
+            case 2: launch_restore<2>(ctx, s, dim, b); break;
+            case 3: launch_restore<3>(ctx, s, dim, b); break;
+            case 4: launch_restore<4>(ctx, s, dim, b); break;
+            default: launch_restore<8>(ctx, s, dim, b); break;
+        }
+        if ((st = cnr_launch_status(ctx)) != CNR_OK) return st;
+    }
+    return CNR_OK;
+}
+
+extern "C" cnr_status cnr_restore_rows(cnr_ctx *ctx, float *table, uint64_t n_rows, uint32_t dim,
+                                       const uint32_t *row_ids, const uint64_t *n_dev, uint64_t n_max,
+                                       int bits, const uint8_t *packed, const float *scale,
+                                       const float *bias, void *stream) {
+    cnr_table_job j = {};
+    j.table = table;
+    j.n_rows = n_rows;
+    j.row_ids = const_cast<uint32_t *>(row_ids);
+    j.n_dirty_dev = const_cast<uint64_t *>(n_dev);
+    j.capacity = n_max;
+    j.packed = const_cast<uint8_t *>(packed);
+    j.scale = const_cast<float *>(scale);
+    j.bias = const_cast<float *>(bias);
+    return cnr_restore_rows_batch(ctx, &j, 1, dim, bits, stream);
 }

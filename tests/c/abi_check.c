@@ -14,7 +14,8 @@ int main(void) {
         (fn)cnr_mark_scratch_bytes, (fn)cnr_greedy_iterations, (fn)cnr_clear_bitmap, (fn)cnr_mark_touched,
         (fn)cnr_compact_dirty, (fn)cnr_quantize_rows, (fn)cnr_pack, (fn)cnr_restore_rows, (fn)cnr_quant_error,
         (fn)cnr_poll_errors, (fn)cnr_status_str, (fn)cnr_last_hip_error, (fn)cnr_full_checkpoint_due,
-        (fn)cnr_policy_init, (fn)cnr_policy_next};
+        (fn)cnr_policy_init, (fn)cnr_policy_next, (fn)cnr_clear_bitmap_batch, (fn)cnr_mark_touched_batch,
+        (fn)cnr_compact_dirty_batch, (fn)cnr_quantize_rows_batch, (fn)cnr_restore_rows_batch};
     size_t i, n_exports = sizeof(exports) / sizeof(exports[0]);
     for (i = 0; i < n_exports; ++i)
         if (!exports[i]) return 10;
@@ -47,6 +48,14 @@ int main(void) {
             if (cnr_quantize_rows(ctx, NULL, 10, 64, NULL, NULL, 10, 5, CNR_RANGE_MINMAX, NULL, NULL, NULL, NULL,
                                   NULL, NULL, NULL, NULL) != CNR_E_BITS) return 19;
             if (cnr_restore_rows(ctx, NULL, 10, 12, NULL, NULL, 10, 3, NULL, NULL, NULL, NULL) != CNR_E_DIM) return 20;
+            {
+                cnr_table_job job;
+                memset(&job, 0, sizeof job);
+                if (cnr_quantize_rows_batch(ctx, &job, 1, 64, 4, (cnr_range_mode)9, NULL, NULL) != CNR_E_INVALID) return 23;
+                if (cnr_quantize_rows_batch(ctx, &job, 1, 64, 4, CNR_RANGE_MINMAX, NULL, NULL) != CNR_OK) return 24;
+                job.n_rows = (uint64_t)1 << 32;
+                if (cnr_mark_touched_batch(ctx, &job, 1, CNR_IDX_I64, NULL) != CNR_E_INVALID) return 25;
+            }
             if (cnr_destroy(ctx) != CNR_OK) return 21;
         } else if (st != CNR_E_HIP || ctx != NULL) {
             return 22;

@@ -1,0 +1,226 @@
+"""GPU parity of the several-tables-per-launch calls: every table of a batch against the CPU oracle,
+and against the single-table calls bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2010_08679_amd as P
+from paper_2010_08679_amd import synth
+from util_parity import compare_quantized, u32
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+BITS = (2, 3, 4, 8)
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = P.cnr_create(0)
+    yield c
+    torch.cuda.synchronize()
+    P.cnr_destroy(c)
+
+
+def _poll_clean(ctx):
+    assert P.cnr_poll_errors(ctx) == (P.CNR_OK, 0, 0)
+
+
+class _Tables:
+    """A few tables of one row length with ragged sizes, their look-up streams, and both per-table
+    and batched checkpointers on the same kind of buffers."""
+
+    def __init__(self, ctx, sizes, dim, seed, n_idx, with_scratch=True, idx_dtype=torch.int64):
+        g = torch.Generator(device=DEV).manual_seed(seed)
+        self.sizes, self.dim = sizes, dim
+        self.tables = [synth.table_outlier_mix(n, dim, 0.02, seed * 100 + i, DEV) for i, n in enumerate(sizes)]
+        self.host = [t.cpu().numpy() for t in self.tables]
+        self.idx = [None if m == 0 else torch.randint(0, n, (m,), generator=g, device=DEV).to(idx_dtype)
+                    for n, m in zip(sizes, n_idx)]
+
+        def cks():
+            return [P.TableCheckpointer(ctx, n, dim, device=DEV,
+                                        mark_scratch=P.TableCheckpointer.new_mark_scratch(n, DEV) if with_scratch else None)
+                    for n in sizes]
+        self.single, self.batched = cks(), cks()
+        self.batch = P.BatchCheckpointer(ctx, self.batched)
+
+    def oracle_track(self, i):
+        bm = O.new_bitmap(self.sizes[i])
+        if self.idx[i] is not None:
+            O.mark_touched(bm, self.sizes[i], self.idx[i].cpu().numpy())
+        ids, n = O.compact_dirty(bm, self.sizes[i])
+        return bm, ids, n
+
+
+def _outputs(cks, bits):
+    return [c.alloc_output(bits, want_range=True) for c in cks]
+
+
+def _host(enc, n, dim, bits):
+    prb = P.cnr_packed_row_bytes(dim, bits)
+    packed = enc.packed.cpu().numpy()[:n * prb].reshape(n, prb)
+    return dict(scale=enc.scale.cpu().numpy()[:n], bias=enc.bias.cpu().numpy()[:n],
+                row_min=enc.row_min.cpu().numpy()[:n], row_max=enc.row_max.cpu().numpy()[:n],
+                packed=packed, codes=O.unpack(packed, dim, bits))
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("dim", [64, 128])
+def test_batched_checkpoint_equals_oracle_and_single_calls(ctx, bits, dim):
+    sizes = [70_001, 5_000, 33, 16_384, 1]
+    n_idx = [300_000, 2_000, 0, 9_000, 3]                      # bulk route, atomic route, nothing, ...
+    T = _Tables(ctx, sizes, dim, seed=bits * 10 + dim, n_idx=n_idx)
+    # --- batched path
+    T.batch.clear()
+    T.batch.mark(T.idx)
+    T.batch.compact()
+    outs_b = _outputs(T.batched, bits)
+    T.batch.encode(T.tables, outs_b)
+    stale_b = [torch.zeros_like(t) for t in T.tables]
+    T.batch.restore(stale_b, outs_b)
+    # --- the same through the single-table calls
+    outs_s = _outputs(T.single, bits)
+    stale_s = [torch.zeros_like(t) for t in T.tables]
+    for c, idx, t, o, st in zip(T.single, T.idx, T.tables, outs_s, stale_s):
+        c.clear()
+        if idx is not None:
+            c.mark(idx)
+        c.compact()
+        c.encode(t, o)
+        c.restore(st, o)
+    torch.cuda.synchronize()
+    for i, n_rows in enumerate(sizes):
+        bm, ids, n = T.oracle_track(i)
+        cb, cs = T.batched[i], T.single[i]
+        assert np.array_equal(u32(cb.bitmap)[:bm.size], bm), "table %d bitmap" % i
+        assert int(cb.n_dirty.item()) == n and np.array_equal(u32(cb.row_ids)[:n], ids)
+        if cb.mark_scratch is not None:
+            assert not cb.mark_scratch.any()
+        got = _host(outs_b[i], n, dim, bits)
+        one = _host(outs_s[i], n, dim, bits)
+        for k in ("scale", "bias", "row_min", "row_max", "packed"):
+            assert np.array_equal(got[k], one[k]), "table %d %s differs from the single-table call" % (i, k)
+        assert torch.equal(stale_b[i], stale_s[i])
+        if n:
+            ora = O.quantize_rows(T.host[i], ids, bits, n_threads=8)
+            compare_quantized(T.host[i][ids], got, ora, bits, what="batch table %d b%d d%d" % (i, bits, dim))
+            want = np.zeros_like(T.host[i])
+            O.restore_rows(want, ids, bits, got["packed"], got["scale"], got["bias"])
+            assert np.array_equal(stale_b[i].cpu().numpy(), want)
+    _poll_clean(ctx)
+
+
+@pytest.mark.parametrize("bits,dim", [(4, 64), (2, 128), (3, 256)])
+def test_batched_greedy(ctx, bits, dim):
+    sizes = [3_001, 700, 64]
+    T = _Tables(ctx, sizes, dim, seed=7 + bits, n_idx=[2_500, 900, 64])
+    T.batch.clear()
+    T.batch.mark(T.idx)
+    T.batch.compact()
+    outs = _outputs(T.batched, bits)
+    T.batch.encode(T.tables, outs, mode=P.CNR_RANGE_GREEDY, greedy=(20, 0.6))
+    torch.cuda.synchronize()
+    for i in range(len(sizes)):
+        _, ids, n = T.oracle_track(i)
+        got = _host(outs[i], n, dim, bits)
+        ora = O.quantize_rows(T.host[i], ids, bits, mode=O.RANGE_GREEDY, num_bins=20, ratio=0.6, n_threads=8)
+        compare_quantized(T.host[i][ids], got, ora, bits, greedy=True, what="batch greedy table %d" % i)
+    _poll_clean(ctx)
+
+
+def test_more_tables_than_one_launch_takes(ctx):
+    n_tables = P.CNR_MAX_BATCH + 3
+    sizes = [1_000 + 37 * i for i in range(n_tables)]
+    T = _Tables(ctx, sizes, 64, seed=3, n_idx=[400 + i for i in range(n_tables)], with_scratch=False,
+                idx_dtype=torch.int32)
+    T.batch.clear()
+    T.batch.mark(T.idx)
+    T.batch.compact()
+    outs = _outputs(T.batched, 4)
+    T.batch.encode(T.tables, outs)
+    stale = [torch.zeros_like(t) for t in T.tables]
+    T.batch.restore(stale, outs)
+    torch.cuda.synchronize()
+    for i in range(n_tables):
+        bm, ids, n = T.oracle_track(i)
+        assert np.array_equal(u32(T.batched[i].bitmap)[:bm.size], bm)
+        assert int(T.batched[i].n_dirty.item()) == n and np.array_equal(u32(T.batched[i].row_ids)[:n], ids)
+        got = _host(outs[i], n, 64, 4)
+        ora = O.quantize_rows(T.host[i], ids, 4)
+        compare_quantized(T.host[i][ids], got, ora, 4, what="table %d of %d" % (i, n_tables))
+        want = np.zeros_like(T.host[i])
+        O.restore_rows(want, ids, 4, got["packed"], got["scale"], got["bias"])
+        assert np.array_equal(stale[i].cpu().numpy(), want)
+    _poll_clean(ctx)
+
+
+def test_other_row_lengths_go_table_by_table(ctx):
+    sizes = [900, 2_000]
+    T = _Tables(ctx, sizes, 40, seed=11, n_idx=[500, 1_500])
+    T.batch.clear()
+    T.batch.mark(T.idx)
+    T.batch.compact()
+    outs = _outputs(T.batched, 4)
+    T.batch.encode(T.tables, outs)
+    stale = [torch.zeros_like(t) for t in T.tables]
+    T.batch.restore(stale, outs)
+    torch.cuda.synchronize()
+    for i in range(2):
+        _, ids, n = T.oracle_track(i)
+        got = _host(outs[i], n, 40, 4)
+        ora = O.quantize_rows(T.host[i], ids, 4)
+        assert np.array_equal(got["codes"], ora["codes"]) and np.array_equal(got["scale"], ora["scale"])
+        want = np.zeros_like(T.host[i])
+        O.restore_rows(want, ids, 4, got["packed"], got["scale"], got["bias"])
+        assert np.array_equal(stale[i].cpu().numpy(), want)
+    _poll_clean(ctx)
+
+
+def test_bad_job_rejects_the_whole_call_before_any_launch(ctx):
+    T = _Tables(ctx, [2_000, 2_000], 64, seed=5, n_idx=[1_000, 1_000])
+    T.batch.clear()
+    torch.cuda.synchronize()
+    jobs = T.batch.jobs(indices=T.idx)
+    jobs[1].n_rows = 1 << 32
+    with pytest.raises(P.CnrError) as e:
+        P.cnr_mark_touched_batch(ctx, jobs, P.CNR_IDX_I64)
+    assert e.value.status == P.CNR_E_INVALID
+    jobs = T.batch.jobs(indices=T.idx)
+    jobs[1].indices += 4                                       # int64 stream at a 4-byte boundary
+    with pytest.raises(P.CnrError) as e:
+        P.cnr_mark_touched_batch(ctx, jobs, P.CNR_IDX_I64)
+    assert e.value.status == P.CNR_E_ALIGN
+    torch.cuda.synchronize()
+    assert not T.batched[0].bitmap.any() and not T.batched[1].bitmap.any()
+    outs = _outputs(T.batched, 4)
+    with pytest.raises(P.CnrError) as e:
+        P.cnr_quantize_rows_batch(ctx, T.batch.jobs(tables=T.tables, outs=outs), 64, 5, P.CNR_RANGE_MINMAX)
+    assert e.value.status == P.CNR_E_BITS
+    with pytest.raises(P.CnrError) as e:
+        P.cnr_restore_rows_batch(ctx, T.batch.jobs(tables=T.tables, outs=outs), 12, 3)
+    assert e.value.status == P.CNR_E_DIM
+    _poll_clean(ctx)
+
+
+def test_capacity_overflow_in_one_table_of_a_batch(ctx):
+    sizes = [4_000, 4_000]
+    cks = [P.TableCheckpointer(ctx, sizes[0], 64, device=DEV),
+           P.TableCheckpointer(ctx, sizes[1], 64, capacity=100, device=DEV)]
+    batch = P.BatchCheckpointer(ctx, cks)
+    g = torch.Generator(device=DEV).manual_seed(9)
+    idx = [torch.randint(0, n, (3_000,), generator=g, device=DEV) for n in sizes]
+    batch.clear()
+    batch.mark(idx)
+    cks[1].row_ids.fill_(-1)
+    batch.compact()
+    st, bad, flags = P.cnr_poll_errors(ctx)
+    assert st == P.CNR_E_CAPACITY and flags == P.CNR_FLAG_CAPACITY and bad == 0
+    for c, ix in zip(cks, idx):
+        bm = O.new_bitmap(c.n_rows)
+        O.mark_touched(bm, c.n_rows, ix.cpu().numpy())
+        ids, n = O.compact_dirty(bm, c.n_rows)
+        assert int(c.n_dirty.item()) == n                      # the true count, also when truncated
+        m = min(n, c.capacity)
+        assert np.array_equal(u32(c.row_ids)[:m], ids[:m])
+    _poll_clean(ctx)
