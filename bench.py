@@ -41,8 +41,8 @@ ISSUE_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # one vector instruction per lane
 # per dirty row, valid only for the kernel source whose hash is recorded with it.
 TRAFFIC_PER_ROW = {
     # sha256 of csrc/cnr_quantize.hip : (workload, bytes per dirty row)
-    # (2.000 * 1529513.9 KiB FETCH_SIZE + 1.000 * 472806.4 KiB WRITE_SIZE) / 12,000,978 rows of one launch
-    "51a81e26dda74ed3af26f841305040cc5bb4f1892c2a6c73d307dc33550e7d63": ("cfg4/b4", 301.36),
+    # (2.000 * 190490.1 KiB FETCH_SIZE + 1.000 * 60149.6 KiB WRITE_SIZE) / 1,500,122 rows per launch
+    "3495a6330659a0721fb3a26dcdb4c7cfbc01163818a4f8f8baf3a4820b6cffdd": ("cfg4/b4", 301.12),
 }
 
 
@@ -192,21 +192,23 @@ def main() -> int:
     stage_ms = {k: v / args.steps for k, v in stage_timer.totals_ms().items()}
     launches = timer.counts()
 
-    # dominant kernel: the fused gather + quantize + pack
-    enc_launch_ms = timer.totals_ms()["encode"] / launches["encode"]
-    rows_per_launch = sum(n_dirty) / launches_per_stage
+    # dominant kernel: the fused gather + quantize + pack, one launch per table.  A span of events
+    # holds one launch (per-table calls) or the n_tables back-to-back launches of one batched call.
+    launches_per_span = n_tables // launches_per_stage
+    enc_launch_ms = timer.totals_ms()["encode"] / (launches["encode"] * launches_per_span)
+    rows_per_launch = sum(n_dirty) / n_tables
     enc_bytes = encode_bytes_per_row(w.dim, bits) * rows_per_launch
     achieved = enc_bytes / (enc_launch_ms * 1e-3) / 1e9
     traffic = None
     rec = TRAFFIC_PER_ROW.get(_kernel_hash())
     if rec and rec[0] == "%s/b%d" % (w.name, bits):
         traffic = rec[1] * rows_per_launch
-    roofline = {"bound": "hbm", "kernel": "quantize_rows16_kernel<%d, %d>" % (w.dim // 64, bits),
+    roofline = {"bound": "hbm", "kernel": "quantize_tile_kernel<%d, %d>" % (w.dim // 64, bits),
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "bytes_per_launch": int(enc_bytes), "avg_launch_ms": round(enc_launch_ms, 5),
-                "empty_event_pair_ms": round(null_ms, 5)}
-    res_ms = stage_timer.totals_ms()["restore"] / stage_timer.counts()["restore"]
+                "launches_per_event_span": launches_per_span, "empty_event_pair_ms": round(null_ms, 5)}
+    res_ms = stage_timer.totals_ms()["restore"] / (stage_timer.counts()["restore"] * launches_per_span)
     res_bytes = restore_bytes_per_row(w.dim, bits) * rows_per_launch
     stages = {k: round(v, 4) for k, v in stage_ms.items()}
     stages["encode_only_GBps_table_bytes"] = round(table_bytes / ((stage_ms["compact"] + stage_ms["encode"]) * 1e-3) / 1e9, 1)

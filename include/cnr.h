@@ -45,7 +45,7 @@
  *             row one little-endian bit stream in which element j occupies stream bits
  *             [j*bits, (j+1)*bits), least-significant code bit first (stream bit t is bit
  *             (t & 7) of byte (t >> 3)); 16-byte aligned base
- *   codes_u8  uint8 [n][dim], one code per byte
+ *   codes_u8  uint8 [n][dim], one code per byte; 4-byte aligned base
  */
 #ifndef CNR_H
 #define CNR_H
@@ -199,11 +199,11 @@ cnr_status cnr_quant_error(cnr_ctx *ctx, const float *table, uint64_t n_rows, ui
  *
  * One cnr_table_job describes the buffers of one table; the *_batch calls take a host array of
  * them (read during the call) and do for every job what the single-table call of the same name
- * does, with the jobs of a call running side by side in as few launches as possible (one per
- * CNR_MAX_BATCH jobs and kernel).  This matters where a call is short: the per-iteration mark of a
- * few ten thousand indices, the clear, the compaction; and it lets the encode and restore kernels
- * move from one table to the next without draining the GPU in between.  Results are identical to
- * those of the single-table calls.  Buffers of different jobs of one call must not overlap (mark
+ * does.  Where a call is short -- the per-iteration mark of a few ten thousand indices, the clear,
+ * the compaction -- the jobs run side by side in one launch per kernel (and per CNR_MAX_BATCH
+ * jobs), which is what the batch calls are for; the encode and restore kernels, which are bound by
+ * memory bandwidth and sweep a table best with the whole GPU, are launched once per job, back to
+ * back.  Results are identical to those of the single-table calls.  Buffers of different jobs of one call must not overlap (mark
  * scratch included: one per job).  Every field has the meaning, layout and alignment of the
  * argument of the same name of the single-table call; a call reads only the fields listed for it.
  *   cnr_clear_bitmap_batch    bitmap, n_rows

@@ -145,16 +145,6 @@ __device__ __forceinline__ uint64_t live_rows(const uint64_t *n_dev, uint64_t n_
     return ((uint64_t)hi << 32) | lo;
 }
 
-// Work units (passes of one wave) of a persistent kernel are dealt out round-robin over the waves
-// of the grid, and the deal continues across the tables of a batch instead of starting again at
-// wave 0 for each: `carry` is the wave the next table's first unit goes to.  Returns this wave's
-// first unit of a table with `n_units` units (fewer than 2^32) and moves the carry on.
-__device__ __forceinline__ uint32_t first_unit(uint32_t wave, uint32_t n_waves, uint32_t n_units, uint32_t &carry) {
-    const uint32_t first = wave >= carry ? wave - carry : wave + n_waves - carry;
-    carry = (carry + n_units % n_waves) % n_waves;
-    return first;
-}
-
 __device__ __forceinline__ void raise_flag(cnr_dev_errors *err, unsigned flag) {
     atomicOr(&err->flags, flag);
 }

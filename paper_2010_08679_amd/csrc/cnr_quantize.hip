@@ -28,15 +28,7 @@ struct QuantArgs {
     float *scale, *bias, *row_min, *row_max;
     uint8_t *codes, *packed;
     cnr_dev_errors *err;
-};
-
-// The tables of one launch.  A persistent kernel works through them in order: a workgroup that has
-// run out of rows in one table goes on to the next at once, so the GPU is not drained and refilled
-// between tables.
-struct QuantBatch {
-    QuantArgs job[CNR_MAX_BATCH];
-    uint32_t n_jobs;
-    uint32_t n_waves;  // waves of the grid
+    uint32_t n_waves;  // waves of the grid (persistent kernels)
 };
 
 __device__ __forceinline__ uint64_t row_count(const QuantArgs &a) { return live_rows(a.n_dev, a.n_max); }
@@ -61,44 +53,25 @@ __device__ __forceinline__ double fq_sq_err(float x, float lo, float hi, float s
     return (double)d * (double)d;
 }
 
-// 4x4 transpose inside each quad of lanes: on return r[i] of quad lane j holds what r[j] of quad
-// lane i held.
-__device__ __forceinline__ void quad_transpose(uint32_t (&r)[4], int j) {
-#pragma unroll
-    for (int n = 0; n < 4; n += 2) {
-        const uint32_t send = (j & 1) ? r[n] : r[n + 1];
-        const uint32_t recv = (uint32_t)dpp_i<0xB1>((int)send);
-        if (j & 1) r[n] = recv; else r[n + 1] = recv;
-    }
-#pragma unroll
-    for (int n = 0; n < 2; ++n) {
-        const uint32_t send = (j & 2) ? r[n] : r[n + 2];
-        const uint32_t recv = (uint32_t)dpp_i<0x4E>((int)send);
-        if (j & 2) r[n] = recv; else r[n + 2] = recv;
-    }
-}
-
-template <int U>
-__device__ __forceinline__ float quad_bcast(float v) {  // value of quad lane U in all four lanes
-    return dpp_f<U * 0x55>(v);
-}
-
 // ---------------------------------------------------------------------------------------------
 // Bulk kernel (min/max and symmetric range), dim = 64 * M.  Bound by HBM.
 //
-// Sixteen lanes share a row: lane l of the group holds, for every 64-element chunk c of the row,
-// the four consecutive elements 64c + 4l .. 64c + 4l + 3, so one 16-byte load per lane reads 256
-// contiguous bytes per group, and all reductions over a row stay inside one 16-lane DPP row.  Each
-// group works on four consecutive dirty rows at once (a wave has sixteen rows = 4 KB * M in flight),
-// which is also what lets the packed codes leave through full words: after quantizing, a 4x4
-// transpose inside each quad of lanes hands lane j the codes of sixteen consecutive elements of row
-// j.  The loop is software-pipelined: the rows of batch i+1 and the ids of batch i+2 are requested
-// before batch i is reduced and quantized.
+// A wave works on sixteen consecutive dirty rows per pass, in two lane layouts with a transpose
+// through LDS between them:
+//   load layout     sixteen lanes share a row: lane l of group g holds elements 64c + 4l .. + 3 of
+//                   rows 4g .. 4g + 3 of the pass, so every 16-byte load instruction reads 256
+//                   contiguous bytes per row;
+//   compute layout  four lanes share a row: lane j of row rho holds the sixteen consecutive elements
+//                   64c + 16j .. + 15 of every 64-element chunk c.  The row minimum and maximum then
+//                   need only two cross-lane steps, the row's parameters are computed where they are
+//                   used, and a lane's sixteen codes are 2 * BITS contiguous bytes of the packed row,
+//                   so a wave's packed output is one contiguous run.
+// The transpose is private to the wave (LDS operations of one wave complete in order, so no
+// barrier is needed); a row's four quarters sit 80 bytes apart and rows 320 bytes apart, which keeps
+// the eight lanes that the LDS serves together on different banks in both directions.
 //
-// A wave64 instruction occupies a SIMD for four cycles, so vector-ALU issue competes with HBM here,
-// and the per-element work is pared down:
-//   - scale and 1/scale are computed once per row, by the one lane of each quad that owns the row,
-//     with correctly rounded divisions, and broadcast back inside the quad;
+// The kernel has to stay clear of the vector-ALU issue limit (a wave64 instruction occupies a SIMD
+// for four cycles) to run at the speed of its memory traffic, so the per-element work is pared down:
 //   - an element's code is round((x - lo) * (1/scale)); adding 1.5 * 2^23 does the rounding
 //     (half-to-even) and leaves the integer in the low mantissa bits, so four codes are merged by
 //     three shift-adds and one subtraction of the merged constant.  The product differs from the
@@ -107,58 +80,28 @@ __device__ __forceinline__ float quad_bcast(float v) {  // value of quad lane U 
 //     bits, where quotients are larger, one FMA residual step on the quotient removes that too;
 //   - the reciprocal must be a normal number: rows with a scale outside [2^-100, 2^100] (denormal
 //     or near-overflow ranges) are brought there by an exact power-of-two factor applied to both
-//     x - lo and the scale, and a wave takes that variant only if one of its sixteen rows needs it.
-// A layout with sixteen contiguous elements per lane (the greedy kernel's) needs half the
-// instructions but its strided 16-byte loads cost more than they save: 92 us against 81 us per
-// 5 M x 64 table with 30 % dirty rows.
+//     x - lo and the scale, and a wave takes that variant only if one of its sixteen rows needs it;
+//   - rows past the end of the list and row ids outside the table are handled by clamping the
+//     addresses that are read and masking what is stored, not by branches.
 // ---------------------------------------------------------------------------------------------
-#define CNR_SEL4(a) (j == 0 ? (a)[0] : j == 1 ? (a)[1] : j == 2 ? (a)[2] : (a)[3])
+constexpr int kTileQuarterBytes = 80;                  // sixteen floats + 16 bytes
+constexpr int kTileRowBytes = 4 * kTileQuarterBytes;   // 320
+constexpr int kTileBytes = 16 * kTileRowBytes;         // one wave: 5120
 
-template <int M>
-struct RowBatch {
-    float4 x[4][M];  // [row of the group][chunk]
-    unsigned skip;   // bit u: row k0+u is past the end or has an id outside the table
-};
-
-// Row ids of the four rows k0 .. k0+3 of one group.
-__device__ __forceinline__ uint4 gather_ids(const QuantArgs &a, uint64_t k0) {
-    if (!a.row_ids) return make_uint4((uint32_t)k0, (uint32_t)k0 + 1, (uint32_t)k0 + 2, (uint32_t)k0 + 3);
-    if (k0 + 3 < a.n_max)  // the id buffer holds n_max entries: one 16-byte load
-        return *reinterpret_cast<const uint4 *>(a.row_ids + k0);
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (k0 + 0 < a.n_max) v.x = a.row_ids[k0 + 0];
-    if (k0 + 1 < a.n_max) v.y = a.row_ids[k0 + 1];
-    if (k0 + 2 < a.n_max) v.z = a.row_ids[k0 + 2];
-    return v;
+__device__ __forceinline__ float quad_min(float v) {   // over the four lanes of a quad
+    v = fminf(v, dpp_f<0xB1>(v));
+    return fminf(v, dpp_f<0x4E>(v));
+}
+__device__ __forceinline__ float quad_max(float v) {
+    v = fmaxf(v, dpp_f<0xB1>(v));
+    return fmaxf(v, dpp_f<0x4E>(v));
 }
 
-// Issues the loads of the group's four rows (this lane's elements 64c + 4l .. + 3 of each).
-template <int M>
-__device__ __forceinline__ void gather_rows(const QuantArgs &a, uint64_t n, uint64_t k0, uint4 ids, int l,
-                                            RowBatch<M> &rb) {
-    const uint32_t rid[4] = {ids.x, ids.y, ids.z, ids.w};
-    rb.skip = 0;
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const bool past = k0 + u >= n;
-        uint64_t r = rid[u];
-        if (past || r >= a.n_rows) {
-            if (!past && l == 0) raise_flag(a.err, CNR_FLAG_ROW_ID);
-            rb.skip |= 1u << u;
-            r = 0;
-        }
-        const float *src = a.table + r * (uint64_t)(64 * M) + 4u * (uint64_t)l;
-#pragma unroll
-        for (int c = 0; c < M; ++c) {
-            const f32x4 v = load_stream<f32x4>(src + 64 * c);
-            rb.x[u][c] = make_float4(v.x, v.y, v.z, v.w);
-        }
-    }
-}
-
-// Reduces, quantizes and stores the four rows of one group.
+// Quantizes and stores this lane's 16 * M elements of row k (compute layout): x[c][i] holds elements
+// 64c + 16j + 4i .. + 3.
 template <int M, int BITS>
-__device__ __forceinline__ void encode_batch(const QuantArgs &a, uint64_t k0, const RowBatch<M> &rb, int l) {
+__device__ __forceinline__ void encode_row_quarter(const QuantArgs &a, uint64_t k, bool live, int j,
+                                                   const float4 (&x)[M][4]) {
     constexpr int DIM = 64 * M;
     constexpr float QMAXF = (float)((1 << BITS) - 1);
     constexpr uint64_t P = (uint64_t)DIM * BITS / 8;  // packed bytes per row
@@ -167,151 +110,208 @@ __device__ __forceinline__ void encode_batch(const QuantArgs &a, uint64_t k0, co
     // what four magic-biased codes add up to when merged with shifts of B, 2B, 3B bits
     constexpr uint32_t MERGED_BIAS = MAGIC_BITS * (1u + (1u << BITS) + (1u << (2 * BITS)) + (1u << (3 * BITS)));
     constexpr uint32_t MERGED_BIAS8 = MAGIC_BITS * (1u + (1u << 8) + (1u << 16) + (1u << 24));
-    const int q = l >> 2;  // quad in group
-    const int j = l & 3;   // lane in quad
-    const unsigned skip = rb.skip;
-    const float4 (&x)[4][M] = rb.x;
 
     // ---- row minimum / maximum
-    float X_min[4], X_max[4], lo[4], hi[4];
+    float mn = x[0][0].x, mx = x[0][0].x;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        float mn = x[u][0].x, mx = x[u][0].x;
+    for (int c = 0; c < M; ++c)
 #pragma unroll
-        for (int c = 0; c < M; ++c) {
-            mn = fminf(fminf(mn, x[u][c].x), fminf(x[u][c].y, fminf(x[u][c].z, x[u][c].w)));
-            mx = fmaxf(fmaxf(mx, x[u][c].x), fmaxf(x[u][c].y, fmaxf(x[u][c].z, x[u][c].w)));
+        for (int i = 0; i < 4; ++i) {
+            mn = fminf(fminf(mn, x[c][i].x), fminf(x[c][i].y, fminf(x[c][i].z, x[c][i].w)));
+            mx = fmaxf(fmaxf(mx, x[c][i].x), fmaxf(x[c][i].y, fmaxf(x[c][i].z, x[c][i].w)));
         }
-        X_min[u] = row16_min(mn) + 0.0f;  // -0.0 -> +0.0
-        X_max[u] = row16_max(mx) + 0.0f;
-        lo[u] = X_min[u];
-        hi[u] = X_max[u];
-        if (a.mode == kModeSymmetric) {
-            const float m = fmaxf(fabsf(X_min[u]), fabsf(X_max[u]));
-            lo[u] = -m + 0.0f;
-            hi[u] = m;
-        }
+    const float X_min = quad_min(mn) + 0.0f;  // -0.0 -> +0.0
+    const float X_max = quad_max(mx) + 0.0f;
+    float lo = X_min, hi = X_max;
+    if (a.mode == kModeSymmetric) {
+        const float m = fmaxf(fabsf(X_min), fabsf(X_max));
+        lo = -m + 0.0f;
+        hi = m;
     }
 
-    // ---- per-row parameters, computed by the quad lane that owns the row (lane j <-> row k0+j)
-    const float my_lo = CNR_SEL4(lo);
-    const float my_scale = (CNR_SEL4(hi) - my_lo) / QMAXF;
-    const bool my_live = !((skip >> j) & 1u);
-    {   // lanes 0-3 of a group write scale, 4-7 bias, 8-11 min, 12-15 max
-        float *dst = q == 0 ? a.scale : q == 1 ? a.bias : q == 2 ? a.row_min : a.row_max;
-        const float v = q == 0 ? my_scale : q == 1 ? my_lo : q == 2 ? CNR_SEL4(X_min) : CNR_SEL4(X_max);
-        if (dst && my_live) store_stream<float>(dst + k0 + j, v);
+    // ---- the row's parameters; lane 0 of the row writes scale, lane 1 bias, lanes 2, 3 min, max
+    const float scale = (hi - lo) / QMAXF;
+    {
+        float *dst = j == 0 ? a.scale : j == 1 ? a.bias : j == 2 ? a.row_min : a.row_max;
+        const float v = j == 0 ? scale : j == 1 ? lo : j == 2 ? X_min : X_max;
+        if (dst && live) store_stream<float>(dst + k, v);
     }
-    const float my_f = my_scale < 0x1p-100f ? 0x1p120f : my_scale > 0x1p100f ? 0x1p-120f : 1.0f;
-    const float my_fscale = my_scale * my_f;
-    const float my_inv = my_scale == 0.0f ? 0.0f : 1.0f / my_fscale;  // scale 0: every code 0
-    const float inv[4] = {quad_bcast<0>(my_inv), quad_bcast<1>(my_inv), quad_bcast<2>(my_inv),
-                          quad_bcast<3>(my_inv)};
+    const float f = scale < 0x1p-100f ? 0x1p120f : scale > 0x1p100f ? 0x1p-120f : 1.0f;
+    const float fscale = scale * f;
+    const float inv = scale == 0.0f ? 0.0f : 1.0f / fscale;  // scale 0: every code 0
 
-    // ---- quantize; h[c][u] = this lane's four codes of (row u, chunk c)
+    // ---- quantize; h[c][i] = the four codes of elements 64c + 16j + 4i .. + 3, first element lowest
     uint32_t h[M][4];
     auto quantize_by_reciprocal = [&](auto rescale) {
         constexpr bool RESCALE = decltype(rescale)::value;
-        float f[4] = {1.0f, 1.0f, 1.0f, 1.0f}, fsc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        if constexpr (RESCALE) {
-            f[0] = quad_bcast<0>(my_f); f[1] = quad_bcast<1>(my_f);
-            f[2] = quad_bcast<2>(my_f); f[3] = quad_bcast<3>(my_f);
-        }
-        if constexpr (BITS == 8) {
-            fsc[0] = quad_bcast<0>(my_fscale); fsc[1] = quad_bcast<1>(my_fscale);
-            fsc[2] = quad_bcast<2>(my_fscale); fsc[3] = quad_bcast<3>(my_fscale);
-        }
         // magic-biased code of one element: MAGIC_BITS + round((x - lo) / scale)
-        auto biased = [&](float xv, int u) -> uint32_t {
-            float d0 = xv - lo[u];
-            if constexpr (RESCALE) d0 *= f[u];
-            float t = d0 * inv[u];
-            if constexpr (BITS == 8) t = fmaf(fmaf(-t, fsc[u], d0), inv[u], t);
+        auto biased = [&](float xv) -> uint32_t {
+            float d0 = xv - lo;
+            if constexpr (RESCALE) d0 *= f;
+            float t = d0 * inv;
+            if constexpr (BITS == 8) t = fmaf(fmaf(-t, fscale, d0), inv, t);
             return __float_as_uint(t + MAGIC);
         };
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int c = 0; c < M; ++c)
 #pragma unroll
-            for (int c = 0; c < M; ++c) {
-                const uint32_t b0 = biased(x[u][c].x, u), b1 = biased(x[u][c].y, u);
-                const uint32_t b2 = biased(x[u][c].z, u), b3 = biased(x[u][c].w, u);
+            for (int i = 0; i < 4; ++i) {
+                const float4 v = x[c][i];
+                const uint32_t b0 = biased(v.x), b1 = biased(v.y), b2 = biased(v.z), b3 = biased(v.w);
                 uint32_t m = (b3 << BITS) + b2;
                 m = (m << BITS) + b1;
-                h[c][u] = (m << BITS) + b0 - MERGED_BIAS;
-                if (a.codes && !(skip & (1u << u)))
-                    *reinterpret_cast<uint32_t *>(a.codes + (k0 + u) * (uint64_t)DIM + 64 * c + 4 * l) =
+                h[c][i] = (m << BITS) + b0 - MERGED_BIAS;
+                if (a.codes && live)  // one code per byte as well (uniform branch)
+                    *reinterpret_cast<uint32_t *>(a.codes + k * (uint64_t)DIM + 64 * c + 16 * j + 4 * i) =
                         (((((b3 << 8) + b2) << 8) + b1) << 8) + b0 - MERGED_BIAS8;
             }
     };
-    if (__builtin_amdgcn_ballot_w64(my_f != 1.0f) != 0)
+    if (__builtin_amdgcn_ballot_w64(f != 1.0f) != 0)
         quantize_by_reciprocal(std::true_type{});
     else
         quantize_by_reciprocal(std::false_type{});
 
-    // ---- packed codes: after the quad transpose lane j owns 16 consecutive elements
-    // (64c + 16q ..) of row k0 + j
-    if (a.packed) {
-        uint8_t *row = a.packed + (k0 + (uint64_t)j) * P;
 #pragma unroll
-        for (int c = 0; c < M; ++c) {
-            uint32_t t[4] = {h[c][0], h[c][1], h[c][2], h[c][3]};
-            quad_transpose(t, j);
+    for (int c = 0; c < M; ++c) {
+        // ---- packed codes: this lane's bits are 2 * BITS contiguous bytes of the row
+        if (a.packed) {
+            uint8_t *dst = a.packed + k * P + (8 * BITS) * c + (2 * BITS) * j;
             if constexpr (BITS == 8) {
-                if (my_live) store_stream<u32x4>(row + 64 * c + 16 * q, u32x4{t[0], t[1], t[2], t[3]});
+                if (live) store_stream<u32x4>(dst, u32x4{h[c][0], h[c][1], h[c][2], h[c][3]});
             } else if constexpr (BITS == 4) {
-                if (my_live)
-                    store_stream<u32x2>(row + 32 * c + 8 * q, u32x2{t[0] | (t[1] << 16), t[2] | (t[3] << 16)});
+                if (live) store_stream<u32x2>(dst, u32x2{h[c][0] | (h[c][1] << 16), h[c][2] | (h[c][3] << 16)});
             } else if constexpr (BITS == 2) {
-                if (my_live)
-                    store_stream<uint32_t>(row + 16 * c + 4 * q, t[0] | (t[1] << 8) | (t[2] << 16) | (t[3] << 24));
-            } else {  // 3 bits: 48 bits per lane; even quads append the next quad's 48 bits
-                const uint32_t w0 = t[0] | (t[1] << 12) | (t[2] << 24);  // stream bits 0..31
-                const uint32_t w1 = (t[2] >> 8) | (t[3] << 4);           // stream bits 32..47
-                const uint32_t n0 = (uint32_t)dpp_i<0x104>((int)w0);     // row_shl:4 = lane + 4
-                const uint32_t n1 = (uint32_t)dpp_i<0x104>((int)w1);
-                if (my_live && !(q & 1)) {
-                    uint32_t *dst = reinterpret_cast<uint32_t *>(row + 24 * c + 12 * (q >> 1));
-                    store_stream<uint32_t>(dst, w0);
-                    store_stream<uint32_t>(dst + 1, w1 | (n0 << 16));
-                    store_stream<uint32_t>(dst + 2, (n0 >> 16) | (n1 << 16));
+                if (live) store_stream<uint32_t>(dst, h[c][0] | (h[c][1] << 8) | (h[c][2] << 16) | (h[c][3] << 24));
+            } else {  // 3 bits: 48 bits per lane; even lanes append their right neighbour's 48 bits
+                const uint32_t w0 = h[c][0] | (h[c][1] << 12) | (h[c][2] << 24);  // stream bits 0..31
+                const uint32_t w1 = (h[c][2] >> 8) | (h[c][3] << 4);              // stream bits 32..47
+                const uint32_t n0 = (uint32_t)dpp_i<0xB1>((int)w0);                // lane ^ 1
+                const uint32_t n1 = (uint32_t)dpp_i<0xB1>((int)w1);
+                if (live && !(j & 1)) {
+                    uint32_t *d3 = reinterpret_cast<uint32_t *>(dst);
+                    store_stream<uint32_t>(d3, w0);
+                    store_stream<uint32_t>(d3 + 1, w1 | (n0 << 16));
+                    store_stream<uint32_t>(d3 + 2, (n0 >> 16) | (n1 << 16));
                 }
             }
         }
     }
 }
-#undef CNR_SEL4
 
-template <int M, int BITS>
-__device__ __forceinline__ void encode_table(const QuantArgs &a, uint32_t n_waves, uint32_t &carry) {
-    const uint64_t n = row_count(a);
-    const int lane = tid_x() & (kWave - 1);
-    const uint64_t g4 = 4u * (uint64_t)(lane >> 4);  // first row of this lane's group within a batch
-    const int l = lane & 15;                         // lane in group
-    uint64_t batch = first_unit(wave_in_grid(), n_waves, (uint32_t)((n + 15u) / 16u), carry);
-    if (batch * 16u >= n) return;
+// Row ids a lane needs for one pass: of the four rows it helps to load, and of the row it encodes.
+struct PassIds {
+    uint32_t rid[4];
+    uint32_t own;
+};
 
-    RowBatch<M> cur, nxt;
-    gather_rows<M>(a, n, batch * 16u + g4, gather_ids(a, batch * 16u + g4), l, cur);
-    uint64_t next = batch + n_waves;
-    uint4 ids_next = make_uint4(0, 0, 0, 0);
-    if (next * 16u < n) ids_next = gather_ids(a, next * 16u + g4);
-    for (;;) {
-        const bool has_next = next * 16u < n;  // uniform over the wave
-        if (has_next) gather_rows<M>(a, n, next * 16u + g4, ids_next, l, nxt);
-        const uint64_t next2 = next + n_waves;
-        if (next2 * 16u < n) ids_next = gather_ids(a, next2 * 16u + g4);
-        encode_batch<M, BITS>(a, batch * 16u + g4, cur, l);
-        if (!has_next) break;
-        cur = nxt;
-        batch = next;
-        next = next2;
+// Ids of pass `pass` (which must hold at least one row).  Rows past the end repeat the last row of
+// the pass; nothing of theirs is stored.
+__device__ __forceinline__ void load_pass_ids(const QuantArgs &a, uint64_t n, uint64_t pass, int g, int rho, PassIds &o) {
+    const uint64_t base = pass * 16u;
+    const uint64_t left = n - base;
+    const uint32_t rows = left < 16u ? (uint32_t)left : 16u;  // uniform
+    const uint32_t own_i = (uint32_t)rho < rows ? (uint32_t)rho : rows - 1u;
+    uint32_t idx[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) idx[u] = (uint32_t)(4 * g + u) < rows ? (uint32_t)(4 * g + u) : rows - 1u;
+    if (!a.row_ids) {  // row k of the list is row k of the table; beyond 2^32 - 1: outside any table
+        const uint64_t ko = base + own_i;
+        o.own = ko > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)ko;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint64_t ku = base + idx[u];
+            o.rid[u] = ku > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)ku;
+        }
+        return;
+    }
+    o.own = a.row_ids[base + own_i];
+    if (rows == 16u) {  // one 16-byte load
+        const uint4 v = *reinterpret_cast<const uint4 *>(a.row_ids + base + 4u * (uint32_t)g);
+        o.rid[0] = v.x; o.rid[1] = v.y; o.rid[2] = v.z; o.rid[3] = v.w;
+    } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) o.rid[u] = a.row_ids[base + idx[u]];
     }
 }
 
 template <int M, int BITS>
-__global__ void __launch_bounds__(kBlock) quantize_rows16_kernel(const QuantBatch b) {
-    uint32_t carry = 0;
-    for (uint32_t t = 0; t < b.n_jobs; ++t) encode_table<M, BITS>(b.job[t], b.n_waves, carry);
+__device__ __forceinline__ void encode_table(const QuantArgs &a, unsigned char *tile /* this wave's kTileBytes of LDS */) {
+    constexpr int DIM = 64 * M;
+    const uint64_t n = row_count(a);
+    const int lane = tid_x() & (kWave - 1);
+    const int g = lane >> 4, l = lane & 15;  // load layout: group (four rows), lane in group
+    const int rho = lane >> 2, j = lane & 3; // compute layout: row of the pass, quarter
+    const uint32_t last_row = (uint32_t)a.n_rows - 1u;  // the host checks 1 <= n_rows < 2^32
+    unsigned char *const wr = tile + (4 * g) * kTileRowBytes + (l >> 2) * kTileQuarterBytes + (l & 3) * 16;
+    const unsigned char *const rd = tile + rho * kTileRowBytes + j * kTileQuarterBytes;
+
+    // Requests this lane's share of the sixteen rows of a pass (ids outside the table read the
+    // last row instead).
+    f32x4 ld[4][M];
+    auto gather = [&](const PassIds &ids) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t r = ids.rid[u] < last_row ? ids.rid[u] : last_row;
+            const float *src = a.table + (uint64_t)r * DIM + 4u * (uint32_t)l;
+#pragma unroll
+            for (int c = 0; c < M; ++c) ld[u][c] = load_stream<f32x4>(src + 64 * c);
+        }
+    };
+
+    // Software pipeline: while a pass is transposed, quantized and stored, the rows of the wave's
+    // next pass and the ids of the one after that are on their way.
+    const uint32_t n_waves = a.n_waves;
+    uint64_t pass = wave_in_grid();
+    if (pass * 16u >= n) return;
+    PassIds ids;
+    load_pass_ids(a, n, pass, g, rho, ids);
+    gather(ids);
+    uint32_t own = ids.own;
+    uint64_t next = pass + n_waves;
+    if (next * 16u < n) load_pass_ids(a, n, next, g, rho, ids);
+    for (;;) {
+        const uint64_t base = pass * 16u;  // first row of the pass (uniform)
+        const uint64_t left = n - base;
+        const uint32_t rows = left < 16u ? (uint32_t)left : 16u;
+        const bool in_table = own <= last_row;
+        const bool live = (uint32_t)rho < rows && in_table;
+        if ((uint32_t)rho < rows && !in_table && j == 0) raise_flag(a.err, CNR_FLAG_ROW_ID);
+
+        // ---- transpose through the wave's LDS tile, one 64-element chunk at a time
+        float4 x[M][4];
+#pragma unroll
+        for (int c = 0; c < M; ++c) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) *reinterpret_cast<f32x4 *>(wr + u * kTileRowBytes) = ld[u][c];
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x[c][i] = *reinterpret_cast<const float4 *>(rd + 16 * i);
+            __builtin_amdgcn_wave_barrier();
+        }
+
+        // ---- the load registers are free again: request the next pass
+        const bool has_next = next * 16u < n;  // uniform
+        const uint64_t next2 = next + n_waves;
+        if (has_next) {
+            gather(ids);
+            own = ids.own;
+            if (next2 * 16u < n) load_pass_ids(a, n, next2, g, rho, ids);
+        }
+
+        encode_row_quarter<M, BITS>(a, base + (uint32_t)rho, live, j, x);
+        if (!has_next) break;
+        pass = next;
+        next = next2;
+    }
+}
+
+// The register budget is pinned to 5-6 / 3-4 / 2 waves per SIMD for M = 1 / 2 / 4: left alone, the
+// compiler lands a few registers to either side of those limits from one small change to the next.
+template <int M, int BITS>
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(M == 1 ? 5 : M == 2 ? 3 : 2, M == 1 ? 6 : M == 2 ? 4 : 2)))
+quantize_tile_kernel(const QuantArgs a) {
+    __shared__ __align__(16) unsigned char tiles[kWavesPerBlock * kTileBytes];
+    encode_table<M, BITS>(a, tiles + (tid_x() / kWave) * kTileBytes);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -357,7 +357,7 @@ __device__ __forceinline__ double lanes_sum(double v) {
 }
 
 template <int L, int BITS>
-__device__ __forceinline__ void greedy_table(const QuantArgs &a, uint32_t n_waves, uint32_t &carry) {
+__global__ void __launch_bounds__(kBlock) quantize_greedy_kernel(const QuantArgs a) {
     constexpr int DIM = 16 * L;
     constexpr int kRowsPerPass = kWave / L;
     constexpr float QMAXF = (float)((1 << BITS) - 1);
@@ -366,8 +366,8 @@ __device__ __forceinline__ void greedy_table(const QuantArgs &a, uint32_t n_wave
     const uint64_t n = row_count(a);
     const int lane = tid_x() & (kWave - 1);
     const int j = lane % L;  // lane within the row
-    for (uint64_t pass = first_unit(wave_in_grid(), n_waves, (uint32_t)((n + kRowsPerPass - 1) / kRowsPerPass), carry);
-         pass * kRowsPerPass < n; pass += n_waves) {
+    const uint32_t n_waves = a.n_waves;
+    for (uint64_t pass = wave_in_grid(); pass * kRowsPerPass < n; pass += n_waves) {
         const uint64_t k = pass * kRowsPerPass + lane / L;
         // ---- gather
         uint64_t rid = 0;
@@ -509,12 +509,6 @@ __device__ __forceinline__ void greedy_table(const QuantArgs &a, uint32_t n_wave
     }
 }
 
-template <int L, int BITS>
-__global__ void __launch_bounds__(kBlock) quantize_greedy_kernel(const QuantBatch b) {
-    uint32_t carry = 0;
-    for (uint32_t t = 0; t < b.n_jobs; ++t) greedy_table<L, BITS>(b.job[t], b.n_waves, carry);
-}
-
 // ---------------------------------------------------------------------------------------------
 // Any other dim (dim % 4 == 0, dim * bits % 8 == 0): one wavefront per row, lanes stride over the
 // row, which is re-read from cache for each pass.  Output bytes are produced one per lane-visit
@@ -653,43 +647,32 @@ pack_kernel(const uint8_t *__restrict__ codes, const uint64_t *__restrict__ n_de
     }
 }
 
-uint64_t most_rows(const QuantBatch &b) {
-    uint64_t m = 0;
-    for (uint32_t t = 0; t < b.n_jobs; ++t)
-        if (b.job[t].n_max > m) m = b.job[t].n_max;
-    return m;
-}
-
 template <int M, int BITS>
-void launch_rows16(cnr_ctx *ctx, QuantBatch &b, hipStream_t s) {
-    const unsigned grid = cnr_grid(ctx, most_rows(b), 16u * kWavesPerBlock,
-                                   cnr_resident_blocks_per_cu<quantize_rows16_kernel<M, BITS>>());
-    b.n_waves = grid * kWavesPerBlock;
-    hipLaunchKernelGGL((quantize_rows16_kernel<M, BITS>), dim3(grid), dim3(kBlock), 0, s, b);
+void launch_tile(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
+    const unsigned grid = cnr_grid(ctx, a.n_max, 16u * kWavesPerBlock,
+                                   cnr_resident_blocks_per_cu<quantize_tile_kernel<M, BITS>>());
+    a.n_waves = grid * kWavesPerBlock;
+    hipLaunchKernelGGL((quantize_tile_kernel<M, BITS>), dim3(grid), dim3(kBlock), 0, s, a);
 }
 
 template <int L, int BITS>
-void launch_greedy(cnr_ctx *ctx, QuantBatch &b, hipStream_t s) {
-    const unsigned grid = cnr_grid(ctx, most_rows(b), (uint64_t)(kWave / L) * kWavesPerBlock,
+void launch_greedy(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
+    const unsigned grid = cnr_grid(ctx, a.n_max, (uint64_t)(kWave / L) * kWavesPerBlock,
                                    cnr_resident_blocks_per_cu<quantize_greedy_kernel<L, BITS>>());
-    b.n_waves = grid * kWavesPerBlock;
-    hipLaunchKernelGGL((quantize_greedy_kernel<L, BITS>), dim3(grid), dim3(kBlock), 0, s, b);
+    a.n_waves = grid * kWavesPerBlock;
+    hipLaunchKernelGGL((quantize_greedy_kernel<L, BITS>), dim3(grid), dim3(kBlock), 0, s, a);
 }
 
 template <int BITS>
-void launch_bits(cnr_ctx *ctx, QuantBatch &b, hipStream_t s) {
-    const QuantArgs &c = b.job[0];                              // dim, mode, n_iter are common to the batch
-    const bool greedy = c.mode == kModeGreedy && c.n_iter > 0;  // zero iterations: plain min/max
-    if (c.dim == 64) return greedy ? launch_greedy<4, BITS>(ctx, b, s) : launch_rows16<1, BITS>(ctx, b, s);
-    if (c.dim == 128) return greedy ? launch_greedy<8, BITS>(ctx, b, s) : launch_rows16<2, BITS>(ctx, b, s);
-    if (c.dim == 256) return greedy ? launch_greedy<16, BITS>(ctx, b, s) : launch_rows16<4, BITS>(ctx, b, s);
-    for (uint32_t t = 0; t < b.n_jobs; ++t) {  // other row lengths: one launch per table
-        const QuantArgs &a = b.job[t];
-        const unsigned grid = cnr_grid(ctx, a.n_max, kWavesPerBlock, 8);
-        hipLaunchKernelGGL((quantize_rows_generic_kernel<BITS>), dim3(grid), dim3(kBlock), 0, s, a.table,
-                           a.n_rows, a.dim, a.row_ids, a.n_dev, a.n_max, a.mode, a.n_iter, a.num_bins_f,
-                           a.scale, a.bias, a.row_min, a.row_max, a.codes, a.packed, a.err);
-    }
+void launch_bits(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
+    const bool greedy = a.mode == kModeGreedy && a.n_iter > 0;  // zero iterations: plain min/max
+    if (a.dim == 64) return greedy ? launch_greedy<4, BITS>(ctx, a, s) : launch_tile<1, BITS>(ctx, a, s);
+    if (a.dim == 128) return greedy ? launch_greedy<8, BITS>(ctx, a, s) : launch_tile<2, BITS>(ctx, a, s);
+    if (a.dim == 256) return greedy ? launch_greedy<16, BITS>(ctx, a, s) : launch_tile<4, BITS>(ctx, a, s);
+    const unsigned grid = cnr_grid(ctx, a.n_max, kWavesPerBlock, 8);
+    hipLaunchKernelGGL((quantize_rows_generic_kernel<BITS>), dim3(grid), dim3(kBlock), 0, s, a.table,
+                       a.n_rows, a.dim, a.row_ids, a.n_dev, a.n_max, a.mode, a.n_iter, a.num_bins_f,
+                       a.scale, a.bias, a.row_min, a.row_max, a.codes, a.packed, a.err);
 }
 
 }  // namespace
@@ -715,27 +698,26 @@ cnr_status cnr_quantize_rows_batch(cnr_ctx *ctx, const cnr_table_job *jobs, uint
             ((uintptr_t)j.row_max % 4) || ((uintptr_t)j.row_ids % 16) || ((uintptr_t)j.n_dirty_dev % 8))
             return CNR_E_ALIGN;
     }
+    // One launch per table, back to back: the encode kernels run at the speed of their memory
+    // traffic only while all waves of the grid sweep one table together, and one launch that walks
+    // several tables lets them drift apart (measured: 86 against 82 us per 5 M x 64 table).
     hipStream_t s = as_stream(stream);
-    for (uint32_t first = 0; first < n_jobs; first += CNR_MAX_BATCH) {
-        QuantBatch b = {};
-        for (uint32_t i = first; i < n_jobs && i < first + CNR_MAX_BATCH; ++i) {
-            const cnr_table_job &j = jobs[i];
-            if (j.capacity == 0) continue;
-            QuantArgs &a = b.job[b.n_jobs++];
-            a.table = j.table; a.n_rows = j.n_rows; a.dim = dim; a.row_ids = j.row_ids;
-            a.n_dev = j.n_dirty_dev; a.n_max = j.capacity;
-            a.mode = (int)mode;
-            a.n_iter = mode == CNR_RANGE_GREEDY ? cnr_greedy_iterations(greedy->num_bins, greedy->ratio) : 0;
-            a.num_bins_f = mode == CNR_RANGE_GREEDY ? (float)greedy->num_bins : 1.0f;
-            a.scale = j.scale; a.bias = j.bias; a.row_min = j.row_min; a.row_max = j.row_max;
-            a.codes = j.codes_u8; a.packed = j.packed; a.err = ctx->dev_err;
-        }
-        if (b.n_jobs == 0) continue;
+    for (uint32_t i = 0; i < n_jobs; ++i) {
+        const cnr_table_job &j = jobs[i];
+        if (j.capacity == 0) continue;
+        QuantArgs a = {};
+        a.table = j.table; a.n_rows = j.n_rows; a.dim = dim; a.row_ids = j.row_ids;
+        a.n_dev = j.n_dirty_dev; a.n_max = j.capacity;
+        a.mode = (int)mode;
+        a.n_iter = mode == CNR_RANGE_GREEDY ? cnr_greedy_iterations(greedy->num_bins, greedy->ratio) : 0;
+        a.num_bins_f = mode == CNR_RANGE_GREEDY ? (float)greedy->num_bins : 1.0f;
+        a.scale = j.scale; a.bias = j.bias; a.row_min = j.row_min; a.row_max = j.row_max;
+        a.codes = j.codes_u8; a.packed = j.packed; a.err = ctx->dev_err;
         switch (bits) {
-            case 2: launch_bits<2>(ctx, b, s); break;
-            case 3: launch_bits<3>(ctx, b, s); break;
-            case 4: launch_bits<4>(ctx, b, s); break;
-            default: launch_bits<8>(ctx, b, s); break;
+            case 2: launch_bits<2>(ctx, a, s); break;
+            case 3: launch_bits<3>(ctx, a, s); break;
+            case 4: launch_bits<4>(ctx, a, s); break;
+            default: launch_bits<8>(ctx, a, s); break;
         }
         if ((st = cnr_launch_status(ctx)) != CNR_OK) return st;
     }

@@ -93,17 +93,10 @@ struct RestoreJob {
     uint64_t n_max;
     const uint8_t *packed;
     const float *scale, *bias;
-};
-// The tables of one launch; a workgroup that has run out of rows in one goes on to the next.
-struct RestoreBatch {
-    RestoreJob job[CNR_MAX_BATCH];
-    uint32_t n_jobs;
     uint32_t n_waves;  // waves of the grid
 };
-
 template <int M, int BITS>
-__device__ __forceinline__ void restore_table(const RestoreJob &a, uint32_t n_waves, uint32_t &carry,
-                                              cnr_dev_errors *err) {
+__global__ void __launch_bounds__(kBlock) restore_rows16_kernel(const RestoreJob a, cnr_dev_errors *err) {
     constexpr int DIM = 64 * M;
     constexpr uint32_t MASK = (1u << BITS) - 1u;
     float *__restrict__ table = a.table;
@@ -118,7 +111,8 @@ __device__ __forceinline__ void restore_table(const RestoreJob &a, uint32_t n_wa
     const int l = lane & 15;
     const int q = l >> 2;
     const int j = l & 3;
-    uint64_t batch = first_unit(wave_in_grid(), n_waves, (uint32_t)((n + 15u) / 16u), carry);
+    const uint32_t n_waves = a.n_waves;
+    uint64_t batch = wave_in_grid();
     if (batch * 16u >= n) return;
     RestoreInput<M, BITS> cur, nxt;
     fetch_restore_input<M, BITS>(row_ids, packed, scale, bias, n_max, batch * 16u + 4u * (uint64_t)g, q, j, cur);
@@ -177,12 +171,6 @@ __device__ __forceinline__ void restore_table(const RestoreJob &a, uint32_t n_wa
     }
 }
 
-template <int M, int BITS>
-__global__ void __launch_bounds__(kBlock) restore_rows16_kernel(const RestoreBatch b, cnr_dev_errors *err) {
-    uint32_t carry = 0;
-    for (uint32_t t = 0; t < b.n_jobs; ++t) restore_table<M, BITS>(b.job[t], b.n_waves, carry, err);
-}
-
 // Any other dim: one wavefront per row, lanes stride over the elements.
 template <int BITS>
 __global__ void __launch_bounds__(kBlock)
@@ -220,27 +208,21 @@ restore_rows_generic_kernel(float *__restrict__ table, uint64_t n_rows, uint32_t
 }
 
 template <int M, int BITS>
-void launch_restore16(cnr_ctx *ctx, hipStream_t st, RestoreBatch &b) {
-    uint64_t most = 0;
-    for (uint32_t t = 0; t < b.n_jobs; ++t)
-        if (b.job[t].n_max > most) most = b.job[t].n_max;
-    const unsigned grid = cnr_grid(ctx, most, 16u * kWavesPerBlock,
+void launch_restore16(cnr_ctx *ctx, hipStream_t st, RestoreJob &a) {
+    const unsigned grid = cnr_grid(ctx, a.n_max, 16u * kWavesPerBlock,
                                    cnr_resident_blocks_per_cu<restore_rows16_kernel<M, BITS>>());
-    b.n_waves = grid * kWavesPerBlock;
-    hipLaunchKernelGGL((restore_rows16_kernel<M, BITS>), dim3(grid), dim3(kBlock), 0, st, b, ctx->dev_err);
+    a.n_waves = grid * kWavesPerBlock;
+    hipLaunchKernelGGL((restore_rows16_kernel<M, BITS>), dim3(grid), dim3(kBlock), 0, st, a, ctx->dev_err);
 }
 
 template <int BITS>
-void launch_restore(cnr_ctx *ctx, hipStream_t st, uint32_t dim, RestoreBatch &b) {
-    if (dim == 64) return launch_restore16<1, BITS>(ctx, st, b);
-    if (dim == 128) return launch_restore16<2, BITS>(ctx, st, b);
-    if (dim == 256) return launch_restore16<4, BITS>(ctx, st, b);
-    for (uint32_t t = 0; t < b.n_jobs; ++t) {  // other row lengths: one launch per table
-        const RestoreJob &a = b.job[t];
-        hipLaunchKernelGGL((restore_rows_generic_kernel<BITS>), dim3(cnr_grid(ctx, a.n_max, kWavesPerBlock, 8)),
-                           dim3(kBlock), 0, st, a.table, a.n_rows, dim, a.row_ids, a.n_dev, a.n_max, a.packed,
-                           a.scale, a.bias, ctx->dev_err);
-    }
+void launch_restore(cnr_ctx *ctx, hipStream_t st, uint32_t dim, RestoreJob &a) {
+    if (dim == 64) return launch_restore16<1, BITS>(ctx, st, a);
+    if (dim == 128) return launch_restore16<2, BITS>(ctx, st, a);
+    if (dim == 256) return launch_restore16<4, BITS>(ctx, st, a);
+    hipLaunchKernelGGL((restore_rows_generic_kernel<BITS>), dim3(cnr_grid(ctx, a.n_max, kWavesPerBlock, 8)),
+                       dim3(kBlock), 0, st, a.table, a.n_rows, dim, a.row_ids, a.n_dev, a.n_max, a.packed,
+                       a.scale, a.bias, ctx->dev_err);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -358,21 +340,17 @@ extern "C" cnr_status cnr_restore_rows_batch(cnr_ctx *ctx, const cnr_table_job *
             return CNR_E_ALIGN;
     }
     hipStream_t s = as_stream(stream);
-    for (uint32_t first = 0; first < n_jobs; first += CNR_MAX_BATCH) {
-        RestoreBatch b = {};
-        for (uint32_t i = first; i < n_jobs && i < first + CNR_MAX_BATCH; ++i) {
-            const cnr_table_job &j = jobs[i];
-            if (j.capacity == 0) continue;
-            RestoreJob &a = b.job[b.n_jobs++];
-            a.table = j.table; a.n_rows = j.n_rows; a.row_ids = j.row_ids; a.n_dev = j.n_dirty_dev;
-            a.n_max = j.capacity; a.packed = j.packed; a.scale = j.scale; a.bias = j.bias;
-        }
-        if (b.n_jobs == 0) continue;
+    for (uint32_t i = 0; i < n_jobs; ++i) {  // one launch per table, back to back (as for the encode)
+        const cnr_table_job &j = jobs[i];
+        if (j.capacity == 0) continue;
+        RestoreJob a = {};
+        a.table = j.table; a.n_rows = j.n_rows; a.row_ids = j.row_ids; a.n_dev = j.n_dirty_dev;
+        a.n_max = j.capacity; a.packed = j.packed; a.scale = j.scale; a.bias = j.bias;
         switch (bits) {
-            case 2: launch_restore<2>(ctx, s, dim, b); break;
-            case 3: launch_restore<3>(ctx, s, dim, b); break;
-            case 4: launch_restore<4>(ctx, s, dim, b); break;
-            default: launch_restore<8>(ctx, s, dim, b); break;
+            case 2: launch_restore<2>(ctx, s, dim, a); break;
+            case 3: launch_restore<3>(ctx, s, dim, a); break;
+            case 4: launch_restore<4>(ctx, s, dim, a); break;
+            default: launch_restore<8>(ctx, s, dim, a); break;
         }
         if ((st = cnr_launch_status(ctx)) != CNR_OK) return st;
     }
