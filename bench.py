@@ -61,6 +61,12 @@ def restore_bytes_per_row(dim: int, bits: int) -> int:
     return 4 + dim * bits // 8 + 8 + 4 * dim
 
 
+def B_prepare_mark(batch, indices):
+    """One prepared batched mark of `indices` (a list of tensors, one per table of `batch`)."""
+    jobs = batch.jobs(indices=indices)
+    return P.prepare("cnr_mark_touched_batch", batch.ctx, jobs, len(indices), P.CNR_IDX_I64, None)
+
+
 class Timer:
     """Pairs of events on the current stream, summed per label.  Events are created up front so that
     the timed loop only records them."""
@@ -230,6 +236,43 @@ def main() -> int:
         "roofline": roofline,
         "stages_ms_per_step": stages,
     }
+
+    # ---- context for the roofline: what a plain device-to-device copy reaches on this machine -----------
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(5):
+        dst.copy_(src)
+    b.record()
+    torch.cuda.synchronize()
+    out["roofline"]["copy_ceiling_GBps"] = round(5 * 2 * src.numel() * 4 / (a.elapsed_time(b) * 1e-3) / 1e9, 1)
+    del src, dst
+
+    # ---- marking as training issues it: one short index stream per table and iteration -------------
+    per_iter = 40960                                            # 2048 x 20 look-ups (configuration 2)
+    small = [s_[:per_iter].contiguous() for s_ in streams]
+    if batched:
+        small_batched = B_prepare_mark(batch, small)
+    small_single = [P.prepare("cnr_mark_touched", ctx, cks[ti].bitmap, w.n_rows, small[ti], per_iter, P.CNR_IDX_I64,
+                              None, None) for ti in range(n_tables)]
+
+    def time_calls(fns, reps=50):
+        for f in fns:
+            f()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            for f in fns:
+                f()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps * 1e6
+    mark_us = {"per_table_calls_us": round(time_calls(small_single), 2)}
+    if batched:
+        mark_us["batched_call_us"] = round(time_calls([small_batched]), 2)
+    out["mark_per_iteration"] = dict(workload="%d tables x %d int64 look-ups per iteration into %d-row bitmaps"
+                                              % (n_tables, per_iter, w.n_rows), **mark_us)
 
     # ---- greedy range search on the same tables (ALU-bound) ---------------------------------------
     if not args.no_greedy and w.num_bins:
