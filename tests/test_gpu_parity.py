@@ -554,3 +554,46 @@ def test_row_count_limit_is_checked_on_the_host(ctx):
     with pytest.raises(ValueError):                            # the binding's own size check comes first
         P.cnr_quantize_rows(ctx, t, 1 << 32, 64, None, None, 4, 4, P.CNR_RANGE_MINMAX, None, s, s)
     _poll_clean(ctx)
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("dim", [64, 128, 256])
+@pytest.mark.parametrize("n", [1, 5, 16, 19, 33])
+def test_ragged_passes_with_ids_at_every_width(ctx, bits, dim, n):
+    # a 16-row pass that is partly empty, with row ids given, one of them outside the table, and
+    # output buffers exactly n rows long (nothing may be written past them: the next tensors would
+    # catch it in their own checks, and the sentinel rows below do so here)
+    n_rows = 300
+    gt = GpuTable(ctx, _table(n_rows, dim, 90 + bits + dim + n))
+    rng = np.random.default_rng(n * 1000 + dim + bits)
+    ids_np = np.sort(rng.choice(n_rows, size=n, replace=False)).astype(np.uint32)
+    bad_at = n // 2
+    ids_bad = ids_np.copy()
+    ids_bad[bad_at] = n_rows + 5
+    prb = P.cnr_packed_row_bytes(dim, bits)
+    pad = 2                                                     # sentinel rows behind the n real ones
+    ids = torch.zeros(max(16, n), dtype=torch.int32, device=DEV)     # 16-byte aligned, >= n entries
+    ids[:n] = torch.from_numpy(ids_bad.view(np.int32)).to(DEV)
+    scale = torch.full((n + pad,), -7.0, device=DEV)
+    bias = torch.full((n + pad,), -7.0, device=DEV)
+    rmin = torch.full((n + pad,), -7.0, device=DEV)
+    rmax = torch.full((n + pad,), -7.0, device=DEV)
+    packed = torch.full(((n + pad) * prb,), 0xEE, dtype=torch.uint8, device=DEV)
+    codes = torch.full(((n + pad) * dim,), 0xEE, dtype=torch.uint8, device=DEV)
+    P.cnr_quantize_rows(ctx, gt.table, n_rows, dim, ids, None, n, bits, P.CNR_RANGE_MINMAX, None, scale, bias,
+                        rmin, rmax, codes, packed)
+    st, _, flags = P.cnr_poll_errors(ctx)
+    assert st == P.CNR_E_ROW_ID and flags == P.CNR_FLAG_ROW_ID
+    good = [k for k in range(n) if k != bad_at]
+    for t in (scale, bias, rmin, rmax):
+        assert torch.all(t[n:] == -7.0) and t[bad_at] == -7.0
+    assert torch.all(packed.reshape(n + pad, prb)[[bad_at, n, n + 1]] == 0xEE)
+    assert torch.all(codes.reshape(n + pad, dim)[[bad_at, n, n + 1]] == 0xEE)
+    if good:
+        ora = O.quantize_rows(gt.host, ids_np[good], bits)
+        got = dict(scale=scale.cpu().numpy()[good], bias=bias.cpu().numpy()[good],
+                   row_min=rmin.cpu().numpy()[good], row_max=rmax.cpu().numpy()[good],
+                   codes=codes.cpu().numpy().reshape(n + pad, dim)[good])
+        compare_quantized(gt.host[ids_np[good]], got, ora, bits, what="ragged n=%d d%d b%d" % (n, dim, bits))
+        assert np.array_equal(packed.cpu().numpy().reshape(n + pad, prb)[good], O.pack(got["codes"], bits))
+    _poll_clean(ctx)
