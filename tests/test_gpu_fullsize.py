@@ -1,5 +1,6 @@
-"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration the
-benchmark times (shared flag-byte scratch for marking, prepared launches, device-side row counts).
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configurations the
+benchmark times: one prepared batched call per stage over all tables (its default), and prepared
+per-table calls with a shared flag-byte scratch for marking; device-side row counts in both.
 The tracking bitmap and the dirty-row list are compared in full; the encoded rows on a sample the
 oracle can quantize row by row (every position of the first and last wave batches plus a random
 draw); restored tables on the same sample plus rows that must stay untouched."""
@@ -139,3 +140,43 @@ def test_cfg5_table_8bit_and_4bit(ctx):
     table = synth.make_table(w, 0, 5, DEV)
     batches = list(synth.lookup_batches(w, 0, 5, DEV, iterations=1000))
     _check_table(ctx, w, table, batches, (8, 4), sample=60_000, what="cfg5 table 0")
+
+
+def test_cfg4_all_tables_through_the_batched_calls(ctx):
+    # the launch configuration the benchmark times by default: all eight tables of configuration 4
+    # through one prepared batched call per stage, each table with a flag-byte scratch and a stale
+    # table of its own
+    w = synth.WORKLOADS["cfg4"]
+    bits, seed = 4, 4
+    tables = [synth.make_table(w, ti, seed, DEV) for ti in range(w.n_tables)]
+    streams = [torch.cat([b.reshape(-1) for b in synth.lookup_batches(w, ti, seed, DEV)]) for ti in range(w.n_tables)]
+    cks = [P.TableCheckpointer(ctx, w.n_rows, w.dim, device=DEV,
+                               mark_scratch=P.TableCheckpointer.new_mark_scratch(w.n_rows, DEV))
+           for _ in range(w.n_tables)]
+    encs = [c.alloc_output(bits, want_range=True) for c in cks]
+    stale = [torch.full_like(t, -3.0) for t in tables]
+    batch = P.BatchCheckpointer(ctx, cks)
+    for _ in range(2):                                          # a second step must give the same result
+        for _, call in batch.prepare_step(streams, tables, encs, restore_into=stale):
+            call()
+    torch.cuda.synchronize()
+    for ti in range(w.n_tables):
+        what = "cfg4 batched table %d" % ti
+        bm = O.new_bitmap(w.n_rows)
+        O.mark_touched(bm, w.n_rows, streams[ti].cpu().numpy())
+        ids, n = O.compact_dirty(bm, w.n_rows)
+        assert np.array_equal(u32(cks[ti].bitmap)[:bm.size], bm), what + " bitmap"
+        assert int(cks[ti].n_dirty.item()) == n and np.array_equal(u32(cks[ti].row_ids)[:n], ids), what
+        assert not cks[ti].mark_scratch.any()
+        pos = _sample_positions(n, 30_000, ti)
+        sel = torch.from_numpy(ids[pos].astype(np.int64)).to(DEV)
+        rows = tables[ti].index_select(0, sel).cpu().numpy()
+        got = _encoded_sample(encs[ti], pos, w.dim, bits)
+        ora = O.quantize_rows(rows, None, bits, n_threads=8)
+        compare_quantized(rows, got, ora, bits, what=what)
+        back = stale[ti].index_select(0, sel).cpu().numpy()
+        assert np.array_equal(back, O.dequantize(got["codes"], got["scale"], got["bias"])), what + " restore"
+        untouched = np.setdiff1d(np.arange(0, w.n_rows, 100), ids)
+        assert torch.all(stale[ti].index_select(0, torch.from_numpy(untouched).to(DEV)) == -3.0)
+    st, bad, flags = P.cnr_poll_errors(ctx)
+    assert (st, bad, flags) == (P.CNR_OK, 0, 0)
