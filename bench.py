@@ -40,15 +40,17 @@ ISSUE_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # one vector instruction per lane
 # HBM traffic of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), in bytes
 # per dirty row, valid only for the kernel source whose hash is recorded with it.
 TRAFFIC_PER_ROW = {
-    # sha256 of csrc/cnr_quantize.hip : (workload, bytes per dirty row)
+    # sha256 of csrc/cnr_quantize.hip without comments and white space : (workload, bytes per dirty row)
     # (2.000 * 190490.1 KiB FETCH_SIZE + 1.000 * 60149.6 KiB WRITE_SIZE) / 1,500,122 rows per launch
-    "3495a6330659a0721fb3a26dcdb4c7cfbc01163818a4f8f8baf3a4820b6cffdd": ("cfg4/b4", 301.12),
+    "87aacee2652dfb565644a9044f8faacef001f1b7f29951a3cf94da7def773f33": ("cfg4/b4", 301.12),
 }
 
 
 def _kernel_hash() -> str:
-    with open(os.path.join(ROOT, "paper_2010_08679_amd", "csrc", "cnr_quantize.hip"), "rb") as f:
-        return hashlib.sha256(f.read()).hexdigest()
+    """Hash of the encode kernels' source without comments and white space."""
+    with open(os.path.join(ROOT, "paper_2010_08679_amd", "csrc", "cnr_quantize.hip"), "r") as f:
+        code = "".join(line.split("//")[0] for line in f)
+    return hashlib.sha256("".join(code.split()).encode()).hexdigest()
 
 
 def encode_bytes_per_row(dim: int, bits: int) -> int:

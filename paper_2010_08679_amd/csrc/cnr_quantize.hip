@@ -4,7 +4,7 @@
 // formulas): fp32 throughout, one rounding per operation (the build disables contraction into fused
 // multiply-adds), round-half-even, fp32 denormals kept; row minimum, maximum, scale and bias are
 // bit-exact; codes may differ from the divide-and-round definition by one step where the quotient
-// lies within rounding distance of a half-integer (see the bulk kernel).  Error sums that only rank
+// lies within rounding distance of a half-integer (see the tile kernel).  Error sums that only rank
 // candidate ranges are accumulated in fp64.
 #include <type_traits>
 
@@ -54,7 +54,7 @@ __device__ __forceinline__ double fq_sq_err(float x, float lo, float hi, float s
 }
 
 // ---------------------------------------------------------------------------------------------
-// Bulk kernel (min/max and symmetric range), dim = 64 * M.  Bound by HBM.
+// Tile kernel (min/max and symmetric range), dim = 64 * M.  Bound by HBM.
 //
 // A wave works on sixteen consecutive dirty rows per pass, in two lane layouts with a transpose
 // through LDS between them:
@@ -67,8 +67,9 @@ __device__ __forceinline__ double fq_sq_err(float x, float lo, float hi, float s
 //                   used, and a lane's sixteen codes are 2 * BITS contiguous bytes of the packed row,
 //                   so a wave's packed output is one contiguous run.
 // The transpose is private to the wave (LDS operations of one wave complete in order, so no
-// barrier is needed); a row's four quarters sit 80 bytes apart and rows 320 bytes apart, which keeps
-// the eight lanes that the LDS serves together on different banks in both directions.
+// barrier is needed); a row's four quarters sit 80 bytes apart and rows 320 bytes apart, which
+// spreads the lanes that the LDS serves together over its banks in both directions (what conflicts
+// remain cost a few LDS cycles per instruction, far from limiting).
 //
 // The kernel has to stay clear of the vector-ALU issue limit (a wave64 instruction occupies a SIMD
 // for four cycles) to run at the speed of its memory traffic, so the per-element work is pared down:
@@ -320,9 +321,10 @@ quantize_tile_kernel(const QuantArgs a) {
 //
 // Every lane owns sixteen consecutive elements (four 16-byte loads) of one row, L neighbouring lanes
 // own the row, a wave handles 64 / L consecutive dirty rows per pass.  A candidate's error is summed
-// over a lane's sixteen registers and then over the L lanes with log2(L) DPP exchanges, a quarter of
-// the cross-lane work the bulk kernel's layout would need, and a lane's sixteen codes are exactly
-// 2 * BITS contiguous bytes of the packed row, so the output needs no transpose.
+// over a lane's sixteen registers and then over the L lanes with log2(L) DPP exchanges, and a lane's
+// sixteen codes are exactly 2 * BITS contiguous bytes of the packed row.  The rows are read in this
+// layout directly (16-byte loads 64 bytes apart): the kernel is far from the memory system's limits,
+// so the transpose through LDS that the tile kernel pays for coalesced loads would buy nothing.
 // A candidate is evaluated with the cheapest sequence that still reproduces F_Q's codes: the scale
 // (range / (2^b - 1)) and the quotient (x - lo) / scale are formed by a reciprocal multiply followed
 // by one FMA residual correction (q' = q + (a - q*b) * (1/b)), which yields the correctly rounded
