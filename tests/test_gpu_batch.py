@@ -224,3 +224,49 @@ def test_capacity_overflow_in_one_table_of_a_batch(ctx):
         m = min(n, c.capacity)
         assert np.array_equal(u32(c.row_ids)[:m], ids[:m])
     _poll_clean(ctx)
+
+
+def test_batched_step_replays_from_a_hip_graph(ctx):
+    # the batched calls only enqueue kernels on the caller's stream (job descriptors travel by value in
+    # the launch), so a whole step over several tables can be captured once and replayed; inputs are
+    # refreshed in place between replays and every replay is checked against the oracle
+    sizes, dim, bits = [90_001, 20_000, 50], 64, 4
+    T = _Tables(ctx, sizes, dim, seed=21, n_idx=[200_000, 5_000, 40])
+    outs = _outputs(T.batched, bits)
+    stale = [torch.zeros_like(t) for t in T.tables]
+
+    def step():                                                 # prepared calls hold the stream that is
+        for _, call in T.batch.prepare_step(T.idx, T.tables, outs, restore_into=stale):  # current here
+            call()
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                                  # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    g = torch.Generator(device=DEV).manual_seed(77)
+    for rep in range(3):
+        for i, n_rows in enumerate(sizes):                      # eager work between the replays
+            T.idx[i].copy_(torch.randint(0, n_rows, (T.idx[i].numel(),), generator=g, device=DEV))
+            T.tables[i].mul_(1.0 + 0.1 * (rep + 1))
+            stale[i].fill_(float(rep))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, n_rows in enumerate(sizes):
+            host = T.tables[i].cpu().numpy()
+            _, ids, n = T.oracle_track(i)
+            c = T.batched[i]
+            assert int(c.n_dirty.item()) == n and np.array_equal(u32(c.row_ids)[:n], ids)
+            got = _host(outs[i], n, dim, bits)
+            ora = O.quantize_rows(host, ids, bits, n_threads=8)
+            compare_quantized(host[ids], got, ora, bits, what="replay %d table %d" % (rep, i))
+            want = np.full_like(host, float(rep))
+            O.restore_rows(want, ids, bits, got["packed"], got["scale"], got["bias"])
+            assert np.array_equal(stale[i].cpu().numpy(), want)
+            assert not c.mark_scratch.any()
+    _poll_clean(ctx)
