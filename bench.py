@@ -353,6 +353,17 @@ def main() -> int:
                                "sample": "tables 0-%d of %d (%d rows each, %d dirty in all): mark+compact+%d-bit "
                                          "min/max quantize+pack+restore; quantize and restore on %d threads, "
                                          "the rest on one" % (n_cpu_tables - 1, n_tables, w.n_rows, cpu_rows, bits, threads)}
+        # the same oracle on one thread, on a smaller sample of the last table's dirty rows
+        m1 = min(n, 200_000)
+        t0 = time.perf_counter()
+        q1 = O.quantize_rows(host_table, ids[:m1], bits, n_threads=1)
+        pk1 = O.pack(q1["codes"], bits)
+        O.restore_rows(host_stale, ids[:m1], bits, pk1, q1["scale"], q1["bias"], n_threads=1)
+        s1 = time.perf_counter() - t0
+        out["cpu_baseline"]["one_thread"] = {"value": round(m1 * w.dim * 4 / s1 / 1e9, 4), "unit": "GB/s", "cores": 1,
+                                             "sample": "quantize+pack+restore of the first %d dirty rows of table %d"
+                                                       % (m1, n_cpu_tables - 1)}
+        del q1, pk1
         ti = n_cpu_tables - 1
         # the GPU result for the same table must be what the oracle produced
         cks[ti].clear(); cks[ti].mark(streams[ti]); cks[ti].compact(); cks[ti].encode(tables[ti], encs[ti])
