@@ -512,9 +512,10 @@ __global__ void __launch_bounds__(kBlock) quantize_greedy_kernel(const QuantArgs
 }
 
 // ---------------------------------------------------------------------------------------------
-// Any other dim (dim % 4 == 0, dim * bits % 8 == 0): one wavefront per row, lanes stride over the
-// row, which is re-read from cache for each pass.  Output bytes are produced one per lane-visit
-// from the codes they cover, so no staging or barrier is needed.
+// Greedy search at any other dim (dim % 4 == 0, dim * bits % 8 == 0): one wavefront per row, lanes
+// stride over the row, which is re-read from cache for each candidate.  Output bytes are produced
+// one per lane-visit from the codes they cover, so no staging or barrier is needed.  Divides as F_Q
+// is written.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ float wave_min(float v) {
     for (int off = 32; off > 0; off >>= 1) v = fminf(v, __shfl_xor(v, off));
@@ -620,6 +621,133 @@ quantize_rows_generic_kernel(const float *__restrict__ table, uint64_t n_rows, u
 }
 
 // ---------------------------------------------------------------------------------------------
+// Other row lengths, min/max and symmetric range: LPR lanes per row (a power of two, at least the
+// row's number of 16-byte units up to 64), 64 / LPR rows per wave and pass; lane j takes the
+// units j, j + LPR, ... of its row.  The row is read twice, for its range and to quantize (the second
+// time from cache), so nothing depends on its length; a unit's four codes are 4 * BITS bits, stored
+// as one, two or four bytes, and at 3 bits even lanes store three bytes for themselves and their
+// right neighbour.  Same arithmetic as the tile kernel.
+// ---------------------------------------------------------------------------------------------
+template <int LPR>
+__device__ __forceinline__ float lpr_min(float v) {
+    v = fminf(v, dpp_f<0xB1>(v));
+    v = fminf(v, dpp_f<0x4E>(v));
+    if constexpr (LPR >= 8) v = fminf(v, dpp_f<0x141>(v));
+    if constexpr (LPR >= 16) v = fminf(v, dpp_f<0x140>(v));
+    if constexpr (LPR >= 32) v = fminf(v, __shfl_xor(v, 16));
+    if constexpr (LPR >= 64) v = fminf(v, __shfl_xor(v, 32));
+    return v;
+}
+template <int LPR>
+__device__ __forceinline__ float lpr_max(float v) {
+    v = fmaxf(v, dpp_f<0xB1>(v));
+    v = fmaxf(v, dpp_f<0x4E>(v));
+    if constexpr (LPR >= 8) v = fmaxf(v, dpp_f<0x141>(v));
+    if constexpr (LPR >= 16) v = fmaxf(v, dpp_f<0x140>(v));
+    if constexpr (LPR >= 32) v = fmaxf(v, __shfl_xor(v, 16));
+    if constexpr (LPR >= 64) v = fmaxf(v, __shfl_xor(v, 32));
+    return v;
+}
+
+template <int LPR, int BITS>
+__global__ void __launch_bounds__(kBlock) quantize_strided_kernel(const QuantArgs a) {
+    constexpr int kRowsPerPass = kWave / LPR;
+    constexpr float QMAXF = (float)((1 << BITS) - 1);
+    constexpr float MAGIC = 12582912.0f;          // 1.5 * 2^23 (see the tile kernel)
+    constexpr uint32_t MAGIC_BITS = 0x4B400000u;
+    constexpr uint32_t MERGED_BIAS = MAGIC_BITS * (1u + (1u << BITS) + (1u << (2 * BITS)) + (1u << (3 * BITS)));
+    constexpr uint32_t MERGED_BIAS8 = MAGIC_BITS * (1u + (1u << 8) + (1u << 16) + (1u << 24));
+    const uint64_t n = row_count(a);
+    const uint32_t dim = a.dim, n4 = dim / 4;      // 16-byte units per row
+    const uint64_t P = (uint64_t)dim * BITS / 8;   // packed bytes per row
+    const int lane = tid_x() & (kWave - 1);
+    const uint32_t j = lane % LPR;
+    const uint32_t last_row = (uint32_t)a.n_rows - 1u;
+    const uint32_t n_waves = a.n_waves;
+    for (uint64_t pass = wave_in_grid(); pass * kRowsPerPass < n; pass += n_waves) {
+        const uint64_t k = pass * kRowsPerPass + lane / LPR;
+        const uint64_t kc = k < n ? k : n - 1;     // rows past the end repeat the last one; nothing of theirs is stored
+        uint32_t rid;
+        if (a.row_ids)
+            rid = a.row_ids[kc];
+        else
+            rid = kc > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)kc;
+        const bool in_table = rid <= last_row;
+        const bool live = k < n && in_table;
+        if (k < n && !in_table && j == 0) raise_flag(a.err, CNR_FLAG_ROW_ID);
+        const float4 *row = reinterpret_cast<const float4 *>(a.table + (uint64_t)(in_table ? rid : last_row) * dim);
+
+        // ---- row minimum / maximum (every lane starts from the row's first unit, so idle lanes are neutral)
+        const float4 first = row[0];
+        float mn = fminf(fminf(first.x, first.y), fminf(first.z, first.w));
+        float mx = fmaxf(fmaxf(first.x, first.y), fmaxf(first.z, first.w));
+        for (uint32_t u = j; u < n4; u += LPR) {
+            const float4 v = row[u];
+            mn = fminf(fminf(mn, v.x), fminf(v.y, fminf(v.z, v.w)));
+            mx = fmaxf(fmaxf(mx, v.x), fmaxf(v.y, fmaxf(v.z, v.w)));
+        }
+        const float X_min = lpr_min<LPR>(mn) + 0.0f;  // -0.0 -> +0.0
+        const float X_max = lpr_max<LPR>(mx) + 0.0f;
+        float lo = X_min, hi = X_max;
+        if (a.mode == kModeSymmetric) {
+            const float m = fmaxf(fabsf(X_min), fabsf(X_max));
+            lo = -m + 0.0f;
+            hi = m;
+        }
+        const float scale = (hi - lo) / QMAXF;
+        {
+            float *dst = j == 0 ? a.scale : j == 1 ? a.bias : j == 2 ? a.row_min : a.row_max;
+            const float v = j == 0 ? scale : j == 1 ? lo : j == 2 ? X_min : X_max;
+            if (j < 4 && dst && live) dst[k] = v;
+        }
+        const float f = scale < 0x1p-100f ? 0x1p120f : scale > 0x1p100f ? 0x1p-120f : 1.0f;
+        const float fscale = scale * f;
+        const float inv = scale == 0.0f ? 0.0f : 1.0f / fscale;  // scale 0: every code 0
+        auto biased = [&](float xv) -> uint32_t {  // MAGIC_BITS + round((x - lo) / scale)
+            const float d0 = (xv - lo) * f;
+            float t = d0 * inv;
+            if constexpr (BITS == 8) t = fmaf(fmaf(-t, fscale, d0), inv, t);
+            return __float_as_uint(t + MAGIC);
+        };
+
+        // ---- quantize unit by unit; all lanes take every trip so that the 3-bit exchange has partners
+        const uint32_t trips = (n4 + LPR - 1) / LPR;
+        for (uint32_t trip = 0; trip < trips; ++trip) {
+            const uint32_t u = j + trip * LPR;
+            const bool mine = u < n4;
+            const float4 v = row[mine ? u : 0];
+            const uint32_t b0 = biased(v.x), b1 = biased(v.y), b2 = biased(v.z), b3 = biased(v.w);
+            uint32_t m = (b3 << BITS) + b2;
+            m = (m << BITS) + b1;
+            const uint32_t h = (m << BITS) + b0 - MERGED_BIAS;  // 4 * BITS bits
+            const bool store = mine && live;
+            if (a.codes && store)
+                *reinterpret_cast<uint32_t *>(a.codes + k * (uint64_t)dim + 4 * u) =
+                    (((((b3 << 8) + b2) << 8) + b1) << 8) + b0 - MERGED_BIAS8;
+            if (a.packed) {
+                uint8_t *out = a.packed + k * P;
+                if constexpr (BITS == 8) {
+                    if (store) *reinterpret_cast<uint32_t *>(out + 4 * u) = h;
+                } else if constexpr (BITS == 4) {
+                    if (store) *reinterpret_cast<uint16_t *>(out + 2 * u) = (uint16_t)h;
+                } else if constexpr (BITS == 2) {
+                    if (store) out[u] = (uint8_t)h;
+                } else {  // 3 bits: units come in pairs (dim % 8 == 0); the even one stores both
+                    const uint32_t nb = (uint32_t)dpp_i<0xB1>((int)h);  // lane ^ 1: unit u + 1
+                    if (store && !(u & 1)) {
+                        const uint32_t w = h | (nb << 12);
+                        uint8_t *o3 = out + 3 * (u >> 1);
+                        o3[0] = (uint8_t)w;
+                        o3[1] = (uint8_t)(w >> 8);
+                        o3[2] = (uint8_t)(w >> 16);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Stand-alone dense packing of one-code-per-byte input: one output byte per thread-visit.
 // ---------------------------------------------------------------------------------------------
 template <int BITS>
@@ -665,16 +793,33 @@ void launch_greedy(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
     hipLaunchKernelGGL((quantize_greedy_kernel<L, BITS>), dim3(grid), dim3(kBlock), 0, s, a);
 }
 
+template <int LPR, int BITS>
+void launch_strided(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
+    const unsigned grid = cnr_grid(ctx, a.n_max, (uint64_t)(kWave / LPR) * kWavesPerBlock,
+                                   cnr_resident_blocks_per_cu<quantize_strided_kernel<LPR, BITS>>());
+    a.n_waves = grid * kWavesPerBlock;
+    hipLaunchKernelGGL((quantize_strided_kernel<LPR, BITS>), dim3(grid), dim3(kBlock), 0, s, a);
+}
+
 template <int BITS>
 void launch_bits(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
     const bool greedy = a.mode == kModeGreedy && a.n_iter > 0;  // zero iterations: plain min/max
     if (a.dim == 64) return greedy ? launch_greedy<4, BITS>(ctx, a, s) : launch_tile<1, BITS>(ctx, a, s);
     if (a.dim == 128) return greedy ? launch_greedy<8, BITS>(ctx, a, s) : launch_tile<2, BITS>(ctx, a, s);
     if (a.dim == 256) return greedy ? launch_greedy<16, BITS>(ctx, a, s) : launch_tile<4, BITS>(ctx, a, s);
-    const unsigned grid = cnr_grid(ctx, a.n_max, kWavesPerBlock, 8);
-    hipLaunchKernelGGL((quantize_rows_generic_kernel<BITS>), dim3(grid), dim3(kBlock), 0, s, a.table,
-                       a.n_rows, a.dim, a.row_ids, a.n_dev, a.n_max, a.mode, a.n_iter, a.num_bins_f,
-                       a.scale, a.bias, a.row_min, a.row_max, a.codes, a.packed, a.err);
+    if (greedy) {  // other row lengths, greedy: one wave per row
+        const unsigned grid = cnr_grid(ctx, a.n_max, kWavesPerBlock, 8);
+        hipLaunchKernelGGL((quantize_rows_generic_kernel<BITS>), dim3(grid), dim3(kBlock), 0, s, a.table,
+                           a.n_rows, a.dim, a.row_ids, a.n_dev, a.n_max, a.mode, a.n_iter, a.num_bins_f,
+                           a.scale, a.bias, a.row_min, a.row_max, a.codes, a.packed, a.err);
+        return;
+    }
+    const uint32_t n4 = a.dim / 4;
+    if (n4 <= 4) return launch_strided<4, BITS>(ctx, a, s);
+    if (n4 <= 8) return launch_strided<8, BITS>(ctx, a, s);
+    if (n4 <= 16) return launch_strided<16, BITS>(ctx, a, s);
+    if (n4 <= 32) return launch_strided<32, BITS>(ctx, a, s);
+    return launch_strided<64, BITS>(ctx, a, s);
 }
 
 }  // namespace

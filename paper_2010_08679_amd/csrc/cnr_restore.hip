@@ -171,38 +171,53 @@ __global__ void __launch_bounds__(kBlock) restore_rows16_kernel(const RestoreJob
     }
 }
 
-// Any other dim: one wavefront per row, lanes stride over the elements.
-template <int BITS>
-__global__ void __launch_bounds__(kBlock)
-restore_rows_generic_kernel(float *__restrict__ table, uint64_t n_rows, uint32_t dim,
-                            const uint32_t *__restrict__ row_ids, const uint64_t *__restrict__ n_dev,
-                            uint64_t n_max, const uint8_t *__restrict__ packed,
-                            const float *__restrict__ scale, const float *__restrict__ bias,
-                            cnr_dev_errors *err) {
+// Other row lengths: LPR lanes per row (a power of two, at least the row's number of 16-byte units up
+// to 64), 64 / LPR rows per wave and pass; lane j takes the units j, j + LPR, ... of its row: it reads
+// the unit's 4 * BITS code bits (one, two or four bytes; at 3 bits the three bytes that hold the
+// unit and its pair partner) and stores 16 bytes.
+template <int LPR, int BITS>
+__global__ void __launch_bounds__(kBlock) restore_strided_kernel(const RestoreJob a, uint32_t dim, cnr_dev_errors *err) {
+    constexpr int kRowsPerPass = kWave / LPR;
     constexpr uint32_t MASK = (1u << BITS) - 1u;
-    uint64_t n = n_max;
-    if (n_dev) {
-        const uint64_t nd = *n_dev;
-        n = nd < n_max ? nd : n_max;
-    }
-    const int lane = tid_x() & (kWave - 1);
-    const uint64_t n_waves = (uint64_t)grid_x() * kWavesPerBlock;
+    const uint64_t n = live_rows(a.n_dev, a.n_max);
+    const uint32_t n4 = dim / 4;
     const uint64_t P = (uint64_t)dim * BITS / 8;
-    for (uint64_t k = (uint64_t)wg_x() * kWavesPerBlock + tid_x() / kWave; k < n; k += n_waves) {
-        const uint64_t r = row_ids ? (uint64_t)row_ids[k] : k;
-        if (r >= n_rows) {
-            if (lane == 0) raise_flag(err, CNR_FLAG_ROW_ID);
-            continue;
-        }
-        const uint8_t *__restrict__ in = packed + k * P;
-        const float s = scale[k], b = bias[k];
-        float *__restrict__ out = table + r * (uint64_t)dim;
-        for (uint32_t e = lane; e < dim; e += kWave) {
-            const uint64_t bit = (uint64_t)e * BITS;
-            uint32_t two = in[bit >> 3];
-            if (((bit & 7u) + BITS) > 8u) two |= (uint32_t)in[(bit >> 3) + 1] << 8;
-            const uint32_t code = (two >> (bit & 7u)) & MASK;
-            out[e] = s * (float)code + b;
+    const int lane = tid_x() & (kWave - 1);
+    const uint32_t j = lane % LPR;
+    const uint32_t n_waves = a.n_waves;
+    const uint32_t trips = (n4 + LPR - 1) / LPR;
+    for (uint64_t pass = wave_in_grid(); pass * kRowsPerPass < n; pass += n_waves) {
+        const uint64_t k = pass * kRowsPerPass + lane / LPR;
+        const uint64_t kc = k < n ? k : n - 1;  // rows past the end repeat the last one; nothing of theirs is stored
+        const uint64_t r = a.row_ids ? (uint64_t)a.row_ids[kc] : kc;
+        const bool in_table = r < a.n_rows;
+        const bool live = k < n && in_table;
+        if (k < n && !in_table && j == 0) raise_flag(err, CNR_FLAG_ROW_ID);
+        const uint8_t *in = a.packed + kc * P;
+        const float s = a.scale[kc], b = a.bias[kc];
+        f32x4 *out = reinterpret_cast<f32x4 *>(a.table + (in_table ? r : 0) * (uint64_t)dim);
+        for (uint32_t trip = 0; trip < trips; ++trip) {
+            const uint32_t u = j + trip * LPR;
+            const bool mine = u < n4;
+            const uint32_t uc = mine ? u : 0;
+            uint32_t w;  // the unit's four codes, first element lowest
+            if constexpr (BITS == 8) {
+                w = *reinterpret_cast<const uint32_t *>(in + 4 * uc);
+            } else if constexpr (BITS == 4) {
+                w = *reinterpret_cast<const uint16_t *>(in + 2 * uc);
+            } else if constexpr (BITS == 2) {
+                w = in[uc];
+            } else {  // units come in pairs (dim % 8 == 0): three bytes hold the even one's 12 bits, then the odd one's
+                const uint8_t *i3 = in + 3 * (uc >> 1);
+                const uint32_t both = (uint32_t)i3[0] | ((uint32_t)i3[1] << 8) | ((uint32_t)i3[2] << 16);
+                w = (uc & 1) ? both >> 12 : both & 0xFFFu;
+            }
+            f32x4 v;
+            v.x = s * (float)(w & MASK) + b;
+            v.y = s * (float)((w >> BITS) & MASK) + b;
+            v.z = s * (float)((w >> (2 * BITS)) & MASK) + b;
+            v.w = s * (float)((w >> (3 * BITS)) & MASK) + b;
+            if (mine && live) store_stream<f32x4>(out + u, v);
         }
     }
 }
@@ -215,14 +230,25 @@ void launch_restore16(cnr_ctx *ctx, hipStream_t st, RestoreJob &a) {
     hipLaunchKernelGGL((restore_rows16_kernel<M, BITS>), dim3(grid), dim3(kBlock), 0, st, a, ctx->dev_err);
 }
 
+template <int LPR, int BITS>
+void launch_restore_strided(cnr_ctx *ctx, hipStream_t st, uint32_t dim, RestoreJob &a) {
+    const unsigned grid = cnr_grid(ctx, a.n_max, (uint64_t)(kWave / LPR) * kWavesPerBlock,
+                                   cnr_resident_blocks_per_cu<restore_strided_kernel<LPR, BITS>>());
+    a.n_waves = grid * kWavesPerBlock;
+    hipLaunchKernelGGL((restore_strided_kernel<LPR, BITS>), dim3(grid), dim3(kBlock), 0, st, a, dim, ctx->dev_err);
+}
+
 template <int BITS>
 void launch_restore(cnr_ctx *ctx, hipStream_t st, uint32_t dim, RestoreJob &a) {
     if (dim == 64) return launch_restore16<1, BITS>(ctx, st, a);
     if (dim == 128) return launch_restore16<2, BITS>(ctx, st, a);
     if (dim == 256) return launch_restore16<4, BITS>(ctx, st, a);
-    hipLaunchKernelGGL((restore_rows_generic_kernel<BITS>), dim3(cnr_grid(ctx, a.n_max, kWavesPerBlock, 8)),
-                       dim3(kBlock), 0, st, a.table, a.n_rows, dim, a.row_ids, a.n_dev, a.n_max, a.packed,
-                       a.scale, a.bias, ctx->dev_err);
+    const uint32_t n4 = dim / 4;
+    if (n4 <= 4) return launch_restore_strided<4, BITS>(ctx, st, dim, a);
+    if (n4 <= 8) return launch_restore_strided<8, BITS>(ctx, st, dim, a);
+    if (n4 <= 16) return launch_restore_strided<16, BITS>(ctx, st, dim, a);
+    if (n4 <= 32) return launch_restore_strided<32, BITS>(ctx, st, dim, a);
+    return launch_restore_strided<64, BITS>(ctx, st, dim, a);
 }
 
 // ---------------------------------------------------------------------------------------------

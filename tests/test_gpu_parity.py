@@ -516,12 +516,12 @@ def test_largest_supported_row_dimension(ctx, bits):
     ora = O.quantize_rows(gt.host, None, bits, n_threads=8)
     for k in ("scale", "bias", "row_min", "row_max"):
         assert np.array_equal(got[k], ora[k])
-    assert np.array_equal(got["codes"], ora["codes"])          # the generic kernel divides like F_Q
-    assert np.array_equal(got["packed"], O.pack(ora["codes"], bits))
+    compare_quantized(gt.host, got, ora, bits, what="dim %d b%d" % (dim, bits))
+    assert np.array_equal(got["packed"], O.pack(got["codes"], bits))
     d = got["dev"]
     stale = torch.zeros_like(gt.table)
     P.cnr_restore_rows(ctx, stale, n_rows, dim, None, None, n_rows, bits, d["packed"], d["scale"], d["bias"])
-    assert np.array_equal(stale.cpu().numpy(), O.dequantize(ora["codes"], ora["scale"], ora["bias"]))
+    assert np.array_equal(stale.cpu().numpy(), O.dequantize(got["codes"], got["scale"], got["bias"]))
     t = torch.zeros((4, dim + 4), device=DEV)
     s = torch.zeros(4, device=DEV)
     with pytest.raises(P.CnrError) as e:
@@ -596,4 +596,29 @@ def test_ragged_passes_with_ids_at_every_width(ctx, bits, dim, n):
                    codes=codes.cpu().numpy().reshape(n + pad, dim)[good])
         compare_quantized(gt.host[ids_np[good]], got, ora, bits, what="ragged n=%d d%d b%d" % (n, dim, bits))
         assert np.array_equal(packed.cpu().numpy().reshape(n + pad, prb)[good], O.pack(got["codes"], bits))
+    _poll_clean(ctx)
+
+
+@pytest.mark.parametrize("bits", BITS)
+@pytest.mark.parametrize("dim", [4, 16, 32, 48, 72, 192, 320, 512, 1000, 2048])
+def test_other_row_lengths(ctx, bits, dim):
+    # row lengths beside 64 / 128 / 256: every lanes-per-row variant, full and partly used, rows past the end
+    if (dim * bits) % 8:
+        pytest.skip("dim * bits is not a whole number of bytes")
+    n_rows, n = 700, 333
+    gt = GpuTable(ctx, _table(n_rows, dim, 200 + dim + bits))
+    rng = np.random.default_rng(dim * 10 + bits)
+    ids_np = np.sort(rng.choice(n_rows, size=n, replace=False)).astype(np.uint32)
+    ids = torch.from_numpy(ids_np.view(np.int32)).to(DEV)
+    for mode, omode in ((P.CNR_RANGE_MINMAX, O.RANGE_MINMAX), (P.CNR_RANGE_SYMMETRIC, O.RANGE_SYMMETRIC)):
+        got = gpu_encode_all_outputs(gt, bits, mode=mode, row_ids=ids, n=n)
+        ora = O.quantize_rows(gt.host, ids_np, bits, mode=omode, n_threads=8)
+        compare_quantized(gt.host[ids_np], got, ora, bits, what="dim %d b%d mode %d" % (dim, bits, mode))
+        assert np.array_equal(got["packed"], O.pack(got["codes"], bits))
+    d = got["dev"]
+    stale = torch.zeros_like(gt.table)
+    P.cnr_restore_rows(ctx, stale, n_rows, dim, ids, None, n, bits, d["packed"], d["scale"], d["bias"])
+    want = np.zeros_like(gt.host)
+    O.restore_rows(want, ids_np, bits, got["packed"], got["scale"], got["bias"])
+    assert np.array_equal(stale.cpu().numpy(), want)
     _poll_clean(ctx)
