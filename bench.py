@@ -40,16 +40,19 @@ ISSUE_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # one vector instruction per lane
 # HBM traffic of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), in bytes
 # per dirty row, valid only for the kernel source whose hash is recorded with it.
 TRAFFIC_PER_ROW = {
-    # sha256 of csrc/cnr_quantize.hip without comments and white space : (workload, bytes per dirty row)
+    # _kernel_hash() : (workload, bytes per dirty row)
     # (2.000 * 190490.1 KiB FETCH_SIZE + 1.000 * 60149.6 KiB WRITE_SIZE) / 1,500,122 rows per launch
-    "87aacee2652dfb565644a9044f8faacef001f1b7f29951a3cf94da7def773f33": ("cfg4/b4", 301.12),
+    "323eb128a062ee92f5c433825fe8a469888cad6db0f30a744e438e1408aa6f4c": ("cfg4/b4", 301.12),
 }
 
 
 def _kernel_hash() -> str:
-    """Hash of the encode kernels' source without comments and white space."""
+    """Hash of the tile kernel's source (everything in its file above the greedy kernel's section),
+    without comments and white space."""
     with open(os.path.join(ROOT, "paper_2010_08679_amd", "csrc", "cnr_quantize.hip"), "r") as f:
-        code = "".join(line.split("//")[0] for line in f)
+        text = f.read()
+    text = text[:text.index("// Greedy range search")]
+    code = "".join(line.split("//")[0] for line in text.splitlines(True))
     return hashlib.sha256("".join(code.split()).encode()).hexdigest()
 
 
