@@ -311,7 +311,7 @@ def main() -> int:
 
     # ---- chunked encode with the device-to-host copy overlapped (what follows the path) -----------
     if not args.no_host_copy:
-        writer = P.HostCheckpointWriter(ctx, w.dim, bits, capacity=w.n_rows, chunk_rows=1 << 18, device=dev)
+        writer = P.HostCheckpointWriter(ctx, w.dim, bits, capacity=w.n_rows, chunk_rows=1 << 20, device=dev)
         cks[0].clear(); cks[0].mark(streams[0]); cks[0].compact()
         res = {}
         for label, overlap in (("overlapped", True), ("serialized", False)):

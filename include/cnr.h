@@ -244,6 +244,39 @@ cnr_status cnr_quantize_rows_batch(cnr_ctx *ctx, const cnr_table_job *jobs /* ho
 cnr_status cnr_restore_rows_batch(cnr_ctx *ctx, const cnr_table_job *jobs /* host */, uint32_t n_jobs,
                                   uint32_t dim, int bits, void *stream);
 
+/* ---- chunked encode into host memory (Sections 4.4 and 5.2: the optimized checkpoint is built chunk
+ *      by chunk, and a finished chunk is handed on while the next one is quantized) ----------------
+ *
+ * A writer owns two device staging sets of chunk_rows rows (scale, bias, packed codes), a copy
+ * stream of default priority and the events that order it against the caller's stream.
+ * cnr_host_writer_create allocates them (cnr_host_writer_device_bytes tells how much device memory),
+ * cnr_host_writer_destroy waits for the copy stream and frees them; nothing is allocated in between.
+ *
+ * cnr_encode_to_host quantizes rows row_ids[0 .. n) of `table` (min/max, symmetric or greedy range, as
+ * cnr_quantize_rows does) chunk by chunk on `stream` and copies every finished chunk, and the matching
+ * slice of row_ids, into the host buffers; with `overlap` != 0 the copies run on the writer's stream
+ * while the next chunk is encoded, else on `stream` itself.  It only enqueues work; the host buffers
+ * are complete after cnr_host_writer_wait (which synchronizes both streams).  One call at a time per
+ * writer.
+ *   n               host value: the number of rows (read it back from cnr_compact_dirty's count first)
+ *   row_ids         device, uint32 [n], 16-byte aligned; NULL means rows 0 .. n-1 and then n must not
+ *                   exceed chunk_rows
+ *   host_row_ids    host uint32 [n] (ignored when row_ids is NULL)
+ *   host_scale, host_bias   host float [n]
+ *   host_packed     host uint8 [n][cnr_packed_row_bytes(dim, bits)]
+ *                   Pinned host memory lets the copies overlap; pageable memory works but serializes.
+ *   chunk_rows      a multiple of 16 */
+typedef struct cnr_host_writer cnr_host_writer; /* opaque */
+
+size_t cnr_host_writer_device_bytes(uint32_t dim, int bits, uint64_t chunk_rows);
+cnr_status cnr_host_writer_create(cnr_ctx *ctx, uint32_t dim, int bits, uint64_t chunk_rows, cnr_host_writer **out);
+cnr_status cnr_host_writer_destroy(cnr_host_writer *w);
+cnr_status cnr_encode_to_host(cnr_host_writer *w, const float *table, uint64_t n_rows, const uint32_t *row_ids,
+                              uint64_t n, cnr_range_mode mode, const cnr_greedy_params *greedy /* host */,
+                              uint32_t *host_row_ids, float *host_scale, float *host_bias, uint8_t *host_packed,
+                              int overlap, void *stream);
+cnr_status cnr_host_writer_wait(cnr_host_writer *w, void *stream);
+
 /* ---- device-side conditions ---------------------------------------------------------------- */
 
 /* Waits for `stream`, then reports and resets what the kernels recorded since the last poll.

@@ -35,6 +35,8 @@ EXPORTS = (
     "cnr_last_hip_error", "cnr_full_checkpoint_due", "cnr_policy_init", "cnr_policy_next",
     "cnr_clear_bitmap_batch", "cnr_mark_touched_batch", "cnr_compact_dirty_batch", "cnr_quantize_rows_batch",
     "cnr_restore_rows_batch",
+    "cnr_host_writer_device_bytes", "cnr_host_writer_create", "cnr_host_writer_destroy", "cnr_encode_to_host",
+    "cnr_host_writer_wait",
 )
 
 
@@ -115,6 +117,12 @@ def load() -> ctypes.CDLL:
             "cnr_quantize_rows_batch": (i32, [vp, ctypes.POINTER(cnr_table_job), u32, u32, i32, i32,
                                               ctypes.POINTER(cnr_greedy_params), vp]),
             "cnr_restore_rows_batch": (i32, [vp, ctypes.POINTER(cnr_table_job), u32, u32, i32, vp]),
+            "cnr_host_writer_device_bytes": (sz, [u32, i32, u64]),
+            "cnr_host_writer_create": (i32, [vp, u32, i32, u64, ctypes.POINTER(vp)]),
+            "cnr_host_writer_destroy": (i32, [vp]),
+            "cnr_encode_to_host": (i32, [vp, vp, u64, vp, u64, i32, ctypes.POINTER(cnr_greedy_params),
+                                         vp, vp, vp, vp, i32, vp]),
+            "cnr_host_writer_wait": (i32, [vp, vp]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(lib, name)
@@ -340,6 +348,54 @@ def cnr_quantize_rows_batch(ctx, jobs, dim: int, bits: int, mode: int, greedy=No
 def cnr_restore_rows_batch(ctx, jobs, dim: int, bits: int, stream=None) -> None:
     arr, n = _jobs_arg(jobs)
     _check(load().cnr_restore_rows_batch(ctx, arr, n, dim, bits, _stream(stream)), "cnr_restore_rows_batch")
+
+
+# ---- chunked encode into host memory --------------------------------------------------------------
+
+def cnr_host_writer_device_bytes(dim: int, bits: int, chunk_rows: int) -> int:
+    return int(load().cnr_host_writer_device_bytes(dim, bits, chunk_rows))
+
+
+def cnr_host_writer_create(ctx, dim: int, bits: int, chunk_rows: int) -> ctypes.c_void_p:
+    w = ctypes.c_void_p()
+    _check(load().cnr_host_writer_create(ctx, dim, bits, chunk_rows, ctypes.byref(w)), "cnr_host_writer_create")
+    return w
+
+
+def cnr_host_writer_destroy(writer) -> None:
+    _check(load().cnr_host_writer_destroy(writer), "cnr_host_writer_destroy")
+
+
+def _host(t, dtype, name: str, n_items: int):
+    """Pointer of a contiguous CPU tensor with room for n_items elements."""
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError("%s must be a contiguous CPU tensor of %s" % (name, dtype))
+    if t.numel() < n_items:
+        raise ValueError("%s too small" % name)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def cnr_encode_to_host(writer, table, n_rows: int, dim: int, bits: int, row_ids, n: int, mode: int, greedy,
+                       host_row_ids, host_scale, host_bias, host_packed, overlap: bool = True, stream=None) -> None:
+    """``dim`` and ``bits`` are the writer's (used here to check the host buffers' sizes)."""
+    gp = None
+    if greedy is not None:
+        gp = ctypes.pointer(cnr_greedy_params(int(greedy[0]), float(greedy[1])))
+    if table.numel() < n_rows * dim:
+        raise ValueError("table smaller than n_rows * dim")
+    if row_ids is not None and row_ids.numel() < n:
+        raise ValueError("row_ids shorter than n")
+    _check(load().cnr_encode_to_host(writer, _dev(table, F32, "table"), n_rows, _dev(row_ids, U32, "row_ids"), n, mode,
+                                     gp, _host(host_row_ids, U32, "host_row_ids", n),
+                                     _host(host_scale, F32, "host_scale", n), _host(host_bias, F32, "host_bias", n),
+                                     _host(host_packed, U8, "host_packed", n * cnr_packed_row_bytes(dim, bits)),
+                                     1 if overlap else 0, _stream(stream)), "cnr_encode_to_host")
+
+
+def cnr_host_writer_wait(writer, stream=None) -> None:
+    _check(load().cnr_host_writer_wait(writer, _stream(stream)), "cnr_host_writer_wait")
 
 
 def cnr_poll_errors(ctx, stream=None):

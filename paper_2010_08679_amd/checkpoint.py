@@ -216,28 +216,34 @@ class HostCheckpointWriter:
     (Section 4.4 and 5.2: the optimized checkpoint is built chunk by chunk and every finished chunk
     is handed on while the next one is being quantized).
 
-    Two device staging buffers of ``chunk_rows`` rows take the encoder's output in turn; a copy
-    stream moves each finished chunk into pinned host memory (where a storage writer would pick it
-    up).  Streams have the default priority.  Plumbing only: the encode itself is
-    ``cnr_quantize_rows`` on a slice of the dirty-row list."""
+    Plumbing only: the library's writer (``cnr_host_writer_*``, ``cnr_encode_to_host``) owns the two
+    device staging sets and the copy stream and orders the chunks; this class owns the pinned host
+    buffers the chunks land in (where a storage writer would pick them up)."""
 
-    def __init__(self, ctx, dim: int, bits: int, capacity: int, chunk_rows: int = 1 << 18, device="cuda:0"):
+    def __init__(self, ctx, dim: int, bits: int, capacity: int, chunk_rows: int = 1 << 20, device="cuda:0"):
         if chunk_rows % 16:
             raise ValueError("chunk_rows must be a multiple of 16 (keeps every slice 16-byte aligned)")
         self.ctx, self.dim, self.bits, self.capacity, self.chunk = ctx, dim, bits, int(capacity), int(chunk_rows)
         self.prb = B.cnr_packed_row_bytes(dim, bits)
-        dev = torch.device(device)
-        self.stage = [dict(scale=torch.empty(self.chunk, dtype=torch.float32, device=dev),
-                           bias=torch.empty(self.chunk, dtype=torch.float32, device=dev),
-                           packed=torch.empty(self.chunk * self.prb, dtype=torch.uint8, device=dev))
-                      for _ in range(2)]
+        with torch.cuda.device(torch.device(device)):
+            self.writer = B.cnr_host_writer_create(ctx, dim, bits, self.chunk)
         cap = max(1, self.capacity)
         self.host = dict(row_ids=torch.empty(cap, dtype=torch.int32, pin_memory=True),
                          scale=torch.empty(cap, dtype=torch.float32, pin_memory=True),
                          bias=torch.empty(cap, dtype=torch.float32, pin_memory=True),
                          packed=torch.empty(cap * self.prb, dtype=torch.uint8, pin_memory=True))
-        self.copy_stream = torch.cuda.Stream(device=dev)
         self.n_host = torch.zeros(1, dtype=torch.int64, pin_memory=True)
+
+    def close(self) -> None:
+        if self.writer is not None:
+            B.cnr_host_writer_destroy(self.writer)
+            self.writer = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
     def encode_to_host(self, ck: TableCheckpointer, table: torch.Tensor, mode: int = B.CNR_RANGE_MINMAX,
                        greedy=None, overlap: bool = True) -> int:
@@ -248,27 +254,8 @@ class HostCheckpointWriter:
         self.n_host.copy_(ck.n_dirty, non_blocking=True)
         main.synchronize()
         n = min(int(self.n_host.item()), ck.capacity, self.capacity)
-        copied = [None, None]                                    # event: staging buffer free again
-        copier = self.copy_stream if overlap else main
-        for c, k0 in enumerate(range(0, n, self.chunk)):
-            m = min(self.chunk, n - k0)
-            st = self.stage[c & 1]
-            if copied[c & 1] is not None:
-                main.wait_event(copied[c & 1])
-            B.cnr_quantize_rows(self.ctx, table, ck.n_rows, self.dim, ck.row_ids[k0:k0 + m], None, m, self.bits,
-                                mode, greedy, st["scale"], st["bias"], packed=st["packed"], stream=main)
-            ready = torch.cuda.Event()
-            ready.record(main)
-            copier.wait_event(ready)
-            with torch.cuda.stream(copier):
-                self.host["row_ids"][k0:k0 + m].copy_(ck.row_ids[k0:k0 + m], non_blocking=True)
-                self.host["scale"][k0:k0 + m].copy_(st["scale"][:m], non_blocking=True)
-                self.host["bias"][k0:k0 + m].copy_(st["bias"][:m], non_blocking=True)
-                self.host["packed"][k0 * self.prb:(k0 + m) * self.prb].copy_(st["packed"][:m * self.prb],
-                                                                            non_blocking=True)
-                done = torch.cuda.Event()
-                done.record(copier)
-            copied[c & 1] = done
-        copier.synchronize()
-        main.synchronize()
+        B.cnr_encode_to_host(self.writer, table, ck.n_rows, self.dim, self.bits, ck.row_ids, n, mode, greedy,
+                             self.host["row_ids"], self.host["scale"], self.host["bias"], self.host["packed"],
+                             overlap, main)
+        B.cnr_host_writer_wait(self.writer, main)
         return n

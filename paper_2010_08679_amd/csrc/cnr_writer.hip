@@ -1,0 +1,144 @@
+// Chunked encode with the device-to-host copy of one chunk overlapping the encode of the next
+// (Sections 4.4 and 5.2: the optimized checkpoint is built chunk by chunk and every finished chunk
+// is handed on while the next one is being quantized).
+//
+// Two device staging sets of chunk_rows rows take the encoder's output in turn; a copy stream of
+// the writer's own (default priority) moves each finished chunk into the caller's host buffers.
+// Events order the two streams: a chunk is copied after it is encoded, and a staging set is encoded
+// into again only after its previous content has been copied out.
+#include <new>
+
+#include "cnr_common.h"
+
+struct cnr_host_writer {
+    cnr_ctx *ctx;
+    uint32_t dim;
+    int bits;
+    uint64_t chunk_rows;
+    size_t row_bytes;  // packed bytes per row
+    float *scale[2], *bias[2];
+    uint8_t *packed[2];
+    hipStream_t copy;
+    hipEvent_t encoded[2], drained[2];
+    bool in_use[2];  // drained[b] has been recorded and not yet waited for
+};
+
+namespace {
+
+void release(cnr_host_writer *w) {
+    for (int b = 0; b < 2; ++b) {
+        if (w->scale[b]) (void)hipFree(w->scale[b]);
+        if (w->bias[b]) (void)hipFree(w->bias[b]);
+        if (w->packed[b]) (void)hipFree(w->packed[b]);
+        if (w->encoded[b]) (void)hipEventDestroy(w->encoded[b]);
+        if (w->drained[b]) (void)hipEventDestroy(w->drained[b]);
+    }
+    if (w->copy) (void)hipStreamDestroy(w->copy);
+    delete w;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t cnr_host_writer_device_bytes(uint32_t dim, int bits, uint64_t chunk_rows) {
+    const size_t row_bytes = cnr_packed_row_bytes(dim, bits);
+    if (row_bytes == 0) return 0;
+    return (size_t)(2u * chunk_rows * (row_bytes + 8u));
+}
+
+cnr_status cnr_host_writer_create(cnr_ctx *ctx, uint32_t dim, int bits, uint64_t chunk_rows, cnr_host_writer **out) {
+    if (!out) return CNR_E_INVALID;
+    *out = nullptr;
+    cnr_status st = cnr_enter(ctx);
+    if (st != CNR_OK) return st;
+    if (!cnr_valid_bits(bits)) return CNR_E_BITS;
+    if (dim == 0 || dim % 4 || dim > CNR_MAX_DIM || ((uint64_t)dim * (uint64_t)bits) % 8) return CNR_E_DIM;
+    if (chunk_rows == 0 || chunk_rows % 16) return CNR_E_INVALID;  // keeps every row-id slice 16-byte aligned
+    cnr_host_writer *w = new (std::nothrow) cnr_host_writer();
+    if (!w) return CNR_E_INVALID;
+    *w = cnr_host_writer{};
+    w->ctx = ctx;
+    w->dim = dim;
+    w->bits = bits;
+    w->chunk_rows = chunk_rows;
+    w->row_bytes = cnr_packed_row_bytes(dim, bits);
+    hipError_t e = hipStreamCreateWithFlags(&w->copy, hipStreamNonBlocking);
+    for (int b = 0; b < 2 && e == hipSuccess; ++b) {
+        e = hipMalloc((void **)&w->scale[b], chunk_rows * sizeof(float));
+        if (e == hipSuccess) e = hipMalloc((void **)&w->bias[b], chunk_rows * sizeof(float));
+        if (e == hipSuccess) e = hipMalloc((void **)&w->packed[b], chunk_rows * w->row_bytes);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&w->encoded[b], hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&w->drained[b], hipEventDisableTiming);
+    }
+    if (e != hipSuccess) {
+        release(w);
+        return cnr_hip_status(ctx, e);
+    }
+    *out = w;
+    return CNR_OK;
+}
+
+cnr_status cnr_host_writer_destroy(cnr_host_writer *w) {
+    if (!w) return CNR_E_INVALID;
+    cnr_status st = cnr_enter(w->ctx);
+    if (st == CNR_OK) st = cnr_hip_status(w->ctx, hipStreamSynchronize(w->copy));
+    release(w);
+    return st;
+}
+
+cnr_status cnr_encode_to_host(cnr_host_writer *w, const float *table, uint64_t n_rows, const uint32_t *row_ids,
+                              uint64_t n, cnr_range_mode mode, const cnr_greedy_params *greedy,
+                              uint32_t *host_row_ids, float *host_scale, float *host_bias, uint8_t *host_packed,
+                              int overlap, void *stream) {
+    if (!w) return CNR_E_INVALID;
+    cnr_ctx *ctx = w->ctx;
+    cnr_status st = cnr_enter(ctx);
+    if (st != CNR_OK) return st;
+    if (n == 0) return CNR_OK;
+    if (!host_scale || !host_bias || !host_packed || (row_ids && !host_row_ids)) return CNR_E_INVALID;
+    if (!row_ids && n > w->chunk_rows) return CNR_E_INVALID;  // without a row list there is only one chunk
+    hipStream_t main = as_stream(stream);
+    hipStream_t copier = overlap ? w->copy : main;
+    hipError_t e = hipSuccess;
+    uint64_t c = 0;
+    for (uint64_t k0 = 0; k0 < n && e == hipSuccess; k0 += w->chunk_rows, ++c) {
+        const uint64_t m = n - k0 < w->chunk_rows ? n - k0 : w->chunk_rows;
+        const int b = (int)(c & 1);
+        if (w->in_use[b]) {  // the staging set still holds a chunk that is being copied out
+            e = hipStreamWaitEvent(main, w->drained[b], 0);
+            if (e != hipSuccess) break;
+            w->in_use[b] = false;
+        }
+        st = cnr_quantize_rows(ctx, table, n_rows, w->dim, row_ids ? row_ids + k0 : nullptr, nullptr, m, w->bits, mode,
+                               greedy, w->scale[b], w->bias[b], nullptr, nullptr, nullptr, w->packed[b], stream);
+        if (st != CNR_OK) return st;
+        if (copier != main) {
+            e = hipEventRecord(w->encoded[b], main);
+            if (e == hipSuccess) e = hipStreamWaitEvent(copier, w->encoded[b], 0);
+            if (e != hipSuccess) break;
+        }
+        if (row_ids) e = hipMemcpyAsync(host_row_ids + k0, row_ids + k0, m * sizeof(uint32_t), hipMemcpyDeviceToHost, copier);
+        if (e == hipSuccess) e = hipMemcpyAsync(host_scale + k0, w->scale[b], m * sizeof(float), hipMemcpyDeviceToHost, copier);
+        if (e == hipSuccess) e = hipMemcpyAsync(host_bias + k0, w->bias[b], m * sizeof(float), hipMemcpyDeviceToHost, copier);
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(host_packed + k0 * w->row_bytes, w->packed[b], m * w->row_bytes, hipMemcpyDeviceToHost, copier);
+        if (e == hipSuccess && copier != main) {
+            e = hipEventRecord(w->drained[b], copier);
+            w->in_use[b] = e == hipSuccess;
+        }
+    }
+    return cnr_hip_status(ctx, e);
+}
+
+cnr_status cnr_host_writer_wait(cnr_host_writer *w, void *stream) {
+    if (!w) return CNR_E_INVALID;
+    cnr_status st = cnr_enter(w->ctx);
+    if (st != CNR_OK) return st;
+    hipError_t e = hipStreamSynchronize(as_stream(stream));
+    if (e == hipSuccess) e = hipStreamSynchronize(w->copy);
+    w->in_use[0] = w->in_use[1] = false;
+    return cnr_hip_status(w->ctx, e);
+}
+
+}  // extern "C"
