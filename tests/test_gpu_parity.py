@@ -622,3 +622,56 @@ def test_other_row_lengths(ctx, bits, dim):
     O.restore_rows(want, ids_np, bits, got["packed"], got["scale"], got["bias"])
     assert np.array_equal(stale.cpu().numpy(), want)
     _poll_clean(ctx)
+
+
+def test_host_writer_back_to_back_tables_and_argument_errors(ctx):
+    # two tables through one writer without waiting in between: the second call's first chunks go into
+    # staging sets the first call's copies may still be reading, which the writer's events must order
+    dim, bits, chunk = 64, 4, 16 * 500
+    prb = P.cnr_packed_row_bytes(dim, bits)
+    writer = P.cnr_host_writer_create(ctx, dim, bits, chunk)
+    assert P.cnr_host_writer_device_bytes(dim, bits, chunk) == 2 * chunk * (prb + 8)
+    jobs = []
+    for seed, n_rows in ((1, 50_000), (2, 33_000)):
+        gt = GpuTable(ctx, _table(n_rows, dim, 300 + seed))
+        _dirty(gt, 0.5, seed)
+        n = int(gt.ck.n_dirty.item())
+        host = dict(ids=torch.empty(n, dtype=torch.int32, pin_memory=(seed == 1)),      # pinned and pageable
+                    scale=torch.empty(n, dtype=torch.float32, pin_memory=(seed == 1)),
+                    bias=torch.empty(n, dtype=torch.float32, pin_memory=(seed == 1)),
+                    packed=torch.empty(n * prb, dtype=torch.uint8, pin_memory=(seed == 1)))
+        jobs.append((gt, n, host))
+    for gt, n, host in jobs:
+        assert n > 2 * chunk
+        P.cnr_encode_to_host(writer, gt.table, gt.n_rows, dim, bits, gt.ck.row_ids, n, P.CNR_RANGE_MINMAX, None,
+                             host["ids"], host["scale"], host["bias"], host["packed"], overlap=True)
+    P.cnr_host_writer_wait(writer)
+    for gt, n, host in jobs:
+        ids = u32(gt.ck.row_ids)[:n]
+        ora = O.quantize_rows(gt.host, ids, bits, n_threads=8)
+        assert np.array_equal(host["ids"].numpy().view(np.uint32), ids)
+        got = dict(scale=host["scale"].numpy(), bias=host["bias"].numpy(),
+                   codes=O.unpack(host["packed"].numpy().reshape(n, prb), dim, bits))
+        compare_quantized(gt.host[ids], got, ora, bits, what="host writer, %d rows" % n)
+    # rows 0 .. n-1 without a list: one chunk at most
+    gt = jobs[0][0]
+    hs, hb = torch.empty(chunk), torch.empty(chunk)
+    hp = torch.empty(chunk * prb, dtype=torch.uint8)
+    P.cnr_encode_to_host(writer, gt.table, gt.n_rows, dim, bits, None, chunk, P.CNR_RANGE_MINMAX, None, None, hs, hb, hp)
+    P.cnr_host_writer_wait(writer)
+    ora = O.quantize_rows(gt.host[:chunk].copy(), None, bits, n_threads=8)
+    assert np.array_equal(hs.numpy(), ora["scale"])
+    with pytest.raises(P.CnrError) as e:
+        P.cnr_encode_to_host(writer, gt.table, gt.n_rows, dim, bits, None, chunk + 16, P.CNR_RANGE_MINMAX, None, None,
+                             torch.empty(chunk + 16), torch.empty(chunk + 16),
+                             torch.empty((chunk + 16) * prb, dtype=torch.uint8))
+    assert e.value.status == P.CNR_E_INVALID
+    P.cnr_host_writer_destroy(writer)
+    for bad_chunk, status in ((100, P.CNR_E_INVALID), (0, P.CNR_E_INVALID)):
+        with pytest.raises(P.CnrError) as e:
+            P.cnr_host_writer_create(ctx, dim, bits, bad_chunk)
+        assert e.value.status == status
+    with pytest.raises(P.CnrError) as e:
+        P.cnr_host_writer_create(ctx, 12, 3, 1024)
+    assert e.value.status == P.CNR_E_DIM
+    _poll_clean(ctx)
