@@ -194,6 +194,30 @@ cnr_status cnr_quant_error(cnr_ctx *ctx, const float *table, uint64_t n_rows, ui
                            const uint8_t *packed, const float *scale, const float *bias, double *err,
                            double *mean_out, void *stream);
 
+/* ---- greedy parameters by profiling (Section 5.2, "Parameter selection") ------------------------
+ *
+ * Quantizes the rows `sample_ids` of `table` (a uniform sample of the checkpoint drawn by the caller;
+ * the paper samples 0.001 % of it) with min/max quantization and with the greedy search at every
+ * num_bins of `bins_grid` (ratio 1), keeps the num_bins at which the improvement of the mean l2
+ * error tapers off, then does the same over `ratio_grid` at that num_bins.  "Tapers off" is read as:
+ * with I(p) = 1 - E(p) / E_minmax, the first p of the grid with I(p) >= (1 - taper) * max I (the
+ * first grid value when nothing improves on min/max).  Grids are taken in the order given.
+ * Synchronizes `stream` once per grid point (each mean is read back).
+ *   sample_ids  device uint32 [n_sample], 16-byte aligned
+ *   bins_grid   host uint32 [n_bins], ratio_grid host float [n_ratios]; at most CNR_SELECT_MAX_GRID each
+ *   taper       in [0, 1), e.g. 0.05
+ *   scratch     device, cnr_select_scratch_bytes(n_sample, dim, bits) bytes, 16-byte aligned
+ *   chosen      host out
+ *   report      host out or NULL: double [1 + n_bins + n_ratios]: the mean l2 error of min/max, of
+ *               each num_bins, of each ratio */
+#define CNR_SELECT_MAX_GRID 64u
+size_t cnr_select_scratch_bytes(uint64_t n_sample, uint32_t dim, int bits);
+cnr_status cnr_select_greedy_params(cnr_ctx *ctx, const float *table, uint64_t n_rows, uint32_t dim,
+                                    const uint32_t *sample_ids, uint64_t n_sample, int bits,
+                                    const uint32_t *bins_grid, uint32_t n_bins, const float *ratio_grid,
+                                    uint32_t n_ratios, double taper, void *scratch, cnr_greedy_params *chosen,
+                                    double *report, void *stream);
+
 /* ---- several tables per launch (Section 2.1: a GPU holds many embedding tables; Section 4.1: a
  *      checkpoint covers every table of the GPU's shard) ------------------------------------------
  *

@@ -36,7 +36,7 @@ EXPORTS = (
     "cnr_clear_bitmap_batch", "cnr_mark_touched_batch", "cnr_compact_dirty_batch", "cnr_quantize_rows_batch",
     "cnr_restore_rows_batch",
     "cnr_host_writer_device_bytes", "cnr_host_writer_create", "cnr_host_writer_destroy", "cnr_encode_to_host",
-    "cnr_host_writer_wait",
+    "cnr_host_writer_wait", "cnr_select_scratch_bytes", "cnr_select_greedy_params",
 )
 
 
@@ -123,6 +123,10 @@ def load() -> ctypes.CDLL:
             "cnr_encode_to_host": (i32, [vp, vp, u64, vp, u64, i32, ctypes.POINTER(cnr_greedy_params),
                                          vp, vp, vp, vp, i32, vp]),
             "cnr_host_writer_wait": (i32, [vp, vp]),
+            "cnr_select_scratch_bytes": (sz, [u64, u32, i32]),
+            "cnr_select_greedy_params": (i32, [vp, vp, u64, u32, vp, u64, i32, ctypes.POINTER(u32), u32,
+                                               ctypes.POINTER(f32), u32, ctypes.c_double, vp,
+                                               ctypes.POINTER(cnr_greedy_params), ctypes.POINTER(ctypes.c_double), vp]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(lib, name)
@@ -348,6 +352,29 @@ def cnr_quantize_rows_batch(ctx, jobs, dim: int, bits: int, mode: int, greedy=No
 def cnr_restore_rows_batch(ctx, jobs, dim: int, bits: int, stream=None) -> None:
     arr, n = _jobs_arg(jobs)
     _check(load().cnr_restore_rows_batch(ctx, arr, n, dim, bits, _stream(stream)), "cnr_restore_rows_batch")
+
+
+# ---- greedy parameters by profiling ----------------------------------------------------------------
+
+def cnr_select_scratch_bytes(n_sample: int, dim: int, bits: int) -> int:
+    return int(load().cnr_select_scratch_bytes(n_sample, dim, bits))
+
+
+def cnr_select_greedy_params(ctx, table, n_rows: int, dim: int, sample_ids, bits: int, bins_grid, ratio_grid,
+                             taper: float, scratch, stream=None):
+    """Returns ((num_bins, ratio), report) with report = [E_minmax, E(bins...)..., E(ratios...)...]."""
+    n = sample_ids.numel()
+    if scratch.numel() * scratch.element_size() < cnr_select_scratch_bytes(n, dim, bits):
+        raise ValueError("scratch smaller than cnr_select_scratch_bytes")
+    bins = (ctypes.c_uint32 * len(bins_grid))(*[int(b) for b in bins_grid])
+    ratios = (ctypes.c_float * len(ratio_grid))(*[float(r) for r in ratio_grid])
+    report = (ctypes.c_double * (1 + len(bins_grid) + len(ratio_grid)))()
+    chosen = cnr_greedy_params()
+    _check(load().cnr_select_greedy_params(ctx, _dev(table, F32, "table"), n_rows, dim, _dev(sample_ids, U32, "sample_ids"),
+                                           n, bits, bins, len(bins_grid), ratios, len(ratio_grid), float(taper),
+                                           _dev(scratch, scratch.dtype, "scratch"), ctypes.byref(chosen), report,
+                                           _stream(stream)), "cnr_select_greedy_params")
+    return (int(chosen.num_bins), float(chosen.ratio)), list(report)
 
 
 # ---- chunked encode into host memory --------------------------------------------------------------

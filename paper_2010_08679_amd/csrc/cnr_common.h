@@ -18,6 +18,7 @@ struct cnr_ctx {
     int n_cu;                  // compute units of the device
     cnr_dev_errors *dev_err;   // device
     cnr_dev_errors *host_err;  // pinned host mirror used by cnr_poll_errors
+    double *host_scalar;       // pinned host double (behind host_err) for results read back one at a time
     int last_hip_error;
 };
 

@@ -38,6 +38,7 @@ cnr_status cnr_create(cnr_ctx **out, int device) {
     ctx->last_hip_error = 0;
     ctx->dev_err = nullptr;
     ctx->host_err = nullptr;
+    ctx->host_scalar = nullptr;
     hipError_t e = hipSetDevice(device);
     hipDeviceProp_t prop;
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, device);
@@ -45,7 +46,10 @@ cnr_status cnr_create(cnr_ctx **out, int device) {
         ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
         e = hipMalloc((void **)&ctx->dev_err, sizeof(cnr_dev_errors));
     }
-    if (e == hipSuccess) e = hipHostMalloc((void **)&ctx->host_err, sizeof(cnr_dev_errors), hipHostMallocDefault);
+    if (e == hipSuccess) {
+        e = hipHostMalloc((void **)&ctx->host_err, sizeof(cnr_dev_errors) + sizeof(double), hipHostMallocDefault);
+        if (e == hipSuccess) ctx->host_scalar = reinterpret_cast<double *>(ctx->host_err + 1);
+    }
     if (e == hipSuccess) e = hipMemset(ctx->dev_err, 0, sizeof(cnr_dev_errors));
     if (e != hipSuccess) {
         if (ctx->dev_err) (void)hipFree(ctx->dev_err);
