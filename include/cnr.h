@@ -16,6 +16,13 @@
  *   cnr_pack           dense packing alone, for codes produced one per byte
  *   cnr_restore_rows   resume: de-quantize (x = scale * x_q + zero_point) and write the rows
  *                      back over a stale baseline table (Sections 5.1 and 6.2)
+ * Around the path:
+ *   cnr_*_batch        every stage for several tables per call (Sections 2.1, 4.1)
+ *   cnr_quant_error    the l2 error metric of Section 5.2
+ *   cnr_select_greedy_params   greedy parameters by profiling a sample (Section 5.2)
+ *   cnr_host_writer_*, cnr_encode_to_host   chunked encode into host memory with the copy of one
+ *                      chunk overlapping the encode of the next (Sections 4.4, 5.2)
+ *   cnr_policy_*       the incremental-checkpoint policies (Section 5.1), host only
  *
  * General rules
  *   - Every pointer argument is a DEVICE pointer owned by the caller unless its comment says
