@@ -675,3 +675,51 @@ def test_host_writer_back_to_back_tables_and_argument_errors(ctx):
         P.cnr_host_writer_create(ctx, 12, 3, 1024)
     assert e.value.status == P.CNR_E_DIM
     _poll_clean(ctx)
+
+
+def test_seeded_random_cases_against_the_oracle(ctx):
+    # a sweep of seeded random shapes through every encode / restore kernel family: row length, bit
+    # width, range mode, list length, with or without a row list, device-side count below n_max
+    rng = np.random.default_rng(20240607)
+    dims = [4, 8, 16, 24, 32, 40, 64, 72, 96, 128, 160, 256, 264, 512, 1024]
+    n_cases = 0
+    for case in range(160):
+        dim = int(rng.choice(dims))
+        bits = int(rng.choice(BITS))
+        if (dim * bits) % 8:
+            continue
+        n_rows = int(rng.integers(1, 900))
+        n = int(rng.integers(1, n_rows + 1))
+        mode, omode = [(P.CNR_RANGE_MINMAX, O.RANGE_MINMAX), (P.CNR_RANGE_SYMMETRIC, O.RANGE_SYMMETRIC)][int(rng.integers(2))]
+        with_ids = bool(rng.integers(2))
+        n_live = int(rng.integers(1, n + 1))                   # what the device-side count says
+        table = torch.from_numpy((rng.standard_normal((n_rows, dim)) * 10.0 ** rng.uniform(-3, 2)).astype(np.float32)).to(DEV)
+        host = table.cpu().numpy()
+        ids_np = np.sort(rng.choice(n_rows, size=n, replace=False)).astype(np.uint32) if with_ids else np.arange(n, dtype=np.uint32)
+        ids = torch.zeros(max(16, n), dtype=torch.int32, device=DEV)
+        ids[:n] = torch.from_numpy(ids_np.view(np.int32)).to(DEV)
+        n_dev = torch.tensor([n_live], dtype=torch.int64, device=DEV)
+        prb = P.cnr_packed_row_bytes(dim, bits)
+        scale = torch.full((n,), -7.0, device=DEV)
+        bias = torch.full((n,), -7.0, device=DEV)
+        packed = torch.full((n * prb,), 0xEE, dtype=torch.uint8, device=DEV)
+        P.cnr_quantize_rows(ctx, table, n_rows, dim, ids if with_ids else None, n_dev, n, bits, mode, None, scale, bias,
+                            packed=packed)
+        stale = torch.full_like(table, -3.0)
+        P.cnr_restore_rows(ctx, stale, n_rows, dim, ids if with_ids else None, n_dev, n, bits, packed, scale, bias)
+        torch.cuda.synchronize()
+        what = "case %d: dim %d b%d n_rows %d n %d live %d ids %d mode %d" % (case, dim, bits, n_rows, n, n_live, with_ids, mode)
+        assert torch.all(scale[n_live:] == -7.0) and torch.all(packed[n_live * prb:] == 0xEE), what
+        ora = O.quantize_rows(host, ids_np[:n_live], bits, mode=omode)
+        got = dict(scale=scale.cpu().numpy()[:n_live], bias=bias.cpu().numpy()[:n_live],
+                   codes=O.unpack(packed.cpu().numpy()[:n_live * prb].reshape(n_live, prb), dim, bits))
+        assert np.array_equal(got["scale"].view(np.uint32), ora["scale"].view(np.uint32)), what
+        assert np.array_equal(got["bias"].view(np.uint32), ora["bias"].view(np.uint32)), what
+        diff = np.abs(got["codes"].astype(np.int16) - ora["codes"].astype(np.int16))
+        assert diff.max(initial=0) <= 1 and np.count_nonzero(diff) <= max(1, diff.size // 2000), what
+        want = np.full_like(host, -3.0)
+        O.restore_rows(want, ids_np[:n_live], bits, packed.cpu().numpy()[:n_live * prb].reshape(n_live, prb), got["scale"], got["bias"])
+        assert np.array_equal(stale.cpu().numpy(), want), what
+        n_cases += 1
+    assert n_cases > 100
+    _poll_clean(ctx)
