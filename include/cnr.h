@@ -52,7 +52,8 @@
  *             row one little-endian bit stream in which element j occupies stream bits
  *             [j*bits, (j+1)*bits), least-significant code bit first (stream bit t is bit
  *             (t & 7) of byte (t >> 3)); 16-byte aligned base
- *   codes_u8  uint8 [n][dim], one code per byte; 4-byte aligned base
+ *   codes_u8  uint8 [n][dim], one code per byte; 16-byte aligned base where cnr_quantize_rows
+ *             writes it
  */
 #ifndef CNR_H
 #define CNR_H

@@ -316,7 +316,7 @@ quantize_tile_kernel(const QuantArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Greedy range search (Approach 3), dim = 16 * L with L = 4, 8 or 16 lanes per row.  Bound by
+// Greedy range search (Approach 3), dim = 16 * L with L = 1, 2, 4, 8 or 16 lanes per row.  Bound by
 // vector-ALU issue: 1 + 2 * n_iter candidate ranges are tried per row.
 //
 // Every lane owns sixteen consecutive elements (four 16-byte loads) of one row, L neighbouring lanes
@@ -335,24 +335,24 @@ quantize_tile_kernel(const QuantArgs a) {
 // ---------------------------------------------------------------------------------------------
 template <int L>
 __device__ __forceinline__ float lanes_min(float v) {
-    v = fminf(v, dpp_f<0xB1>(v));
-    v = fminf(v, dpp_f<0x4E>(v));
+    if constexpr (L >= 2) v = fminf(v, dpp_f<0xB1>(v));
+    if constexpr (L >= 4) v = fminf(v, dpp_f<0x4E>(v));
     if constexpr (L >= 8) v = fminf(v, dpp_f<0x141>(v));
     if constexpr (L >= 16) v = fminf(v, dpp_f<0x140>(v));
     return v;
 }
 template <int L>
 __device__ __forceinline__ float lanes_max(float v) {
-    v = fmaxf(v, dpp_f<0xB1>(v));
-    v = fmaxf(v, dpp_f<0x4E>(v));
+    if constexpr (L >= 2) v = fmaxf(v, dpp_f<0xB1>(v));
+    if constexpr (L >= 4) v = fmaxf(v, dpp_f<0x4E>(v));
     if constexpr (L >= 8) v = fmaxf(v, dpp_f<0x141>(v));
     if constexpr (L >= 16) v = fmaxf(v, dpp_f<0x140>(v));
     return v;
 }
 template <int L>
 __device__ __forceinline__ double lanes_sum(double v) {
-    v += dpp_d<0xB1>(v);
-    v += dpp_d<0x4E>(v);
+    if constexpr (L >= 2) v += dpp_d<0xB1>(v);
+    if constexpr (L >= 4) v += dpp_d<0x4E>(v);
     if constexpr (L >= 8) v += dpp_d<0x141>(v);
     if constexpr (L >= 16) v += dpp_d<0x140>(v);
     return v;
@@ -465,11 +465,17 @@ __global__ void __launch_bounds__(kBlock) quantize_greedy_kernel(const QuantArgs
             search(std::true_type{});
 
         // ---- per-row parameters: lane 0 of the row writes scale, lane 1 bias, lanes 2, 3 min, max
+        // (with fewer than four lanes per row, the lanes there are share them out)
         const float scale = (hi - lo) / QMAXF;
-        {
+        if constexpr (L >= 4) {
             float *dst = j == 0 ? a.scale : j == 1 ? a.bias : j == 2 ? a.row_min : a.row_max;
             const float v = j == 0 ? scale : j == 1 ? lo : j == 2 ? X_min : X_max;
             if (j < 4 && dst && live) dst[k] = v;
+        } else {
+            if (live && j == 0) a.scale[k] = scale;
+            if (live && j == L - 1) a.bias[k] = lo;
+            if (live && j == 0 && a.row_min) a.row_min[k] = X_min;
+            if (live && j == L - 1 && a.row_max) a.row_max[k] = X_max;
         }
 
         // ---- final codes by F_Q as written; h[i] = the four codes of x[i], first element lowest
@@ -498,13 +504,22 @@ __global__ void __launch_bounds__(kBlock) quantize_greedy_kernel(const QuantArgs
             } else {  // 3 bits: 48 bits per lane; even lanes append their right neighbour's 48 bits
                 const uint32_t w0 = h[0] | (h[1] << 12) | (h[2] << 24);  // stream bits 0..31
                 const uint32_t w1 = (h[2] >> 8) | (h[3] << 4);           // stream bits 32..47
-                const uint32_t n0 = (uint32_t)dpp_i<0xB1>((int)w0);      // lane ^ 1
-                const uint32_t n1 = (uint32_t)dpp_i<0xB1>((int)w1);
-                if (live && !(j & 1)) {
-                    uint32_t *d3 = reinterpret_cast<uint32_t *>(dst);
-                    d3[0] = w0;
-                    d3[1] = w1 | (n0 << 16);
-                    d3[2] = (n0 >> 16) | (n1 << 16);
+                if constexpr (L == 1) {  // the row is this lane's 48 bits alone
+                    uint16_t *d2 = reinterpret_cast<uint16_t *>(dst);
+                    if (live) {
+                        d2[0] = (uint16_t)w0;
+                        d2[1] = (uint16_t)(w0 >> 16);
+                        d2[2] = (uint16_t)w1;
+                    }
+                } else {
+                    const uint32_t n0 = (uint32_t)dpp_i<0xB1>((int)w0);  // lane ^ 1
+                    const uint32_t n1 = (uint32_t)dpp_i<0xB1>((int)w1);
+                    if (live && !(j & 1)) {
+                        uint32_t *d3 = reinterpret_cast<uint32_t *>(dst);
+                        d3[0] = w0;
+                        d3[1] = w1 | (n0 << 16);
+                        d3[2] = (n0 >> 16) | (n1 << 16);
+                    }
                 }
             }
         }
@@ -807,6 +822,8 @@ void launch_bits(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
     if (a.dim == 64) return greedy ? launch_greedy<4, BITS>(ctx, a, s) : launch_tile<1, BITS>(ctx, a, s);
     if (a.dim == 128) return greedy ? launch_greedy<8, BITS>(ctx, a, s) : launch_tile<2, BITS>(ctx, a, s);
     if (a.dim == 256) return greedy ? launch_greedy<16, BITS>(ctx, a, s) : launch_tile<4, BITS>(ctx, a, s);
+    if (greedy && a.dim == 32) return launch_greedy<2, BITS>(ctx, a, s);
+    if (greedy && a.dim == 16) return launch_greedy<1, BITS>(ctx, a, s);
     if (greedy) {  // other row lengths, greedy: one wave per row
         const unsigned grid = cnr_grid(ctx, a.n_max, kWavesPerBlock, 8);
         hipLaunchKernelGGL((quantize_rows_generic_kernel<BITS>), dim3(grid), dim3(kBlock), 0, s, a.table,
@@ -840,7 +857,7 @@ cnr_status cnr_quantize_rows_batch(cnr_ctx *ctx, const cnr_table_job *jobs, uint
         const cnr_table_job &j = jobs[i];
         if (j.capacity == 0) continue;
         if (!j.table || !j.scale || !j.bias || j.n_rows == 0 || j.n_rows >= (1ull << 32)) return CNR_E_INVALID;
-        if (((uintptr_t)j.table % 16) || ((uintptr_t)j.packed % 16) || ((uintptr_t)j.codes_u8 % 4) ||
+        if (((uintptr_t)j.table % 16) || ((uintptr_t)j.packed % 16) || ((uintptr_t)j.codes_u8 % 16) ||
             ((uintptr_t)j.scale % 4) || ((uintptr_t)j.bias % 4) || ((uintptr_t)j.row_min % 4) ||
             ((uintptr_t)j.row_max % 4) || ((uintptr_t)j.row_ids % 16) || ((uintptr_t)j.n_dirty_dev % 8))
             return CNR_E_ALIGN;

@@ -250,7 +250,7 @@ def test_special_rows(ctx):
 
 
 @pytest.mark.parametrize("bits", (2, 3, 4))
-@pytest.mark.parametrize("dim", [64, 128, 40])
+@pytest.mark.parametrize("dim", [64, 128, 40, 16, 32, 256])
 @pytest.mark.parametrize("params", [(25, 1.0), (45, 0.6), (100, 1.0)])
 def test_greedy_encode(ctx, bits, dim, params):
     print("case greedy bits=%d dim=%d params=%s" % (bits, dim, params), flush=True)
