@@ -85,25 +85,44 @@ __device__ __forceinline__ double fq_sq_err(float x, float lo, float hi, float s
 //   - rows past the end of the list and row ids outside the table are handled by clamping the
 //     addresses that are read and masking what is stored, not by branches.
 // ---------------------------------------------------------------------------------------------
-constexpr int kTileQuarterBytes = 80;                  // sixteen floats + 16 bytes
-constexpr int kTileRowBytes = 4 * kTileQuarterBytes;   // 320
-constexpr int kTileBytes = 16 * kTileRowBytes;         // one wave: 5120
+// Shapes.  Q = dim / 16.  Rows of 64 elements and more (Q = 4 * M) go through the tile in M chunks of
+// 64 elements, with 16 rows per pass, 16 lanes per row in the load layout and 4 in the compute
+// layout, as described above.  Rows of 32 and 16 elements (Q = 2, 1) keep 4 KB per pass by taking
+// 32 and 64 rows per pass: 8 and 4 lanes per row in the load layout, 2 and 1 in the compute layout
+// (a lane still holds 16 consecutive elements).
+template <int Q>
+struct TileShape {
+    static_assert(Q == 1 || Q == 2 || (Q >= 4 && Q % 4 == 0), "row length");
+    static constexpr int DIM = 16 * Q;
+    static constexpr int LC = Q >= 4 ? 4 : Q;        // lanes per row, compute layout
+    static constexpr int M = Q >= 4 ? Q / 4 : 1;     // chunks per row
+    static constexpr int CHUNK = DIM / M;            // elements per chunk: 64, 32 or 16
+    static constexpr int LR = CHUNK / 4;             // lanes per row, load layout
+    static constexpr int ROWS = kWave / LC;          // rows per pass: 16, 32 or 64
+    static constexpr int ROW_BYTES = 80 * (CHUNK / 16);  // tile: 16 elements + 16 bytes per segment
+};
+constexpr int kTileBytes = 5120;  // one wave: ROWS * ROW_BYTES for every shape
 
-__device__ __forceinline__ float quad_min(float v) {   // over the four lanes of a quad
-    v = fminf(v, dpp_f<0xB1>(v));
-    return fminf(v, dpp_f<0x4E>(v));
+template <int LC>
+__device__ __forceinline__ float row_lanes_min(float v) {  // over the LC lanes of a row
+    if constexpr (LC >= 2) v = fminf(v, dpp_f<0xB1>(v));
+    if constexpr (LC >= 4) v = fminf(v, dpp_f<0x4E>(v));
+    return v;
 }
-__device__ __forceinline__ float quad_max(float v) {
-    v = fmaxf(v, dpp_f<0xB1>(v));
-    return fmaxf(v, dpp_f<0x4E>(v));
+template <int LC>
+__device__ __forceinline__ float row_lanes_max(float v) {
+    if constexpr (LC >= 2) v = fmaxf(v, dpp_f<0xB1>(v));
+    if constexpr (LC >= 4) v = fmaxf(v, dpp_f<0x4E>(v));
+    return v;
 }
 
 // Quantizes and stores this lane's 16 * M elements of row k (compute layout): x[c][i] holds elements
-// 64c + 16j + 4i .. + 3.
-template <int M, int BITS>
-__device__ __forceinline__ void encode_row_quarter(const QuantArgs &a, uint64_t k, bool live, int j,
-                                                   const float4 (&x)[M][4]) {
-    constexpr int DIM = 64 * M;
+// CHUNK * c + 16j + 4i .. + 3.
+template <int Q, int BITS>
+__device__ __forceinline__ void encode_row_share(const QuantArgs &a, uint64_t k, bool live, int j,
+                                                 const float4 (&x)[TileShape<Q>::M][4]) {
+    using S = TileShape<Q>;
+    constexpr int M = S::M, LC = S::LC, DIM = S::DIM;
     constexpr float QMAXF = (float)((1 << BITS) - 1);
     constexpr uint64_t P = (uint64_t)DIM * BITS / 8;  // packed bytes per row
     constexpr float MAGIC = 12582912.0f;              // 1.5 * 2^23: x + MAGIC rounds x to an integer
@@ -121,8 +140,8 @@ __device__ __forceinline__ void encode_row_quarter(const QuantArgs &a, uint64_t 
             mn = fminf(fminf(mn, x[c][i].x), fminf(x[c][i].y, fminf(x[c][i].z, x[c][i].w)));
             mx = fmaxf(fmaxf(mx, x[c][i].x), fmaxf(x[c][i].y, fmaxf(x[c][i].z, x[c][i].w)));
         }
-    const float X_min = quad_min(mn) + 0.0f;  // -0.0 -> +0.0
-    const float X_max = quad_max(mx) + 0.0f;
+    const float X_min = row_lanes_min<LC>(mn) + 0.0f;  // -0.0 -> +0.0
+    const float X_max = row_lanes_max<LC>(mx) + 0.0f;
     float lo = X_min, hi = X_max;
     if (a.mode == kModeSymmetric) {
         const float m = fmaxf(fabsf(X_min), fabsf(X_max));
@@ -130,18 +149,24 @@ __device__ __forceinline__ void encode_row_quarter(const QuantArgs &a, uint64_t 
         hi = m;
     }
 
-    // ---- the row's parameters; lane 0 of the row writes scale, lane 1 bias, lanes 2, 3 min, max
+    // ---- the row's parameters: with four lanes per row, lane 0 writes scale, lane 1 bias, lanes 2, 3
+    // min, max; with fewer, the lanes there are share them out
     const float scale = (hi - lo) / QMAXF;
-    {
+    if constexpr (LC == 4) {
         float *dst = j == 0 ? a.scale : j == 1 ? a.bias : j == 2 ? a.row_min : a.row_max;
         const float v = j == 0 ? scale : j == 1 ? lo : j == 2 ? X_min : X_max;
         if (dst && live) store_stream<float>(dst + k, v);
+    } else {
+        if (live && j == 0) store_stream<float>(a.scale + k, scale);
+        if (live && j == LC - 1) store_stream<float>(a.bias + k, lo);
+        if (live && j == 0 && a.row_min) store_stream<float>(a.row_min + k, X_min);
+        if (live && j == LC - 1 && a.row_max) store_stream<float>(a.row_max + k, X_max);
     }
     const float f = scale < 0x1p-100f ? 0x1p120f : scale > 0x1p100f ? 0x1p-120f : 1.0f;
     const float fscale = scale * f;
     const float inv = scale == 0.0f ? 0.0f : 1.0f / fscale;  // scale 0: every code 0
 
-    // ---- quantize; h[c][i] = the four codes of elements 64c + 16j + 4i .. + 3, first element lowest
+    // ---- quantize; h[c][i] = the four codes of x[c][i], first element lowest
     uint32_t h[M][4];
     auto quantize_by_reciprocal = [&](auto rescale) {
         constexpr bool RESCALE = decltype(rescale)::value;
@@ -163,7 +188,7 @@ __device__ __forceinline__ void encode_row_quarter(const QuantArgs &a, uint64_t 
                 m = (m << BITS) + b1;
                 h[c][i] = (m << BITS) + b0 - MERGED_BIAS;
                 if (a.codes && live)  // one code per byte as well (uniform branch)
-                    *reinterpret_cast<uint32_t *>(a.codes + k * (uint64_t)DIM + 64 * c + 16 * j + 4 * i) =
+                    *reinterpret_cast<uint32_t *>(a.codes + k * (uint64_t)DIM + S::CHUNK * c + 16 * j + 4 * i) =
                         (((((b3 << 8) + b2) << 8) + b1) << 8) + b0 - MERGED_BIAS8;
             }
     };
@@ -176,7 +201,7 @@ __device__ __forceinline__ void encode_row_quarter(const QuantArgs &a, uint64_t 
     for (int c = 0; c < M; ++c) {
         // ---- packed codes: this lane's bits are 2 * BITS contiguous bytes of the row
         if (a.packed) {
-            uint8_t *dst = a.packed + k * P + (8 * BITS) * c + (2 * BITS) * j;
+            uint8_t *dst = a.packed + k * P + (2 * BITS * LC) * c + (2 * BITS) * j;
             if constexpr (BITS == 8) {
                 if (live) store_stream<u32x4>(dst, u32x4{h[c][0], h[c][1], h[c][2], h[c][3]});
             } else if constexpr (BITS == 4) {
@@ -186,13 +211,22 @@ __device__ __forceinline__ void encode_row_quarter(const QuantArgs &a, uint64_t 
             } else {  // 3 bits: 48 bits per lane; even lanes append their right neighbour's 48 bits
                 const uint32_t w0 = h[c][0] | (h[c][1] << 12) | (h[c][2] << 24);  // stream bits 0..31
                 const uint32_t w1 = (h[c][2] >> 8) | (h[c][3] << 4);              // stream bits 32..47
-                const uint32_t n0 = (uint32_t)dpp_i<0xB1>((int)w0);                // lane ^ 1
-                const uint32_t n1 = (uint32_t)dpp_i<0xB1>((int)w1);
-                if (live && !(j & 1)) {
-                    uint32_t *d3 = reinterpret_cast<uint32_t *>(dst);
-                    store_stream<uint32_t>(d3, w0);
-                    store_stream<uint32_t>(d3 + 1, w1 | (n0 << 16));
-                    store_stream<uint32_t>(d3 + 2, (n0 >> 16) | (n1 << 16));
+                if constexpr (LC == 1) {  // the row is this lane's 48 bits alone
+                    uint16_t *d2 = reinterpret_cast<uint16_t *>(dst);
+                    if (live) {
+                        d2[0] = (uint16_t)w0;
+                        d2[1] = (uint16_t)(w0 >> 16);
+                        d2[2] = (uint16_t)w1;
+                    }
+                } else {
+                    const uint32_t n0 = (uint32_t)dpp_i<0xB1>((int)w0);  // lane ^ 1
+                    const uint32_t n1 = (uint32_t)dpp_i<0xB1>((int)w1);
+                    if (live && !(j & 1)) {
+                        uint32_t *d3 = reinterpret_cast<uint32_t *>(dst);
+                        store_stream<uint32_t>(d3, w0);
+                        store_stream<uint32_t>(d3 + 1, w1 | (n0 << 16));
+                        store_stream<uint32_t>(d3 + 2, (n0 >> 16) | (n1 << 16));
+                    }
                 }
             }
         }
@@ -205,12 +239,13 @@ struct PassIds {
     uint32_t own;
 };
 
-// Ids of pass `pass` (which must hold at least one row).  Rows past the end repeat the last row of
-// the pass; nothing of theirs is stored.
+// Ids of pass `pass` of ROWS rows (which must hold at least one row).  Rows past the end repeat the
+// last row of the pass; nothing of theirs is stored.
+template <int ROWS>
 __device__ __forceinline__ void load_pass_ids(const QuantArgs &a, uint64_t n, uint64_t pass, int g, int rho, PassIds &o) {
-    const uint64_t base = pass * 16u;
+    const uint64_t base = pass * (uint64_t)ROWS;
     const uint64_t left = n - base;
-    const uint32_t rows = left < 16u ? (uint32_t)left : 16u;  // uniform
+    const uint32_t rows = left < (uint64_t)ROWS ? (uint32_t)left : (uint32_t)ROWS;  // uniform
     const uint32_t own_i = (uint32_t)rho < rows ? (uint32_t)rho : rows - 1u;
     uint32_t idx[4];
 #pragma unroll
@@ -226,7 +261,7 @@ __device__ __forceinline__ void load_pass_ids(const QuantArgs &a, uint64_t n, ui
         return;
     }
     o.own = a.row_ids[base + own_i];
-    if (rows == 16u) {  // one 16-byte load
+    if (rows == (uint32_t)ROWS) {  // one 16-byte load
         const uint4 v = *reinterpret_cast<const uint4 *>(a.row_ids + base + 4u * (uint32_t)g);
         o.rid[0] = v.x; o.rid[1] = v.y; o.rid[2] = v.z; o.rid[3] = v.w;
     } else {
@@ -235,19 +270,20 @@ __device__ __forceinline__ void load_pass_ids(const QuantArgs &a, uint64_t n, ui
     }
 }
 
-template <int M, int BITS>
+template <int Q, int BITS>
 __device__ __forceinline__ void encode_table(const QuantArgs &a, unsigned char *tile /* this wave's kTileBytes of LDS */) {
-    constexpr int DIM = 64 * M;
+    using S = TileShape<Q>;
+    constexpr int DIM = S::DIM, M = S::M, ROWS = S::ROWS;
     const uint64_t n = row_count(a);
     const int lane = tid_x() & (kWave - 1);
-    const int g = lane >> 4, l = lane & 15;  // load layout: group (four rows), lane in group
-    const int rho = lane >> 2, j = lane & 3; // compute layout: row of the pass, quarter
+    const int g = lane / S::LR, l = lane % S::LR;   // load layout: group (four rows), lane in group
+    const int rho = lane / S::LC, j = lane % S::LC; // compute layout: row of the pass, share of the row
     const uint32_t last_row = (uint32_t)a.n_rows - 1u;  // the host checks 1 <= n_rows < 2^32
-    unsigned char *const wr = tile + (4 * g) * kTileRowBytes + (l >> 2) * kTileQuarterBytes + (l & 3) * 16;
-    const unsigned char *const rd = tile + rho * kTileRowBytes + j * kTileQuarterBytes;
+    unsigned char *const wr = tile + (4 * g) * S::ROW_BYTES + (l >> 2) * 80 + (l & 3) * 16;
+    const unsigned char *const rd = tile + rho * S::ROW_BYTES + j * 80;
 
-    // Requests this lane's share of the sixteen rows of a pass (ids outside the table read the
-    // last row instead).
+    // Requests this lane's share of the rows of a pass (ids outside the table read the last row
+    // instead).
     f32x4 ld[4][M];
     auto gather = [&](const PassIds &ids) {
 #pragma unroll
@@ -255,7 +291,7 @@ __device__ __forceinline__ void encode_table(const QuantArgs &a, unsigned char *
             const uint32_t r = ids.rid[u] < last_row ? ids.rid[u] : last_row;
             const float *src = a.table + (uint64_t)r * DIM + 4u * (uint32_t)l;
 #pragma unroll
-            for (int c = 0; c < M; ++c) ld[u][c] = load_stream<f32x4>(src + 64 * c);
+            for (int c = 0; c < M; ++c) ld[u][c] = load_stream<f32x4>(src + S::CHUNK * c);
         }
     };
 
@@ -263,27 +299,27 @@ __device__ __forceinline__ void encode_table(const QuantArgs &a, unsigned char *
     // next pass and the ids of the one after that are on their way.
     const uint32_t n_waves = a.n_waves;
     uint64_t pass = wave_in_grid();
-    if (pass * 16u >= n) return;
+    if (pass * ROWS >= n) return;
     PassIds ids;
-    load_pass_ids(a, n, pass, g, rho, ids);
+    load_pass_ids<ROWS>(a, n, pass, g, rho, ids);
     gather(ids);
     uint32_t own = ids.own;
     uint64_t next = pass + n_waves;
-    if (next * 16u < n) load_pass_ids(a, n, next, g, rho, ids);
+    if (next * ROWS < n) load_pass_ids<ROWS>(a, n, next, g, rho, ids);
     for (;;) {
-        const uint64_t base = pass * 16u;  // first row of the pass (uniform)
+        const uint64_t base = pass * (uint64_t)ROWS;  // first row of the pass (uniform)
         const uint64_t left = n - base;
-        const uint32_t rows = left < 16u ? (uint32_t)left : 16u;
+        const uint32_t rows = left < (uint64_t)ROWS ? (uint32_t)left : (uint32_t)ROWS;
         const bool in_table = own <= last_row;
         const bool live = (uint32_t)rho < rows && in_table;
         if ((uint32_t)rho < rows && !in_table && j == 0) raise_flag(a.err, CNR_FLAG_ROW_ID);
 
-        // ---- transpose through the wave's LDS tile, one 64-element chunk at a time
+        // ---- transpose through the wave's LDS tile, one chunk at a time
         float4 x[M][4];
 #pragma unroll
         for (int c = 0; c < M; ++c) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) *reinterpret_cast<f32x4 *>(wr + u * kTileRowBytes) = ld[u][c];
+            for (int u = 0; u < 4; ++u) *reinterpret_cast<f32x4 *>(wr + u * S::ROW_BYTES) = ld[u][c];
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int i = 0; i < 4; ++i) x[c][i] = *reinterpret_cast<const float4 *>(rd + 16 * i);
@@ -291,28 +327,29 @@ __device__ __forceinline__ void encode_table(const QuantArgs &a, unsigned char *
         }
 
         // ---- the load registers are free again: request the next pass
-        const bool has_next = next * 16u < n;  // uniform
+        const bool has_next = next * ROWS < n;  // uniform
         const uint64_t next2 = next + n_waves;
         if (has_next) {
             gather(ids);
             own = ids.own;
-            if (next2 * 16u < n) load_pass_ids(a, n, next2, g, rho, ids);
+            if (next2 * ROWS < n) load_pass_ids<ROWS>(a, n, next2, g, rho, ids);
         }
 
-        encode_row_quarter<M, BITS>(a, base + (uint32_t)rho, live, j, x);
+        encode_row_share<Q, BITS>(a, base + (uint32_t)rho, live, j, x);
         if (!has_next) break;
         pass = next;
         next = next2;
     }
 }
 
-// The register budget is pinned to 5-6 / 3-4 / 2 waves per SIMD for M = 1 / 2 / 4: left alone, the
-// compiler lands a few registers to either side of those limits from one small change to the next.
-template <int M, int BITS>
-__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(M == 1 ? 5 : M == 2 ? 3 : 2, M == 1 ? 6 : M == 2 ? 4 : 2)))
+// The register budget is pinned to 5-6 / 3-4 / 2 waves per SIMD for rows of up to 64 / 128 / 256
+// elements: left alone, the compiler lands a few registers to either side of those limits from one
+// small change to the next.
+template <int Q, int BITS>
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(Q <= 4 ? 5 : Q == 8 ? 3 : 2, Q <= 4 ? 6 : Q == 8 ? 4 : 2)))
 quantize_tile_kernel(const QuantArgs a) {
     __shared__ __align__(16) unsigned char tiles[kWavesPerBlock * kTileBytes];
-    encode_table<M, BITS>(a, tiles + (tid_x() / kWave) * kTileBytes);
+    encode_table<Q, BITS>(a, tiles + (tid_x() / kWave) * kTileBytes);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -792,12 +829,12 @@ pack_kernel(const uint8_t *__restrict__ codes, const uint64_t *__restrict__ n_de
     }
 }
 
-template <int M, int BITS>
+template <int Q, int BITS>
 void launch_tile(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
-    const unsigned grid = cnr_grid(ctx, a.n_max, 16u * kWavesPerBlock,
-                                   cnr_resident_blocks_per_cu<quantize_tile_kernel<M, BITS>>());
+    const unsigned grid = cnr_grid(ctx, a.n_max, (uint64_t)TileShape<Q>::ROWS * kWavesPerBlock,
+                                   cnr_resident_blocks_per_cu<quantize_tile_kernel<Q, BITS>>());
     a.n_waves = grid * kWavesPerBlock;
-    hipLaunchKernelGGL((quantize_tile_kernel<M, BITS>), dim3(grid), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL((quantize_tile_kernel<Q, BITS>), dim3(grid), dim3(kBlock), 0, s, a);
 }
 
 template <int L, int BITS>
@@ -819,11 +856,11 @@ void launch_strided(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
 template <int BITS>
 void launch_bits(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
     const bool greedy = a.mode == kModeGreedy && a.n_iter > 0;  // zero iterations: plain min/max
-    if (a.dim == 64) return greedy ? launch_greedy<4, BITS>(ctx, a, s) : launch_tile<1, BITS>(ctx, a, s);
-    if (a.dim == 128) return greedy ? launch_greedy<8, BITS>(ctx, a, s) : launch_tile<2, BITS>(ctx, a, s);
-    if (a.dim == 256) return greedy ? launch_greedy<16, BITS>(ctx, a, s) : launch_tile<4, BITS>(ctx, a, s);
-    if (greedy && a.dim == 32) return launch_greedy<2, BITS>(ctx, a, s);
-    if (greedy && a.dim == 16) return launch_greedy<1, BITS>(ctx, a, s);
+    if (a.dim == 16) return greedy ? launch_greedy<1, BITS>(ctx, a, s) : launch_tile<1, BITS>(ctx, a, s);
+    if (a.dim == 32) return greedy ? launch_greedy<2, BITS>(ctx, a, s) : launch_tile<2, BITS>(ctx, a, s);
+    if (a.dim == 64) return greedy ? launch_greedy<4, BITS>(ctx, a, s) : launch_tile<4, BITS>(ctx, a, s);
+    if (a.dim == 128) return greedy ? launch_greedy<8, BITS>(ctx, a, s) : launch_tile<8, BITS>(ctx, a, s);
+    if (a.dim == 256) return greedy ? launch_greedy<16, BITS>(ctx, a, s) : launch_tile<16, BITS>(ctx, a, s);
     if (greedy) {  // other row lengths, greedy: one wave per row
         const unsigned grid = cnr_grid(ctx, a.n_max, kWavesPerBlock, 8);
         hipLaunchKernelGGL((quantize_rows_generic_kernel<BITS>), dim3(grid), dim3(kBlock), 0, s, a.table,
