@@ -41,8 +41,8 @@ ISSUE_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # one vector instruction per lane
 # per dirty row, valid only for the kernel source whose hash is recorded with it.
 TRAFFIC_PER_ROW = {
     # _kernel_hash() : (workload, bytes per dirty row)
-    # (2.000 * 190490.1 KiB FETCH_SIZE + 1.000 * 60149.6 KiB WRITE_SIZE) / 1,500,122 rows per launch
-    "323eb128a062ee92f5c433825fe8a469888cad6db0f30a744e438e1408aa6f4c": ("cfg4/b4", 301.12),
+    # (2.000 * 190489.1 KiB FETCH_SIZE + 1.000 * 60151.7 KiB WRITE_SIZE) / 1,500,122 rows per launch
+    "cf1533b45736d648e449e29e5ff9121d469d6f622fddea6f909bf84222b69cb5": ("cfg4/b4", 301.12),
 }
 
 
@@ -214,7 +214,7 @@ def main() -> int:
     rec = TRAFFIC_PER_ROW.get(_kernel_hash())
     if rec and rec[0] == "%s/b%d" % (w.name, bits):
         traffic = rec[1] * rows_per_launch
-    roofline = {"bound": "hbm", "kernel": "quantize_tile_kernel<%d, %d>" % (w.dim // 64, bits),
+    roofline = {"bound": "hbm", "kernel": "quantize_tile_kernel<%d, %d>" % (w.dim // 16, bits),
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "bytes_per_launch": int(enc_bytes), "avg_launch_ms": round(enc_launch_ms, 5),

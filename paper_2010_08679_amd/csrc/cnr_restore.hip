@@ -21,24 +21,35 @@ __device__ __forceinline__ void quad_transpose(uint32_t (&r)[4], int j) {
     }
 }
 
-// What one group of sixteen lanes needs to restore its four rows k0 .. k0+3: ids, scales and biases
+// Shape of the kernel for rows of DIM = 16 * Q floats: LR lanes per group of four rows (16, or the
+// row's 4 * Q units of 16 bytes when it is shorter than 64 floats), M chunks of 64 floats per row.
+template <int Q>
+struct RestoreShape {
+    static constexpr int DIM = 16 * Q;
+    static constexpr int LR = Q >= 4 ? 16 : 4 * Q;
+    static constexpr int M = Q >= 4 ? Q / 4 : 1;
+    static constexpr int ROWS = 4 * (kWave / LR);  // rows per wave and pass
+};
+
+// What one group of LR lanes needs to restore its four rows k0 .. k0+3: ids, scales and biases
 // (the same 16 bytes for every lane of the group, one load each) and this lane's share of the packed
 // codes, fetched in the layout the encoder stored them in: quad lane j of quad q holds the codes of
 // the 16 consecutive elements 64c + 16q .. of row k0 + j (w[c][0..]: 16*BITS bits).
-template <int M, int BITS>
+template <int Q, int BITS>
 struct RestoreInput {
     uint4 ids;
     float4 scale, bias;
-    uint32_t w[M][BITS == 8 ? 4 : BITS == 4 ? 2 : BITS == 3 ? 3 : 1];
+    uint32_t w[RestoreShape<Q>::M][BITS == 8 ? 4 : BITS == 4 ? 2 : BITS == 3 ? 3 : 1];
 };
 
-template <int M, int BITS>
+template <int Q, int BITS>
 __device__ __forceinline__ void fetch_restore_input(const uint32_t *__restrict__ row_ids,
                                                     const uint8_t *__restrict__ packed,
                                                     const float *__restrict__ scale,
                                                     const float *__restrict__ bias, uint64_t n_max, uint64_t k0,
-                                                    int q, int j, RestoreInput<M, BITS> &in) {
-    constexpr uint64_t P = (uint64_t)(64 * M) * BITS / 8;
+                                                    int q, int j, RestoreInput<Q, BITS> &in) {
+    constexpr int M = RestoreShape<Q>::M;
+    constexpr uint64_t P = (uint64_t)RestoreShape<Q>::DIM * BITS / 8;
     if (k0 + 3 < n_max) {  // every buffer holds n_max rows: whole 16-byte loads
         in.ids = row_ids ? *reinterpret_cast<const uint4 *>(row_ids + k0)
                          : make_uint4((uint32_t)k0, (uint32_t)k0 + 1, (uint32_t)k0 + 2, (uint32_t)k0 + 3);
@@ -70,6 +81,14 @@ __device__ __forceinline__ void fetch_restore_input(const uint32_t *__restrict__
             in.w[c][0] = v.x; in.w[c][1] = v.y;
         } else if constexpr (BITS == 2) {
             in.w[c][0] = row_in_buffer ? load_stream<uint32_t>(row + 16 * c + 4 * q) : 0u;
+        } else if constexpr (Q == 1) {  // 3 bits, one quad per row: its 48 bits, at a two-byte boundary
+            const uint16_t *src = reinterpret_cast<const uint16_t *>(row);
+            const uint32_t h0 = row_in_buffer ? load_stream<uint16_t>(src) : 0u;
+            const uint32_t h1 = row_in_buffer ? load_stream<uint16_t>(src + 1) : 0u;
+            const uint32_t h2 = row_in_buffer ? load_stream<uint16_t>(src + 2) : 0u;
+            in.w[c][0] = h0 | (h1 << 16);
+            in.w[c][1] = h2;
+            in.w[c][2] = 0u;
         } else {  // 3 bits: even quads fetch 12 bytes = their own 48 bits and the next quad's
             const uint32_t *src = reinterpret_cast<const uint32_t *>(row + 24 * c + 12 * (q >> 1));
             const bool fetch = row_in_buffer && !(q & 1);
@@ -80,10 +99,10 @@ __device__ __forceinline__ void fetch_restore_input(const uint32_t *__restrict__
     }
 }
 
-// Fast path, dim = 64 * M: the mirror image of the encoder.  Sixteen lanes share a row, four rows
-// per group; packed codes arrive as whole words per lane and a 4x4 transpose inside each quad turns
-// them into "lane l owns elements 64c + 4l .. + 3 of each of the four rows", so the fp32 rows leave
-// as 16-byte streaming stores that cover 256 contiguous bytes per row.  The input of the next batch
+// Fast path, dim = 16 * Q in {16, 32, 64, 128, 256}: the mirror image of the encoder.  LR lanes share
+// a row, four rows per group; packed codes arrive as whole words per lane and a 4x4 transpose inside
+// each quad turns them into "lane l owns elements 64c + 4l .. + 3 of each of the four rows", so the
+// fp32 rows leave as 16-byte streaming stores that cover up to 256 contiguous bytes per row.  The input of the next batch
 // is requested before the current batch is de-quantized and stored.
 struct RestoreJob {
     float *table;
@@ -95,9 +114,11 @@ struct RestoreJob {
     const float *scale, *bias;
     uint32_t n_waves;  // waves of the grid
 };
-template <int M, int BITS>
+template <int Q, int BITS>
 __global__ void __launch_bounds__(kBlock) restore_rows16_kernel(const RestoreJob a, cnr_dev_errors *err) {
-    constexpr int DIM = 64 * M;
+    using S = RestoreShape<Q>;
+    constexpr int DIM = S::DIM, M = S::M, LR = S::LR;
+    constexpr uint64_t ROWS = S::ROWS;
     constexpr uint32_t MASK = (1u << BITS) - 1u;
     float *__restrict__ table = a.table;
     const uint32_t *__restrict__ row_ids = a.row_ids;
@@ -107,22 +128,22 @@ __global__ void __launch_bounds__(kBlock) restore_rows16_kernel(const RestoreJob
     const uint64_t n_rows = a.n_rows, n_max = a.n_max;
     const uint64_t n = live_rows(n_dev, n_max);
     const int lane = tid_x() & (kWave - 1);
-    const int g = lane >> 4;
-    const int l = lane & 15;
+    const int g = lane / LR;
+    const int l = lane % LR;
     const int q = l >> 2;
     const int j = l & 3;
     const uint32_t n_waves = a.n_waves;
     uint64_t batch = wave_in_grid();
-    if (batch * 16u >= n) return;
-    RestoreInput<M, BITS> cur, nxt;
-    fetch_restore_input<M, BITS>(row_ids, packed, scale, bias, n_max, batch * 16u + 4u * (uint64_t)g, q, j, cur);
+    if (batch * ROWS >= n) return;
+    RestoreInput<Q, BITS> cur, nxt;
+    fetch_restore_input<Q, BITS>(row_ids, packed, scale, bias, n_max, batch * ROWS + 4u * (uint64_t)g, q, j, cur);
     for (;;) {
         const uint64_t next = batch + n_waves;
-        const bool has_next = next * 16u < n;  // uniform over the wave
+        const bool has_next = next * ROWS < n;  // uniform over the wave
         if (has_next)
-            fetch_restore_input<M, BITS>(row_ids, packed, scale, bias, n_max, next * 16u + 4u * (uint64_t)g, q, j, nxt);
+            fetch_restore_input<Q, BITS>(row_ids, packed, scale, bias, n_max, next * ROWS + 4u * (uint64_t)g, q, j, nxt);
 
-        const uint64_t k0 = batch * 16u + 4u * (uint64_t)g;
+        const uint64_t k0 = batch * ROWS + 4u * (uint64_t)g;
         const uint32_t rid[4] = {cur.ids.x, cur.ids.y, cur.ids.z, cur.ids.w};
         const float s[4] = {cur.scale.x, cur.scale.y, cur.scale.z, cur.scale.w};
         const float b[4] = {cur.bias.x, cur.bias.y, cur.bias.z, cur.bias.w};
@@ -138,6 +159,10 @@ __global__ void __launch_bounds__(kBlock) restore_rows16_kernel(const RestoreJob
             } else if constexpr (BITS == 2) {
                 t[0] = cur.w[c][0] & 0xFFu; t[1] = (cur.w[c][0] >> 8) & 0xFFu;
                 t[2] = (cur.w[c][0] >> 16) & 0xFFu; t[3] = cur.w[c][0] >> 24;
+            } else if constexpr (Q == 1) {
+                const uint32_t lo32 = cur.w[c][0], hi16 = cur.w[c][1];
+                t[0] = lo32 & 0xFFFu; t[1] = (lo32 >> 12) & 0xFFFu;
+                t[2] = (lo32 >> 24) | ((hi16 & 0xFu) << 8); t[3] = hi16 >> 4;
             } else {
                 // odd quads take bits 48..95 of the 96 their left neighbour quad fetched
                 const uint32_t p1 = (uint32_t)dpp_i<0x114>((int)cur.w[c][1]);  // row_shr:4 = lane - 4
@@ -222,12 +247,12 @@ __global__ void __launch_bounds__(kBlock) restore_strided_kernel(const RestoreJo
     }
 }
 
-template <int M, int BITS>
+template <int Q, int BITS>
 void launch_restore16(cnr_ctx *ctx, hipStream_t st, RestoreJob &a) {
-    const unsigned grid = cnr_grid(ctx, a.n_max, 16u * kWavesPerBlock,
-                                   cnr_resident_blocks_per_cu<restore_rows16_kernel<M, BITS>>());
+    const unsigned grid = cnr_grid(ctx, a.n_max, (uint64_t)RestoreShape<Q>::ROWS * kWavesPerBlock,
+                                   cnr_resident_blocks_per_cu<restore_rows16_kernel<Q, BITS>>());
     a.n_waves = grid * kWavesPerBlock;
-    hipLaunchKernelGGL((restore_rows16_kernel<M, BITS>), dim3(grid), dim3(kBlock), 0, st, a, ctx->dev_err);
+    hipLaunchKernelGGL((restore_rows16_kernel<Q, BITS>), dim3(grid), dim3(kBlock), 0, st, a, ctx->dev_err);
 }
 
 template <int LPR, int BITS>
@@ -240,9 +265,11 @@ void launch_restore_strided(cnr_ctx *ctx, hipStream_t st, uint32_t dim, RestoreJ
 
 template <int BITS>
 void launch_restore(cnr_ctx *ctx, hipStream_t st, uint32_t dim, RestoreJob &a) {
-    if (dim == 64) return launch_restore16<1, BITS>(ctx, st, a);
-    if (dim == 128) return launch_restore16<2, BITS>(ctx, st, a);
-    if (dim == 256) return launch_restore16<4, BITS>(ctx, st, a);
+    if (dim == 16) return launch_restore16<1, BITS>(ctx, st, a);
+    if (dim == 32) return launch_restore16<2, BITS>(ctx, st, a);
+    if (dim == 64) return launch_restore16<4, BITS>(ctx, st, a);
+    if (dim == 128) return launch_restore16<8, BITS>(ctx, st, a);
+    if (dim == 256) return launch_restore16<16, BITS>(ctx, st, a);
     const uint32_t n4 = dim / 4;
     if (n4 <= 4) return launch_restore_strided<4, BITS>(ctx, st, dim, a);
     if (n4 <= 8) return launch_restore_strided<8, BITS>(ctx, st, dim, a);
