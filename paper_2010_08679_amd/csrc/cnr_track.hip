@@ -118,6 +118,109 @@ __global__ void __launch_bounds__(kBlock) mark_flags_kernel(const TrackBatch b, 
     if (bad && (tid_x() & (kWave - 1)) == 0) atomicAdd(&err->n_bad_indices, (unsigned long long)bad);
 }
 
+// Bulk route for tables of up to a few tens of millions of rows: bitmap slices held in LDS.
+//
+// A workgroup owns kSliceRows consecutive rows of one table as a bitmap in LDS (all 160 KB of a
+// compute unit) and one eighth of the table's index stream: it reads its share of the stream, sets
+// the bits of the look-ups that fall into its rows with LDS atomics, and stores the slice to slab
+// s (= its eighth of the stream) of the scratch buffer, eight partial bitmaps per table that
+// fold_slabs_kernel ORs into the bitmap and zeroes again.  Nothing is scattered to memory; the
+// price is that the W = ceil(n_rows / kSliceRows) workgroups of a team read the same eighth of the
+// stream.  Workgroups are dealt to the eight XCDs in turn along x, so x & 7 names both the eighth
+// and the XCD: a team shares its part of the stream through one L2 and memory is read once.
+constexpr int kSliceThreads = 1024;
+constexpr uint32_t kSliceWords = 40960;
+constexpr uint64_t kSliceRows = 32ull * kSliceWords;
+constexpr uint32_t kStreamParts = 8;
+
+template <typename IdxT>
+__global__ void __launch_bounds__(kSliceThreads) mark_slices_kernel(const TrackBatch b, cnr_dev_errors *err) {
+    constexpr int kVec = 16 / (int)sizeof(IdxT);
+    typedef IdxT vec_t __attribute__((ext_vector_type(kVec)));
+    constexpr int kUnroll = 4;
+    __shared__ uint32_t bits[kSliceWords];
+    const TrackJob &t = b.job[wg_y()];
+    const uint32_t part = wg_x() & (kStreamParts - 1u), w = wg_x() / kStreamParts;
+    const uint32_t n_rows = (uint32_t)t.n_rows;
+    const uint64_t first = (uint64_t)w * kSliceRows;
+    if (first >= t.n_rows) return;  // the whole workgroup: tables of a batch differ in size
+    const uint32_t lo = (uint32_t)first;
+    const uint32_t span = n_rows - lo < kSliceRows ? n_rows - lo : (uint32_t)kSliceRows;
+    const uint32_t tid = tid_x();
+    for (uint32_t i = tid; i < kSliceWords; i += kSliceThreads) bits[i] = 0u;
+    __syncthreads();
+
+    unsigned bad = 0;
+    auto look_up = [&](IdxT v) {
+        // a row id is valid iff it is below n_rows < 2^32: upper half zero (int64), not negative
+        bool valid;
+        if constexpr (sizeof(IdxT) == 8) valid = ((uint64_t)v >> 32) == 0 && (uint32_t)v < n_rows;
+        else valid = (uint32_t)v < n_rows;
+        const uint32_t d = (uint32_t)v - lo;
+        if (valid && d < span)
+            __hip_atomic_fetch_or(&bits[d >> 5], 1u << (d & 31u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (w == 0 && !valid) ++bad;
+    };
+
+    // the stream as [head][16-byte vectors][tail]: head and tail are fewer than kVec elements each
+    const IdxT *idx = static_cast<const IdxT *>(t.idx);
+    const uint64_t n = t.n_idx;
+    uint64_t head = ((16u - (uint32_t)((uintptr_t)idx & 15u)) & 15u) / sizeof(IdxT);
+    if (head > n) head = n;
+    const vec_t *vecs = reinterpret_cast<const vec_t *>(idx + head);
+    const uint64_t n_vec = (n - head) / kVec;
+    const uint64_t tail = head + n_vec * kVec;
+    const uint64_t per_part = (n_vec + kStreamParts - 1u) / kStreamParts;
+    const uint64_t v0 = part * per_part;
+    const uint64_t v1 = v0 + per_part < n_vec ? v0 + per_part : n_vec;
+    for (uint64_t p = v0 + tid; p < v1; p += (uint64_t)kSliceThreads * kUnroll) {
+        vec_t v[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const uint64_t q = p + (uint64_t)u * kSliceThreads;
+            if (q < v1) v[u] = vecs[q];
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const uint64_t q = p + (uint64_t)u * kSliceThreads;
+            if (q < v1) {
+#pragma unroll
+                for (int e = 0; e < kVec; ++e) look_up(v[u][e]);
+            }
+        }
+    }
+    if (part == 0) {
+        if (tid < head) look_up(idx[tid]);
+        else if (tid - head < n - tail) look_up(idx[tail + (tid - head)]);
+    }
+    for (int off = 32; off > 0; off >>= 1) bad += __shfl_xor(bad, off);
+    if (bad && (tid & (kWave - 1)) == 0) atomicAdd(&err->n_bad_indices, (unsigned long long)bad);
+    __syncthreads();
+
+    const uint64_t n_words = (t.n_rows + 31u) / 32u;
+    uint32_t *slab = reinterpret_cast<uint32_t *>(t.flags) + part * n_words + (uint64_t)w * kSliceWords;
+    const uint32_t words = (span + 31u) / 32u;
+    for (uint32_t i = tid; i < words; i += kSliceThreads) slab[i] = bits[i];
+}
+
+// bitmap |= OR of the eight slabs; the slabs are left all zero.
+__global__ void __launch_bounds__(kBlock) fold_slabs_kernel(const TrackBatch b) {
+    const TrackJob &t = b.job[wg_y()];
+    uint32_t *__restrict__ slabs = reinterpret_cast<uint32_t *>(t.flags);
+    uint32_t *__restrict__ bitmap = t.bitmap;
+    const uint64_t n_words = (t.n_rows + 31u) / 32u;
+    const uint64_t stride = (uint64_t)b.grid_x * kBlock;
+    for (uint64_t i = (uint64_t)wg_x() * kBlock + tid_x(); i < n_words; i += stride) {
+        uint32_t acc = 0;
+#pragma unroll
+        for (uint32_t s = 0; s < kStreamParts; ++s) {
+            acc |= slabs[s * n_words + i];
+            slabs[s * n_words + i] = 0u;
+        }
+        if (acc) bitmap[i] |= acc;
+    }
+}
+
 // Eight flag bytes (each 0 or 1) to eight bits, first byte in bit 0.
 __device__ __forceinline__ uint32_t flags_to_bits(uint64_t eight) {
     return (uint32_t)((eight * 0x0102040810204080ull) >> 56);
@@ -335,24 +438,48 @@ cnr_status cnr_mark_touched_batch(cnr_ctx *ctx, const cnr_table_job *jobs, uint3
     }
     hipStream_t s = as_stream(stream);
     for (uint32_t first = 0; first < n_jobs; first += CNR_MAX_BATCH) {
-        // The flag-byte route pays a pass over n_rows bytes; below this stream length the atomics
-        // are cheaper (about 16 G atomics/s against about 5 TB/s for the fold).
-        TrackBatch bulk = {}, direct = {};
-        uint32_t n_bulk = 0, n_direct = 0;
-        uint64_t bulk_idx = 0, bulk_words = 0, direct_idx = 0;
+        // Three routes.  Short streams: atomic ORs on the bitmap (about 16 G atomics/s; the other two
+        // pay a pass over n_rows bytes).  Long streams into tables of at most kSliceTeamMax slices:
+        // bitmap slices in LDS (every look-up is read by as many workgroups as the table has slices,
+        // which beats the flag bytes' one 32-byte memory write per look-up up to there).  Long
+        // streams into larger tables: one flag byte per row, then a fold.
+        constexpr uint64_t kSliceTeamMax = 16;
+        TrackBatch slices = {}, bulk = {}, direct = {};
+        uint32_t n_slices = 0, n_bulk = 0, n_direct = 0;
+        uint64_t slices_words = 0, slices_team = 0, bulk_idx = 0, bulk_words = 0, direct_idx = 0;
         for (uint32_t i = first; i < n_jobs && i < first + CNR_MAX_BATCH; ++i) {
             const cnr_table_job &j = jobs[i];
             if (j.n_indices == 0) continue;
-            const bool use_flags = j.mark_scratch && j.n_rows && j.n_indices > j.n_rows / 256 + 65536;
-            TrackJob &t = use_flags ? bulk.job[n_bulk++] : direct.job[n_direct++];
+            const bool long_stream = j.mark_scratch && j.n_rows && j.n_indices > j.n_rows / 256 + 65536;
+            const uint64_t team = (j.n_rows + kSliceRows - 1) / kSliceRows;
+            const bool use_slices = long_stream && team <= kSliceTeamMax;
+            TrackJob &t = use_slices ? slices.job[n_slices++] : long_stream ? bulk.job[n_bulk++] : direct.job[n_direct++];
             t.bitmap = j.bitmap;
             t.n_rows = j.n_rows;
             t.idx = j.indices;
             t.n_idx = j.n_indices;
             t.flags = (uint8_t *)j.mark_scratch;
-            uint64_t &most = use_flags ? bulk_idx : direct_idx;
-            if (j.n_indices > most) most = j.n_indices;
-            if (use_flags && cnr_bitmap_words(j.n_rows) > bulk_words) bulk_words = cnr_bitmap_words(j.n_rows);
+            const uint64_t words = cnr_bitmap_words(j.n_rows);
+            if (use_slices) {
+                if (team > slices_team) slices_team = team;
+                if (words > slices_words) slices_words = words;
+            } else if (long_stream) {
+                if (j.n_indices > bulk_idx) bulk_idx = j.n_indices;
+                if (words > bulk_words) bulk_words = words;
+            } else if (j.n_indices > direct_idx) {
+                direct_idx = j.n_indices;
+            }
+        }
+        if (n_slices) {
+            const dim3 grid((unsigned)(kStreamParts * slices_team), n_slices);
+            if (type == CNR_IDX_I64)
+                hipLaunchKernelGGL(mark_slices_kernel<int64_t>, grid, dim3(kSliceThreads), 0, s, slices, ctx->dev_err);
+            else
+                hipLaunchKernelGGL(mark_slices_kernel<int32_t>, grid, dim3(kSliceThreads), 0, s, slices, ctx->dev_err);
+            if ((st = cnr_launch_status(ctx)) != CNR_OK) return st;
+            slices.grid_x = batch_grid_x(ctx, slices_words, kBlock, 8, n_slices);
+            hipLaunchKernelGGL(fold_slabs_kernel, dim3(slices.grid_x, n_slices), dim3(kBlock), 0, s, slices);
+            if ((st = cnr_launch_status(ctx)) != CNR_OK) return st;
         }
         if (n_bulk) {
             bulk.grid_x = batch_grid_x(ctx, bulk_idx, (uint64_t)kBlock * 4, 8, n_bulk);

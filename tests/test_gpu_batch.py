@@ -111,6 +111,39 @@ def test_batched_checkpoint_equals_oracle_and_single_calls(ctx, bits, dim):
     _poll_clean(ctx)
 
 
+@pytest.mark.parametrize("dtype", [torch.int64, torch.int32])
+def test_batched_mark_takes_each_table_by_its_own_route(ctx, dtype):
+    # one batch whose tables need all three routes of the mark: bitmap slices in LDS with teams of one,
+    # two and three workgroups, flag bytes for a table too large for that, atomics for short streams
+    slice_rows = 32 * 40960
+    sizes = [3 * slice_rows - 5, 100, 16 * slice_rows + 77, slice_rows + 1, 40_000, slice_rows]
+    n_idx = [400_001, 50, 500_003, 300_000, 100, 0]
+    print("case mixed-route mark dtype=%s" % dtype, flush=True)
+    g = torch.Generator(device=DEV).manual_seed(77)
+    cks = [P.TableCheckpointer(ctx, n, 16, device=DEV, mark_scratch=P.TableCheckpointer.new_mark_scratch(n, DEV))
+           for n in sizes]
+    batch = P.BatchCheckpointer(ctx, cks)
+    idx = [None if m == 0 else torch.randint(-1, n + 1, (m,), generator=g, device=DEV).to(dtype)
+           for n, m in zip(sizes, n_idx)]
+    batch.clear()
+    batch.mark(idx)
+    batch.mark(idx)                                            # marks accumulate; the same streams again
+    batch.compact()
+    torch.cuda.synchronize()
+    skipped = 0
+    for i, n_rows in enumerate(sizes):
+        bm = O.new_bitmap(n_rows)
+        if idx[i] is not None:
+            skipped += 2 * O.mark_touched(bm, n_rows, idx[i].cpu().numpy())
+        ids, n = O.compact_dirty(bm, n_rows)
+        assert np.array_equal(u32(cks[i].bitmap)[:bm.size], bm), "table %d bitmap" % i
+        assert int(cks[i].n_dirty.item()) == n and np.array_equal(u32(cks[i].row_ids)[:n], ids)
+        assert not cks[i].mark_scratch.any()
+    st, bad, flags = P.cnr_poll_errors(ctx)
+    assert st == P.CNR_E_INDEX_RANGE and bad == skipped and skipped > 0 and flags == 0
+    _poll_clean(ctx)
+
+
 @pytest.mark.parametrize("bits,dim", [(4, 64), (2, 128), (3, 256)])
 def test_batched_greedy(ctx, bits, dim):
     sizes = [3_001, 700, 64]

@@ -60,19 +60,28 @@ def test_mark_and_compact_bit_exact(ctx, n_rows, dtype):
     _poll_clean(ctx)
 
 
-@pytest.mark.parametrize("n_rows", [1, 33, 1000, 16385, 100_000, 1_000_003, 5_000_000])
+# rows per LDS bitmap slice of the bulk mark, and the table size beyond which it uses flag bytes instead
+SLICE_ROWS = 32 * 40960
+FLAG_ROUTE_ROWS = 16 * SLICE_ROWS + 1
+
+
+@pytest.mark.parametrize("n_rows", [1, 33, 1000, 16385, 100_000, 1_000_003, SLICE_ROWS - 1, SLICE_ROWS, SLICE_ROWS + 1,
+                                    2 * SLICE_ROWS + 33, 5_000_000, FLAG_ROUTE_ROWS])
 @pytest.mark.parametrize("dtype", [torch.int64, torch.int32])
-def test_bulk_mark_through_flag_bytes(ctx, n_rows, dtype):
-    # long streams with a scratch buffer take the flag-byte route; the bitmap must be the same, the
-    # scratch must come back zeroed, and marks must accumulate over calls and over both routes
+def test_bulk_mark_through_scratch(ctx, n_rows, dtype):
+    # long streams with a scratch buffer take a bulk route (bitmap slices in LDS, or flag bytes for the
+    # largest table here); the bitmap must be the same, the scratch must come back zeroed, and marks
+    # must accumulate over calls and over the routes
     print("case bulk n_rows=%d dtype=%s" % (n_rows, dtype), flush=True)
     g = torch.Generator(device=DEV).manual_seed(n_rows + 1)
     scratch = P.TableCheckpointer.new_mark_scratch(n_rows, DEV)
     ck = P.TableCheckpointer(ctx, n_rows, 64, device=DEV, mark_scratch=scratch)
     ck.clear()
     batches = []
-    for n_idx in (300_000, 1000, 150_000):                     # bulk, atomic, bulk
+    for n_idx in (300_000 + n_rows // 256, 1000, 150_001 + n_rows // 256):   # bulk, atomic, bulk
         idx = torch.randint(-2, n_rows + 2, (n_idx,), generator=g, device=DEV).to(dtype)
+        idx[-1] = n_rows - 1                                   # the last row, at the very end of a stream
+        idx[0], idx[1] = -1, n_rows                            # and two that are outside for certain
         batches.append(idx)
         ck.mark(idx)
     ck.compact()
@@ -83,6 +92,33 @@ def test_bulk_mark_through_flag_bytes(ctx, n_rows, dtype):
     assert not scratch.any()
     st, bad, flags = P.cnr_poll_errors(ctx)
     assert st == P.CNR_E_INDEX_RANGE and bad == skipped and flags == 0
+    _poll_clean(ctx)
+
+
+@pytest.mark.parametrize("dtype", [torch.int64, torch.int32])
+@pytest.mark.parametrize("offset,length", [(1, 200_001), (2, 200_002), (3, 199_999), (0, 200_003), (1, 70_000)])
+def test_bulk_mark_any_stream_alignment_and_length(ctx, dtype, offset, length):
+    # the index stream may start at any naturally aligned address and have any length: the elements
+    # before the first and after the last whole 16-byte unit are marked as well
+    n_rows = 3_000_017
+    print("case bulk alignment dtype=%s offset=%d length=%d" % (dtype, offset, length), flush=True)
+    g = torch.Generator(device=DEV).manual_seed(offset * 7 + length)
+    scratch = P.TableCheckpointer.new_mark_scratch(n_rows, DEV)
+    ck = P.TableCheckpointer(ctx, n_rows, 64, device=DEV, mark_scratch=scratch)
+    ck.clear()
+    base = torch.randint(0, n_rows, (offset + length + 5,), generator=g, device=DEV).to(dtype)
+    idx = base[offset:offset + length]
+    idx[0] = 0
+    idx[-1] = n_rows - 1
+    assert idx.data_ptr() == base.data_ptr() + offset * base.element_size()
+    ck.mark(idx)
+    ck.compact()
+    torch.cuda.synchronize()
+    bm, ids, n, skipped = _oracle_track(n_rows, [idx.cpu().numpy()])
+    assert skipped == 0
+    assert np.array_equal(u32(ck.bitmap)[:bm.size], bm)
+    assert int(ck.n_dirty.item()) == n and np.array_equal(u32(ck.row_ids)[:n], ids)
+    assert not scratch.any()
     _poll_clean(ctx)
 
 
