@@ -252,10 +252,10 @@ __global__ void __launch_bounds__(kBlock) fold_flags_kernel(const TrackBatch b) 
 //   count:   population count of the tile -> block_count[b]
 //   scatter: base = sum of block_count[0..b) (read back by every workgroup; at most a few thousand
 //            values), exclusive scan of the per-thread counts inside the workgroup (wave shuffles +
-//            one LDS step across the four waves), then every wave walks its 64 words: the word
-//            itself is the ballot of "row is dirty" for 64 consecutive rows, a lane's rank is the
-//            population count of the word below its own bit, so the 64 lanes write a contiguous,
-//            ascending run of ids.
+//            one LDS step across the four waves), then every lane walks the set bits of its own
+//            word and writes their row numbers, as 16-bit offsets from the tile's first row, to its
+//            place in an LDS copy of the tile's part of the list, which the workgroup then stores
+//            to the list with every lane writing consecutive ids.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint64_t load_tile_word(const uint32_t *__restrict__ bitmap,
                                                    uint64_t n_rows, uint64_t n_words32, uint64_t w64) {
@@ -305,6 +305,7 @@ __global__ void __launch_bounds__(kBlock) compact_count_kernel(const TrackBatch 
 __global__ void __launch_bounds__(kBlock) compact_scatter_kernel(const TrackBatch b, cnr_dev_errors *err) {
     __shared__ unsigned lds[kWavesPerBlock];
     __shared__ unsigned wave_total[kWavesPerBlock];
+    __shared__ uint16_t tile_ids[kCompactRowsPerBlock];
     const TrackJob &t = b.job[wg_y()];
     const uint64_t n_rows = t.n_rows, n_words32 = (n_rows + 31u) / 32u, capacity = t.capacity;
     const uint64_t tiles = compact_tiles(n_rows);
@@ -349,18 +350,23 @@ __global__ void __launch_bounds__(kBlock) compact_scatter_kernel(const TrackBatc
         if (total > capacity) raise_flag(err, CNR_FLAG_CAPACITY);
     }
 
-    const uint32_t lo32 = (uint32_t)word, hi32 = (uint32_t)(word >> 32);
-    const uint64_t wave_row0 = ((uint64_t)wg_x() * kBlock + (uint64_t)wave * kWave) * 64u;
-    const uint64_t below_me = lane ? ((~0ull) >> (64 - lane)) : 0ull;
-    for (int i = 0; i < kWave; ++i) {
-        const uint64_t wi = (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)lo32, i) |
-                            ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)hi32, i) << 32);
-        if (wi == 0) continue;  // uniform over the wave
-        const unsigned off_i = (unsigned)__builtin_amdgcn_readlane((int)excl, i);
-        if ((wi >> lane) & 1ull) {
-            const uint64_t pos = base + off_i + (unsigned)__popcll(wi & below_me);
-            if (pos < capacity) row_ids[pos] = (uint32_t)(wave_row0 + (uint64_t)i * 64u + (uint64_t)lane);
+    // ids of the tile in ascending order, as 16-bit offsets from its first row, into LDS: every lane
+    // walks the set bits of its own word ...
+    {
+        uint64_t rest = word;
+        unsigned k = excl;
+        const uint32_t off0 = tid_x() * 64u;
+        while (rest) {
+            tile_ids[k++] = (uint16_t)(off0 + (uint32_t)__builtin_ctzll(rest));
+            rest &= rest - 1;
         }
+    }
+    __syncthreads();
+    // ... and from there to the list, every lane storing
+    const uint64_t tile_row0 = (uint64_t)wg_x() * kCompactRowsPerBlock;
+    for (unsigned p = tid_x(); p < block_total; p += kBlock) {
+        const uint64_t pos = base + p;
+        if (pos < capacity) row_ids[pos] = (uint32_t)(tile_row0 + tile_ids[p]);
     }
 }
 
