@@ -126,7 +126,7 @@ def main() -> int:
     # ---- resident inputs ------------------------------------------------------------------------
     tables, streams, cks, encs = [], [], [], []
     batched = not args.per_table
-    # per-table calls run one after the other and can share the flag-byte scratch of the bulk mark
+    # per-table calls run one after the other and can share the scratch of the bulk mark
     # and the stale table that restore writes into; batched calls work on all tables at once
     shared_scratch = None if batched else P.TableCheckpointer.new_mark_scratch(w.n_rows, dev)
     for ti in range(n_tables):

@@ -44,7 +44,7 @@ class TableCheckpointer:
         self.scratch = torch.empty((B.cnr_scratch_bytes(n_rows) + 7) // 8, dtype=torch.int64, device=dev)
         self.row_ids = torch.empty(max(1, self.capacity), dtype=torch.int32, device=dev)
         self.n_dirty = torch.zeros(1, dtype=torch.int64, device=dev)
-        # zero-filled flag bytes for marking long index streams; may be shared between the tables of
+        # zero-filled scratch for marking long index streams; may be shared between the tables of
         # one stream (pass the same tensor), the library leaves it zeroed after every call
         self.mark_scratch = mark_scratch
         if mark_scratch is not None and mark_scratch.numel() * mark_scratch.element_size() < B.cnr_mark_scratch_bytes(n_rows):

@@ -6,6 +6,8 @@
 // entry points are batches of one.
 #include "cnr_common.h"
 
+#include <type_traits>
+
 namespace {
 
 struct TrackJob {
@@ -150,18 +152,6 @@ __global__ void __launch_bounds__(kSliceThreads) mark_slices_kernel(const TrackB
     for (uint32_t i = tid; i < kSliceWords; i += kSliceThreads) bits[i] = 0u;
     __syncthreads();
 
-    unsigned bad = 0;
-    auto look_up = [&](IdxT v) {
-        // a row id is valid iff it is below n_rows < 2^32: upper half zero (int64), not negative
-        bool valid;
-        if constexpr (sizeof(IdxT) == 8) valid = ((uint64_t)v >> 32) == 0 && (uint32_t)v < n_rows;
-        else valid = (uint32_t)v < n_rows;
-        const uint32_t d = (uint32_t)v - lo;
-        if (valid && d < span)
-            __hip_atomic_fetch_or(&bits[d >> 5], 1u << (d & 31u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        if (w == 0 && !valid) ++bad;
-    };
-
     // the stream as [head][16-byte vectors][tail]: head and tail are fewer than kVec elements each
     const IdxT *idx = static_cast<const IdxT *>(t.idx);
     const uint64_t n = t.n_idx;
@@ -173,26 +163,48 @@ __global__ void __launch_bounds__(kSliceThreads) mark_slices_kernel(const TrackB
     const uint64_t per_part = (n_vec + kStreamParts - 1u) / kStreamParts;
     const uint64_t v0 = part * per_part;
     const uint64_t v1 = v0 + per_part < n_vec ? v0 + per_part : n_vec;
-    for (uint64_t p = v0 + tid; p < v1; p += (uint64_t)kSliceThreads * kUnroll) {
-        vec_t v[kUnroll];
+
+    unsigned bad = 0;
+    // COUNT: also count the indices outside the table (the team's first workgroup does, for its part
+    // of the stream).  A look-up inside this slice is inside the table, so the bit needs no more
+    // than the slice test.
+    auto run = [&](auto count_tag) {
+        constexpr bool COUNT = decltype(count_tag)::value;
+        auto look_up = [&](IdxT v) {
+            const uint32_t d = (uint32_t)v - lo;
+            bool mine = d < span;
+            if constexpr (sizeof(IdxT) == 8) mine = mine && ((uint64_t)v >> 32) == 0;
+            if (mine)
+                __hip_atomic_fetch_or(&bits[d >> 5], 1u << (d & 31u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if constexpr (COUNT) {
+                bool valid = (uint32_t)v < n_rows;
+                if constexpr (sizeof(IdxT) == 8) valid = valid && ((uint64_t)v >> 32) == 0;
+                bad += valid ? 0u : 1u;
+            }
+        };
+        for (uint64_t p = v0 + tid; p < v1; p += (uint64_t)kSliceThreads * kUnroll) {
+            vec_t v[kUnroll];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const uint64_t q = p + (uint64_t)u * kSliceThreads;
-            if (q < v1) v[u] = vecs[q];
-        }
+            for (int u = 0; u < kUnroll; ++u) {
+                const uint64_t q = p + (uint64_t)u * kSliceThreads;
+                if (q < v1) v[u] = vecs[q];
+            }
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const uint64_t q = p + (uint64_t)u * kSliceThreads;
-            if (q < v1) {
+            for (int u = 0; u < kUnroll; ++u) {
+                const uint64_t q = p + (uint64_t)u * kSliceThreads;
+                if (q < v1) {
 #pragma unroll
-                for (int e = 0; e < kVec; ++e) look_up(v[u][e]);
+                    for (int e = 0; e < kVec; ++e) look_up(v[u][e]);
+                }
             }
         }
-    }
-    if (part == 0) {
-        if (tid < head) look_up(idx[tid]);
-        else if (tid - head < n - tail) look_up(idx[tail + (tid - head)]);
-    }
+        if (part == 0) {
+            if (tid < head) look_up(idx[tid]);
+            else if (tid - head < n - tail) look_up(idx[tail + (tid - head)]);
+        }
+    };
+    if (w == 0) run(std::true_type{});
+    else run(std::false_type{});
     for (int off = 32; off > 0; off >>= 1) bad += __shfl_xor(bad, off);
     if (bad && (tid & (kWave - 1)) == 0) atomicAdd(&err->n_bad_indices, (unsigned long long)bad);
     __syncthreads();
