@@ -78,7 +78,7 @@ __global__ void __launch_bounds__(kBlock) mark_kernel(const TrackBatch b, cnr_de
 }
 
 // ---------------------------------------------------------------------------------------------
-// mark, bulk variant: no atomics.
+// mark, bulk variants: no device-scope atomics.  The first, for tables too large for the second.
 //
 // On this GPU the L2 caches of the eight XCDs are not coherent with each other, so a device-scope
 // atomic OR is carried out at the memory side: each one costs a 64-byte read and a 32-byte write
@@ -120,7 +120,8 @@ __global__ void __launch_bounds__(kBlock) mark_flags_kernel(const TrackBatch b, 
     if (bad && (tid_x() & (kWave - 1)) == 0) atomicAdd(&err->n_bad_indices, (unsigned long long)bad);
 }
 
-// Bulk route for tables of up to a few tens of millions of rows: bitmap slices held in LDS.
+// ---------------------------------------------------------------------------------------------
+// mark, second bulk variant, for tables of up to a few tens of millions of rows: bitmap slices in LDS.
 //
 // A workgroup owns kSliceRows consecutive rows of one table as a bitmap in LDS (all 160 KB of a
 // compute unit) and one eighth of the table's index stream: it reads its share of the stream, sets
@@ -130,6 +131,7 @@ __global__ void __launch_bounds__(kBlock) mark_flags_kernel(const TrackBatch b, 
 // price is that the W = ceil(n_rows / kSliceRows) workgroups of a team read the same eighth of the
 // stream.  Workgroups are dealt to the eight XCDs in turn along x, so x & 7 names both the eighth
 // and the XCD: a team shares its part of the stream through one L2 and memory is read once.
+// ---------------------------------------------------------------------------------------------
 constexpr int kSliceThreads = 1024;
 constexpr uint32_t kSliceWords = 40960;
 constexpr uint64_t kSliceRows = 32ull * kSliceWords;
