@@ -41,7 +41,7 @@ ISSUE_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # one vector instruction per lane
 # per dirty row, valid only for the kernel source whose hash is recorded with it.
 TRAFFIC_PER_ROW = {
     # _kernel_hash() : (workload, bytes per dirty row)
-    # (2.000 * 190489.1 KiB FETCH_SIZE + 1.000 * 60151.7 KiB WRITE_SIZE) / 1,500,122 rows per launch
+    # (2.000 * 190489.1 KiB FETCH_SIZE + 1.000 * 60150.6 KiB WRITE_SIZE) / 1,500,122 rows per launch
     "cf1533b45736d648e449e29e5ff9121d469d6f622fddea6f909bf84222b69cb5": ("cfg4/b4", 301.12),
 }
 
