@@ -364,6 +364,13 @@ cnr_status cnr_policy_init(cnr_policy *p /* host */, cnr_policy_kind kind);
  * policy takes a full checkpoint. */
 cnr_policy_decision cnr_policy_next(cnr_policy *p /* host */, double dirty_fraction);
 
+/* Dynamic bit-width selection (Section 6.2.1): the narrowest code width that keeps the accuracy
+ * loss under the paper's threshold for the number of times the job is expected to resume from a
+ * quantized checkpoint: 2 bits for at most one resume, 3 bits for at most 3, 4 bits for at most
+ * 20, 8 bits beyond that; and 8 bits from the moment the resumes seen so far exceed the
+ * expectation.  Host only.  Returns 2, 3, 4 or 8 (a value cnr_quantize_rows takes as `bits`). */
+int cnr_select_bits(uint32_t expected_resumes, uint32_t observed_resumes);
+
 #ifdef __cplusplus
 }
 #endif

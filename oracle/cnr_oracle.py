@@ -236,3 +236,16 @@ def full_checkpoint_due(sizes) -> bool:
     s = _c(np.asarray(sizes, dtype=np.float64), np.float64).reshape(-1)
     return bool(_load().cnro_full_checkpoint_due(_ptr(s), s.size))
 
+
+
+def select_bits(expected_resumes: int, observed_resumes: int = 0) -> int:
+    """Dynamic bit-width selection (Section 6.2.1): how often a job may resume from a checkpoint of
+    each width before the accuracy loss passes the threshold, narrowest sufficient width first;
+    8 bits once more resumes have happened than were expected."""
+    resumes_tolerated = ((2, 1), (3, 3), (4, 20))
+    if observed_resumes > expected_resumes:
+        return 8
+    for bits, tolerated in resumes_tolerated:
+        if expected_resumes <= tolerated:
+            return bits
+    return 8

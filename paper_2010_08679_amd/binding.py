@@ -32,7 +32,7 @@ EXPORTS = (
     "cnr_mark_scratch_bytes",
     "cnr_greedy_iterations", "cnr_clear_bitmap", "cnr_mark_touched", "cnr_compact_dirty",
     "cnr_quantize_rows", "cnr_pack", "cnr_restore_rows", "cnr_quant_error", "cnr_poll_errors", "cnr_status_str",
-    "cnr_last_hip_error", "cnr_full_checkpoint_due", "cnr_policy_init", "cnr_policy_next",
+    "cnr_last_hip_error", "cnr_full_checkpoint_due", "cnr_policy_init", "cnr_policy_next", "cnr_select_bits",
     "cnr_clear_bitmap_batch", "cnr_mark_touched_batch", "cnr_compact_dirty_batch", "cnr_quantize_rows_batch",
     "cnr_restore_rows_batch",
     "cnr_host_writer_device_bytes", "cnr_host_writer_create", "cnr_host_writer_destroy", "cnr_encode_to_host",
@@ -111,6 +111,7 @@ def load() -> ctypes.CDLL:
             "cnr_full_checkpoint_due": (i32, [ctypes.POINTER(ctypes.c_double), u32]),
             "cnr_policy_init": (i32, [ctypes.POINTER(cnr_policy), i32]),
             "cnr_policy_next": (cnr_policy_decision, [ctypes.POINTER(cnr_policy), ctypes.c_double]),
+            "cnr_select_bits": (i32, [u32, u32]),
             "cnr_clear_bitmap_batch": (i32, [vp, ctypes.POINTER(cnr_table_job), u32, vp]),
             "cnr_mark_touched_batch": (i32, [vp, ctypes.POINTER(cnr_table_job), u32, i32, vp]),
             "cnr_compact_dirty_batch": (i32, [vp, ctypes.POINTER(cnr_table_job), u32, vp]),
@@ -470,6 +471,10 @@ def cnr_last_hip_error(ctx) -> int:
 def cnr_full_checkpoint_due(sizes) -> bool:
     arr = (ctypes.c_double * len(sizes))(*[float(s) for s in sizes])
     return bool(load().cnr_full_checkpoint_due(arr, len(sizes)))
+
+
+def cnr_select_bits(expected_resumes: int, observed_resumes: int = 0) -> int:
+    return int(load().cnr_select_bits(int(expected_resumes), int(observed_resumes)))
 
 
 def cnr_policy_init(kind: int) -> cnr_policy:

@@ -171,4 +171,12 @@ cnr_policy_decision cnr_policy_next(cnr_policy *p, double dirty_fraction) {
     }
 }
 
+int cnr_select_bits(uint32_t expected_resumes, uint32_t observed_resumes) {
+    if (observed_resumes > expected_resumes) return 8;
+    if (expected_resumes <= 1) return 2;
+    if (expected_resumes <= 3) return 3;
+    if (expected_resumes <= 20) return 4;
+    return 8;
+}
+
 }  // extern "C"

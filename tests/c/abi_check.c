@@ -18,7 +18,7 @@ int main(void) {
         (fn)cnr_compact_dirty_batch, (fn)cnr_quantize_rows_batch, (fn)cnr_restore_rows_batch,
         (fn)cnr_host_writer_device_bytes, (fn)cnr_host_writer_create, (fn)cnr_host_writer_destroy,
         (fn)cnr_encode_to_host, (fn)cnr_host_writer_wait, (fn)cnr_select_scratch_bytes,
-        (fn)cnr_select_greedy_params};
+        (fn)cnr_select_greedy_params, (fn)cnr_select_bits};
     size_t i, n_exports = sizeof(exports) / sizeof(exports[0]);
     for (i = 0; i < n_exports; ++i)
         if (!exports[i]) return 10;
@@ -43,6 +43,9 @@ int main(void) {
         if (cnr_policy_init(&p, (cnr_policy_kind)7) != CNR_E_INVALID) return 17;
     }
     if (strcmp(cnr_status_str(CNR_OK), "ok") != 0) return 18;
+    if (cnr_select_bits(1, 0) != 2 || cnr_select_bits(3, 3) != 3 || cnr_select_bits(20, 0) != 4 ||
+        cnr_select_bits(21, 0) != 8 || cnr_select_bits(1, 2) != 8)
+        return 19;
     if (cnr_select_scratch_bytes(100, 64, 4) != 400u + 400u + 3200u + 800u + 16u) return 27;
     if (cnr_host_writer_device_bytes(64, 4, 1024) != 2u * 1024u * 40u || cnr_host_writer_device_bytes(12, 3, 16) != 0) return 26;
     {

@@ -128,3 +128,9 @@ def test_header_is_plain_c_and_every_export_links(tmp_path):
     assert out.returncode == 0, (out.returncode, out.stdout, out.stderr)
     n = int(out.stdout.split(":")[1].split()[0])
     assert n == len(binding.EXPORTS)
+
+
+def test_bit_width_selection_equals_the_oracle():
+    for expected in list(range(0, 30)) + [99, 100, 101, 10_000]:
+        for observed in (0, 1, expected, expected + 1):
+            assert P.cnr_select_bits(expected, observed) == O.select_bits(expected, observed)

@@ -513,3 +513,23 @@ def test_selection_never_worse_than_naive_and_sample_agrees_with_full():
     assert abs(bins.index(small[0]) - bins.index(full[0])) <= 1
     gain = lambda nb: 1.0 - rep_full[("bins", nb)] / rep_full["naive"]  # noqa: E731
     assert gain(small[0]) >= 0.9 * max(gain(nb) for nb in bins)
+
+
+# ------------------------------------------------------------------ dynamic bit-width selection (Section 6.2.1)
+
+def test_bit_width_follows_the_resume_counts_the_paper_reports():
+    # Section 6.2.1: a 2-bit checkpoint survives one resume but not two, 3 bits up to 3 resumes,
+    # 4 bits up to 20, 8 bits more than 100; the narrowest width that survives is taken
+    assert [O.select_bits(e) for e in (0, 1)] == [2, 2]
+    assert [O.select_bits(e) for e in (2, 3)] == [3, 3]
+    assert [O.select_bits(e) for e in (4, 10, 20)] == [4, 4, 4]
+    assert [O.select_bits(e) for e in (21, 100, 1000)] == [8, 8, 8]
+    widths = [O.select_bits(e) for e in range(0, 200)]
+    assert widths == sorted(widths) and set(widths) == {2, 3, 4, 8}
+
+
+def test_bit_width_falls_back_to_eight_bits_when_failures_exceed_the_estimate():
+    assert O.select_bits(1, 1) == 2 and O.select_bits(1, 2) == 8
+    assert O.select_bits(3, 3) == 3 and O.select_bits(3, 4) == 8
+    assert O.select_bits(20, 20) == 4 and O.select_bits(20, 21) == 8
+    assert O.select_bits(50, 51) == 8
