@@ -23,6 +23,7 @@
  *   cnr_host_writer_*, cnr_encode_to_host   chunked encode into host memory with the copy of one
  *                      chunk overlapping the encode of the next (Sections 4.4, 5.2)
  *   cnr_policy_*       the incremental-checkpoint policies (Section 5.1), host only
+ *   cnr_select_bits    the code width for an expected number of resumes (Section 6.2.1), host only
  *
  * General rules
  *   - Every pointer argument is a DEVICE pointer owned by the caller unless its comment says
