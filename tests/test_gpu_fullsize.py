@@ -1,6 +1,6 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch configurations the
 benchmark times: one prepared batched call per stage over all tables (its default), and prepared
-per-table calls with a shared flag-byte scratch for marking; device-side row counts in both.
+per-table calls with a shared scratch for marking; device-side row counts in both.
 The tracking bitmap and the dirty-row list are compared in full; the encoded rows on a sample the
 oracle can quantize row by row (every position of the first and last wave batches plus a random
 draw); restored tables on the same sample plus rows that must stay untouched."""
@@ -178,5 +178,64 @@ def test_cfg4_all_tables_through_the_batched_calls(ctx):
         assert np.array_equal(back, O.dequantize(got["codes"], got["scale"], got["bias"])), what + " restore"
         untouched = np.setdiff1d(np.arange(0, w.n_rows, 100), ids)
         assert torch.all(stale[ti].index_select(0, torch.from_numpy(untouched).to(DEV)) == -3.0)
+    st, bad, flags = P.cnr_poll_errors(ctx)
+    assert (st, bad, flags) == (P.CNR_OK, 0, 0)
+
+
+@pytest.mark.parametrize("with_ids", [False, True])
+def test_host_counted_lists_are_encoded_and_restored_in_slices(ctx, with_ids):
+    # A list whose length the host passes (no count on the device) is cut into several launches; with no
+    # id list either, that is a full checkpoint of the table.  The result must be, bit for bit, what the
+    # single launch over a device-side count gives, and the oracle's on a sample that includes the rows
+    # on either side of every cut.
+    n_rows, dim, bits = 4_000_037, 64, 4
+    print("case sliced launches with_ids=%s" % with_ids, flush=True)
+    table = synth.table_outlier_mix(n_rows, dim, 0.02, 9, DEV)
+    if with_ids:
+        g = torch.Generator(device=DEV).manual_seed(3)
+        ids = torch.nonzero(torch.rand(n_rows, generator=g, device=DEV) < 0.85).reshape(-1).to(torch.int32)
+        n = ids.numel()
+    else:
+        ids, n = None, n_rows
+    target = ((512 << 20) // (4 * dim)) & ~1023
+    assert n > target + target // 2                            # long enough to be cut
+    n_slices = -(-n // target)
+    step = (-(-n // n_slices) + 1023) & ~1023
+    prb = P.cnr_packed_row_bytes(dim, bits)
+    n_dev = torch.tensor([n], dtype=torch.int64, device=DEV)
+
+    def outputs():
+        f = lambda: torch.full((n,), -1.0, dtype=torch.float32, device=DEV)  # noqa: E731
+        return dict(scale=f(), bias=f(), row_min=f(), row_max=f(),
+                    packed=torch.zeros(n * prb, dtype=torch.uint8, device=DEV))
+    cut, one = outputs(), outputs()
+    for o, count in ((cut, None), (one, n_dev)):
+        P.cnr_quantize_rows(ctx, table, n_rows, dim, ids, count, n, bits, P.CNR_RANGE_MINMAX, None,
+                            o["scale"], o["bias"], o["row_min"], o["row_max"], None, o["packed"], None)
+    torch.cuda.synchronize()
+    for k in cut:
+        assert torch.equal(cut[k], one[k]), k
+
+    edges = np.concatenate([np.arange(c - 3, c + 3) for c in range(step, n, step)])
+    pos = np.unique(np.concatenate([_sample_positions(n, 20_000, 5), edges])).astype(np.int64)
+    p = torch.from_numpy(pos).to(DEV)
+    row_of = p if ids is None else ids.index_select(0, p).to(torch.int64)
+    rows = table.index_select(0, row_of).cpu().numpy()
+    packed = cut["packed"].reshape(-1, prb).index_select(0, p).cpu().numpy()
+    got = dict(packed=packed, codes=O.unpack(packed, dim, bits),
+               **{k: cut[k].index_select(0, p).cpu().numpy() for k in ("scale", "bias", "row_min", "row_max")})
+    compare_quantized(rows, got, O.quantize_rows(rows, None, bits, n_threads=8), bits, what="sliced encode")
+
+    stale_cut, stale_one = torch.full_like(table, -3.0), torch.full_like(table, -3.0)
+    for st, count in ((stale_cut, None), (stale_one, n_dev)):
+        P.cnr_restore_rows(ctx, st, n_rows, dim, ids, count, n, bits, cut["packed"], cut["scale"], cut["bias"], None)
+    torch.cuda.synchronize()
+    assert torch.equal(stale_cut, stale_one)
+    back = stale_cut.index_select(0, row_of).cpu().numpy()
+    assert np.array_equal(back, O.dequantize(got["codes"], got["scale"], got["bias"]))
+    if ids is not None:
+        written = torch.zeros(n_rows, dtype=torch.bool, device=DEV)
+        written[ids.to(torch.int64)] = True
+        assert torch.all(stale_cut[~written] == -3.0)
     st, bad, flags = P.cnr_poll_errors(ctx)
     assert (st, bad, flags) == (P.CNR_OK, 0, 0)
