@@ -56,6 +56,20 @@ def _kernel_hash() -> str:
     return hashlib.sha256("".join(code.split()).encode()).hexdigest()
 
 
+# The same for the restore kernel: (2.000 * 32252.1 KiB + 1.000 * 375031.8 KiB) / 1,500,122 rows
+RESTORE_TRAFFIC_PER_ROW = {
+    "479411b26295069cf03d8771324a42c79b5698ffb5c54cce55d08b61bdbc6654": ("cfg4/b4", 300.03),
+}
+
+
+def _restore_kernel_hash() -> str:
+    """Hash of the restore kernels' source file, without comments and white space."""
+    with open(os.path.join(ROOT, "paper_2010_08679_amd", "csrc", "cnr_restore.hip"), "r") as f:
+        text = f.read()
+    code = "".join(line.split("//")[0] for line in text.splitlines(True))
+    return hashlib.sha256("".join(code.split()).encode()).hexdigest()
+
+
 def encode_bytes_per_row(dim: int, bits: int) -> int:
     """Algorithmic bytes of the fused encode per dirty row: row id + gathered row + packed codes +
     scale and bias."""
@@ -222,6 +236,17 @@ def main() -> int:
                 "launches_per_event_span": launches_per_span, "empty_event_pair_ms": round(null_ms, 5)}
     res_ms = stage_timer.totals_ms()["restore"] / (stage_timer.counts()["restore"] * launches_per_span)
     res_bytes = restore_bytes_per_row(w.dim, bits) * rows_per_launch
+    res_achieved = res_bytes / (res_ms * 1e-3) / 1e9
+    res_traffic = None
+    rec = RESTORE_TRAFFIC_PER_ROW.get(_restore_kernel_hash())
+    if rec and rec[0] == "%s/b%d" % (w.name, bits):
+        res_traffic = round(rec[1] * rows_per_launch, 1)
+    # the other long kernel of a step, measured the same way (from the per-stage run)
+    roofline_restore = {"bound": "hbm", "kernel": "restore_rows16_kernel<%d, %d>" % (w.dim // 16, bits),
+                        "achieved": round(res_achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                        "frac": round(res_achieved / HBM_PEAK_GBPS, 4), "traffic": res_traffic,
+                        "bytes_per_launch": int(res_bytes), "avg_launch_ms": round(res_ms, 5),
+                        "launches_per_event_span": launches_per_span}
     stages = {k: round(v, 4) for k, v in stage_ms.items()}
     stages["encode_only_GBps_table_bytes"] = round(table_bytes / ((stage_ms["compact"] + stage_ms["encode"]) * 1e-3) / 1e9, 1)
     stages["restore_hbm_GBps"] = round(res_bytes / (res_ms * 1e-3) / 1e9, 1)
@@ -240,6 +265,7 @@ def main() -> int:
                    "dirty_rows": sum(n_dirty), "lookups_per_step": int(sum(s.numel() for s in streams)),
                    "index_dtype": "int64"},
         "roofline": roofline,
+        "roofline_restore": roofline_restore,
         "stages_ms_per_step": stages,
     }
 
