@@ -22,6 +22,7 @@
  *   cnr_select_greedy_params   greedy parameters by profiling a sample (Section 5.2)
  *   cnr_host_writer_*, cnr_encode_to_host   chunked encode into host memory with the copy of one
  *                      chunk overlapping the encode of the next (Sections 4.4, 5.2)
+ *   cnr_restore_from_host   the way back: chunked copy from host memory overlapping the restore
  *   cnr_policy_*       the incremental-checkpoint policies (Section 5.1), host only
  *   cnr_select_bits    the code width for an expected number of resumes (Section 6.2.1), host only
  *
@@ -282,8 +283,8 @@ cnr_status cnr_restore_rows_batch(cnr_ctx *ctx, const cnr_table_job *jobs /* hos
 /* ---- chunked encode into host memory (Sections 4.4 and 5.2: the optimized checkpoint is built chunk
  *      by chunk, and a finished chunk is handed on while the next one is quantized) ----------------
  *
- * A writer owns two device staging sets of chunk_rows rows (scale, bias, packed codes), a copy
- * stream of default priority and the events that order it against the caller's stream.
+ * A writer owns two device staging sets of chunk_rows rows (row ids, scale, bias, packed codes), a
+ * copy stream of default priority and the events that order it against the caller's stream.
  * cnr_host_writer_create allocates them (cnr_host_writer_device_bytes tells how much device memory),
  * cnr_host_writer_destroy waits for the copy stream and frees them; nothing is allocated in between.
  *
@@ -300,7 +301,17 @@ cnr_status cnr_restore_rows_batch(cnr_ctx *ctx, const cnr_table_job *jobs /* hos
  *   host_scale, host_bias   host float [n]
  *   host_packed     host uint8 [n][cnr_packed_row_bytes(dim, bits)]
  *                   Pinned host memory lets the copies overlap; pageable memory works but serializes.
- *   chunk_rows      a multiple of 16 */
+ *   chunk_rows      a multiple of 16
+ *
+ * cnr_restore_from_host is the way back (Section 5.1: resume = baseline + incremental checkpoint;
+ * Section 6.2: the checkpoint is de-quantized when it is loaded): the same staging sets take the n
+ * rows of a checkpoint from host memory chunk by chunk, and every chunk is de-quantized and
+ * written over `table` as cnr_restore_rows does; with `overlap` != 0 the copy of one chunk runs on
+ * the writer's stream while the chunk before it is restored on `stream`.  The copies start after
+ * everything enqueued on `stream` before the call.  It only enqueues work; the host buffers may be
+ * reused after cnr_host_writer_wait.
+ *   host_row_ids    host uint32 [n]; NULL means rows 0 .. n-1 of the table (a full checkpoint)
+ *   host_scale, host_bias, host_packed   as cnr_encode_to_host wrote them */
 typedef struct cnr_host_writer cnr_host_writer; /* opaque */
 
 size_t cnr_host_writer_device_bytes(uint32_t dim, int bits, uint64_t chunk_rows);
@@ -310,6 +321,9 @@ cnr_status cnr_encode_to_host(cnr_host_writer *w, const float *table, uint64_t n
                               uint64_t n, cnr_range_mode mode, const cnr_greedy_params *greedy /* host */,
                               uint32_t *host_row_ids, float *host_scale, float *host_bias, uint8_t *host_packed,
                               int overlap, void *stream);
+cnr_status cnr_restore_from_host(cnr_host_writer *w, float *table, uint64_t n_rows,
+                                 const uint32_t *host_row_ids, const float *host_scale, const float *host_bias,
+                                 const uint8_t *host_packed, uint64_t n, int overlap, void *stream);
 cnr_status cnr_host_writer_wait(cnr_host_writer *w, void *stream);
 
 /* ---- device-side conditions ---------------------------------------------------------------- */

@@ -36,7 +36,7 @@ EXPORTS = (
     "cnr_clear_bitmap_batch", "cnr_mark_touched_batch", "cnr_compact_dirty_batch", "cnr_quantize_rows_batch",
     "cnr_restore_rows_batch",
     "cnr_host_writer_device_bytes", "cnr_host_writer_create", "cnr_host_writer_destroy", "cnr_encode_to_host",
-    "cnr_host_writer_wait", "cnr_select_scratch_bytes", "cnr_select_greedy_params",
+    "cnr_host_writer_wait", "cnr_restore_from_host", "cnr_select_scratch_bytes", "cnr_select_greedy_params",
 )
 
 
@@ -124,6 +124,7 @@ def load() -> ctypes.CDLL:
             "cnr_encode_to_host": (i32, [vp, vp, u64, vp, u64, i32, ctypes.POINTER(cnr_greedy_params),
                                          vp, vp, vp, vp, i32, vp]),
             "cnr_host_writer_wait": (i32, [vp, vp]),
+            "cnr_restore_from_host": (i32, [vp, vp, u64, vp, vp, vp, vp, u64, i32, vp]),
             "cnr_select_scratch_bytes": (sz, [u64, u32, i32]),
             "cnr_select_greedy_params": (i32, [vp, vp, u64, u32, vp, u64, i32, ctypes.POINTER(u32), u32,
                                                ctypes.POINTER(f32), u32, ctypes.c_double, vp,
@@ -420,6 +421,18 @@ def cnr_encode_to_host(writer, table, n_rows: int, dim: int, bits: int, row_ids,
                                      _host(host_scale, F32, "host_scale", n), _host(host_bias, F32, "host_bias", n),
                                      _host(host_packed, U8, "host_packed", n * cnr_packed_row_bytes(dim, bits)),
                                      1 if overlap else 0, _stream(stream)), "cnr_encode_to_host")
+
+
+def cnr_restore_from_host(writer, table, n_rows: int, dim: int, bits: int, host_row_ids, host_scale, host_bias,
+                          host_packed, n: int, overlap: bool = True, stream=None) -> None:
+    """``dim`` and ``bits`` are the writer's (used here to check the buffers' sizes)."""
+    if table.numel() < n_rows * dim:
+        raise ValueError("table smaller than n_rows * dim")
+    _check(load().cnr_restore_from_host(writer, _dev(table, F32, "table"), n_rows,
+                                        _host(host_row_ids, U32, "host_row_ids", n),
+                                        _host(host_scale, F32, "host_scale", n), _host(host_bias, F32, "host_bias", n),
+                                        _host(host_packed, U8, "host_packed", n * cnr_packed_row_bytes(dim, bits)),
+                                        n, 1 if overlap else 0, _stream(stream)), "cnr_restore_from_host")
 
 
 def cnr_host_writer_wait(writer, stream=None) -> None:

@@ -259,3 +259,14 @@ class HostCheckpointWriter:
                              overlap, main)
         B.cnr_host_writer_wait(self.writer, main)
         return n
+
+    def restore_from_host(self, table: torch.Tensor, n_rows: int, n: int, overlap: bool = True,
+                          with_ids: bool = True) -> None:
+        """Writes the first ``n`` rows held in the pinned host buffers (as :meth:`encode_to_host` left
+        them, or as a loader filled them) over ``table``: the copy of chunk c+1 from host memory
+        overlaps the de-quantize-and-scatter of chunk c.  Synchronises at the end."""
+        main = torch.cuda.current_stream()
+        B.cnr_restore_from_host(self.writer, table, n_rows, self.dim, self.bits,
+                                self.host["row_ids"] if with_ids else None, self.host["scale"], self.host["bias"],
+                                self.host["packed"], n, overlap, main)
+        B.cnr_host_writer_wait(self.writer, main)

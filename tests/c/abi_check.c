@@ -18,7 +18,7 @@ int main(void) {
         (fn)cnr_compact_dirty_batch, (fn)cnr_quantize_rows_batch, (fn)cnr_restore_rows_batch,
         (fn)cnr_host_writer_device_bytes, (fn)cnr_host_writer_create, (fn)cnr_host_writer_destroy,
         (fn)cnr_encode_to_host, (fn)cnr_host_writer_wait, (fn)cnr_select_scratch_bytes,
-        (fn)cnr_select_greedy_params, (fn)cnr_select_bits};
+        (fn)cnr_select_greedy_params, (fn)cnr_select_bits, (fn)cnr_restore_from_host};
     size_t i, n_exports = sizeof(exports) / sizeof(exports[0]);
     for (i = 0; i < n_exports; ++i)
         if (!exports[i]) return 10;
@@ -47,7 +47,7 @@ int main(void) {
         cnr_select_bits(21, 0) != 8 || cnr_select_bits(1, 2) != 8)
         return 19;
     if (cnr_select_scratch_bytes(100, 64, 4) != 400u + 400u + 3200u + 800u + 16u) return 27;
-    if (cnr_host_writer_device_bytes(64, 4, 1024) != 2u * 1024u * 40u || cnr_host_writer_device_bytes(12, 3, 16) != 0) return 26;
+    if (cnr_host_writer_device_bytes(64, 4, 1024) != 2u * 1024u * 44u || cnr_host_writer_device_bytes(12, 3, 16) != 0) return 26;
     {
         cnr_ctx *ctx = NULL;
         cnr_status st = cnr_create(&ctx, 0);

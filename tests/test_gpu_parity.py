@@ -477,6 +477,56 @@ def test_chunked_encode_to_host_equals_one_shot_encode(ctx, overlap):
     _poll_clean(ctx)
 
 
+@pytest.mark.parametrize("overlap", [True, False])
+@pytest.mark.parametrize("with_ids", [True, False])
+def test_round_trip_through_host_memory(ctx, overlap, with_ids):
+    # checkpoint to host memory in chunks, then the way back: the table restored from the host buffers
+    # chunk by chunk equals the one restored by a single call from the device-side encode, and the oracle's
+    n_rows, dim, bits = 60_017, 64, 4
+    print("case host round trip overlap=%s with_ids=%s" % (overlap, with_ids), flush=True)
+    table = synth.table_outlier_mix(n_rows, dim, 0.02, 41, DEV)
+    ck = P.TableCheckpointer(ctx, n_rows, dim, device=DEV)
+    ck.clear()
+    if with_ids:
+        ck.mark(synth.bernoulli_lookup_stream(n_rows, 0.4, 7, DEV))
+    else:
+        ck.bitmap.fill_(-1)                                     # every row: a full checkpoint
+    ck.compact()
+    writer = P.HostCheckpointWriter(ctx, dim, bits, capacity=n_rows, chunk_rows=4096, device=DEV)   # 6 to 15 chunks
+    n = writer.encode_to_host(ck, table, overlap=overlap)
+    assert n == int(ck.n_dirty.item()) and (with_ids or n == n_rows)
+    ids = writer.host["row_ids"][:n].numpy().view(np.uint32).copy()
+
+    direct = torch.full_like(table, -3.0)
+    enc = ck.alloc_output(bits)
+    ck.encode(table, enc)
+    ck.restore(direct, enc)
+    for rep in range(2):                                        # twice: the staging sets are reused
+        back = torch.full_like(table, -3.0)
+        writer.restore_from_host(back, n_rows, n, overlap=overlap, with_ids=with_ids)
+        assert torch.equal(back, direct)
+    want = np.full((n_rows, dim), -3.0, dtype=np.float32)
+    O.restore_rows(want, ids, bits, writer.host["packed"][:n * writer.prb].numpy().reshape(n, -1),
+                   writer.host["scale"][:n].numpy(), writer.host["bias"][:n].numpy())
+    assert np.array_equal(back.cpu().numpy(), want)
+    # a write right after a read, then a read, with no wait between the first two
+    main = torch.cuda.current_stream()
+    back.fill_(-3.0)
+    P.cnr_restore_from_host(writer.writer, back, n_rows, dim, bits, writer.host["row_ids"] if with_ids else None,
+                            writer.host["scale"], writer.host["bias"], writer.host["packed"], n, overlap, main)
+    assert writer.encode_to_host(ck, back, overlap=overlap) == n   # encodes the table just restored
+    again = torch.full_like(table, -3.0)
+    writer.restore_from_host(again, n_rows, n, overlap=overlap, with_ids=with_ids)
+    torch.cuda.synchronize()
+    q = O.quantize_rows(want, ids, bits, n_threads=4)           # the oracle's encode of its own restored table
+    want2 = np.full((n_rows, dim), -3.0, dtype=np.float32)
+    O.restore_rows(want2, ids, bits, O.pack(q["codes"], bits), q["scale"], q["bias"])
+    got2 = again.cpu().numpy()
+    assert np.mean(got2 != want2) <= 1e-4 and np.array_equal(got2[want2 == -3.0], want2[want2 == -3.0])
+    writer.close()
+    _poll_clean(ctx)
+
+
 def test_misaligned_row_id_slice_is_refused(ctx):
     t = torch.zeros((64, 64), device=DEV)
     ids = torch.arange(64, dtype=torch.int32, device=DEV)
@@ -666,7 +716,7 @@ def test_host_writer_back_to_back_tables_and_argument_errors(ctx):
     dim, bits, chunk = 64, 4, 16 * 500
     prb = P.cnr_packed_row_bytes(dim, bits)
     writer = P.cnr_host_writer_create(ctx, dim, bits, chunk)
-    assert P.cnr_host_writer_device_bytes(dim, bits, chunk) == 2 * chunk * (prb + 8)
+    assert P.cnr_host_writer_device_bytes(dim, bits, chunk) == 2 * chunk * (prb + 12)
     jobs = []
     for seed, n_rows in ((1, 50_000), (2, 33_000)):
         gt = GpuTable(ctx, _table(n_rows, dim, 300 + seed))
