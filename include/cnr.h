@@ -295,8 +295,8 @@ cnr_status cnr_restore_rows_batch(cnr_ctx *ctx, const cnr_table_job *jobs /* hos
  * are complete after cnr_host_writer_wait (which synchronizes both streams).  One call at a time per
  * writer.
  *   n               host value: the number of rows (read it back from cnr_compact_dirty's count first)
- *   row_ids         device, uint32 [n], 16-byte aligned; NULL means rows 0 .. n-1 and then n must not
- *                   exceed chunk_rows
+ *   row_ids         device, uint32 [n], 16-byte aligned; NULL means rows 0 .. n-1 of the table (a
+ *                   full checkpoint)
  *   host_row_ids    host uint32 [n] (ignored when row_ids is NULL)
  *   host_scale, host_bias   host float [n]
  *   host_packed     host uint8 [n][cnr_packed_row_bytes(dim, bits)]

@@ -113,7 +113,7 @@ cnr_status cnr_encode_to_host(cnr_host_writer *w, const float *table, uint64_t n
     if (st != CNR_OK) return st;
     if (n == 0) return CNR_OK;
     if (!host_scale || !host_bias || !host_packed || (row_ids && !host_row_ids)) return CNR_E_INVALID;
-    if (!row_ids && n > w->chunk_rows) return CNR_E_INVALID;  // without a row list there is only one chunk
+    if (!row_ids && n > n_rows) return CNR_E_INVALID;  // without a row list the rows are 0 .. n-1 of the table
     hipStream_t main = as_stream(stream);
     hipStream_t copier = overlap ? w->copy : main;
     hipError_t e = hipSuccess;
@@ -127,8 +127,12 @@ cnr_status cnr_encode_to_host(cnr_host_writer *w, const float *table, uint64_t n
             if (e != hipSuccess) break;
             w->in_use[b] = false;
         }
-        st = cnr_quantize_rows(ctx, table, n_rows, w->dim, row_ids ? row_ids + k0 : nullptr, nullptr, m, w->bits, mode,
-                               greedy, w->scale[b], w->bias[b], nullptr, nullptr, nullptr, w->packed[b], stream);
+        if (row_ids)
+            st = cnr_quantize_rows(ctx, table, n_rows, w->dim, row_ids + k0, nullptr, m, w->bits, mode, greedy,
+                                   w->scale[b], w->bias[b], nullptr, nullptr, nullptr, w->packed[b], stream);
+        else  // rows k0 .. k0 + m - 1: the table from row k0 on, without a list
+            st = cnr_quantize_rows(ctx, table + k0 * w->dim, n_rows - k0, w->dim, nullptr, nullptr, m, w->bits, mode,
+                                   greedy, w->scale[b], w->bias[b], nullptr, nullptr, nullptr, w->packed[b], stream);
         if (st != CNR_OK) return st;
         if (copier != main) {
             e = hipEventRecord(w->encoded[b], main);

@@ -739,18 +739,22 @@ def test_host_writer_back_to_back_tables_and_argument_errors(ctx):
         got = dict(scale=host["scale"].numpy(), bias=host["bias"].numpy(),
                    codes=O.unpack(host["packed"].numpy().reshape(n, prb), dim, bits))
         compare_quantized(gt.host[ids], got, ora, bits, what="host writer, %d rows" % n)
-    # rows 0 .. n-1 without a list: one chunk at most
+    # rows 0 .. n-1 without a list (a full checkpoint): several chunks, the last one ragged; more rows than
+    # the table has is an error
     gt = jobs[0][0]
-    hs, hb = torch.empty(chunk), torch.empty(chunk)
-    hp = torch.empty(chunk * prb, dtype=torch.uint8)
-    P.cnr_encode_to_host(writer, gt.table, gt.n_rows, dim, bits, None, chunk, P.CNR_RANGE_MINMAX, None, None, hs, hb, hp)
+    n_full = 2 * chunk + 336
+    assert n_full <= gt.n_rows
+    hs, hb = torch.empty(n_full), torch.empty(n_full)
+    hp = torch.empty(n_full * prb, dtype=torch.uint8)
+    P.cnr_encode_to_host(writer, gt.table, gt.n_rows, dim, bits, None, n_full, P.CNR_RANGE_MINMAX, None, None, hs, hb, hp)
     P.cnr_host_writer_wait(writer)
-    ora = O.quantize_rows(gt.host[:chunk].copy(), None, bits, n_threads=8)
-    assert np.array_equal(hs.numpy(), ora["scale"])
+    ora = O.quantize_rows(gt.host[:n_full].copy(), None, bits, n_threads=8)
+    got = dict(scale=hs.numpy(), bias=hb.numpy(), codes=O.unpack(hp.numpy().reshape(n_full, prb), dim, bits))
+    compare_quantized(gt.host[:n_full], got, ora, bits, what="host writer, no list")
     with pytest.raises(P.CnrError) as e:
-        P.cnr_encode_to_host(writer, gt.table, gt.n_rows, dim, bits, None, chunk + 16, P.CNR_RANGE_MINMAX, None, None,
-                             torch.empty(chunk + 16), torch.empty(chunk + 16),
-                             torch.empty((chunk + 16) * prb, dtype=torch.uint8))
+        m = gt.n_rows + 16
+        P.cnr_encode_to_host(writer, gt.table, gt.n_rows, dim, bits, None, m, P.CNR_RANGE_MINMAX, None, None,
+                             torch.empty(m), torch.empty(m), torch.empty(m * prb, dtype=torch.uint8))
     assert e.value.status == P.CNR_E_INVALID
     P.cnr_host_writer_destroy(writer)
     for bad_chunk, status in ((100, P.CNR_E_INVALID), (0, P.CNR_E_INVALID)):
