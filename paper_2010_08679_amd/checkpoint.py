@@ -260,6 +260,18 @@ class HostCheckpointWriter:
         B.cnr_host_writer_wait(self.writer, main)
         return n
 
+    def encode_table_to_host(self, table: torch.Tensor, n_rows: int, mode: int = B.CNR_RANGE_MINMAX,
+                             greedy=None, overlap: bool = True) -> int:
+        """A full (baseline) checkpoint: every row of ``table``, no id list, into the pinned host
+        buffers; returns ``n_rows``.  Synchronises at the end."""
+        if n_rows > self.capacity:
+            raise ValueError("the writer's host buffers hold %d rows" % self.capacity)
+        main = torch.cuda.current_stream()
+        B.cnr_encode_to_host(self.writer, table, n_rows, self.dim, self.bits, None, n_rows, mode, greedy,
+                             None, self.host["scale"], self.host["bias"], self.host["packed"], overlap, main)
+        B.cnr_host_writer_wait(self.writer, main)
+        return n_rows
+
     def restore_from_host(self, table: torch.Tensor, n_rows: int, n: int, overlap: bool = True,
                           with_ids: bool = True) -> None:
         """Writes the first ``n`` rows held in the pinned host buffers (as :meth:`encode_to_host` left

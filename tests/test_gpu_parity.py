@@ -496,6 +496,11 @@ def test_round_trip_through_host_memory(ctx, overlap, with_ids):
     n = writer.encode_to_host(ck, table, overlap=overlap)
     assert n == int(ck.n_dirty.item()) and (with_ids or n == n_rows)
     ids = writer.host["row_ids"][:n].numpy().view(np.uint32).copy()
+    if not with_ids:                                            # the same checkpoint without any list
+        listed = {k: v[:n * (writer.prb if k == "packed" else 1)].clone() for k, v in writer.host.items()}
+        assert writer.encode_table_to_host(table, n_rows, overlap=overlap) == n_rows
+        for k in ("scale", "bias", "packed"):
+            assert torch.equal(writer.host[k][:listed[k].numel()], listed[k]), k
 
     direct = torch.full_like(table, -3.0)
     enc = ck.alloc_output(bits)
