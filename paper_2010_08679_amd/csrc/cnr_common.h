@@ -50,6 +50,10 @@ static inline unsigned cnr_grid(const cnr_ctx *ctx, uint64_t work_items, uint64_
     return (unsigned)(need < cap ? need : cap);
 }
 
+// A table whose rows (at capacity) come to no more than this many bytes counts as small: in a batch
+// it shares a launch with the other small tables instead of taking one of its own.
+constexpr uint64_t kSideBySideBytes = 64ull << 20;
+
 // Rows per launch for a list whose length the host knows (no count on the device).  The waves of a
 // long encode or restore launch drift apart and stop sweeping one region of the table together;
 // slices of about 512 MB of table rows keep them together (3 to 5 % faster on lists of several

@@ -352,6 +352,19 @@ quantize_tile_kernel(const QuantArgs a) {
     encode_table<Q, BITS>(a, tiles + (tid_x() / kWave) * kTileBytes);
 }
 
+// Several small tables side by side in one launch (grid y = table): a table of a few ten thousand
+// dirty rows does not fill the chip for the few microseconds a launch takes at the least, and a GPU
+// holds many such tables (Section 2.1).
+struct QuantBatchArgs {
+    QuantArgs job[CNR_MAX_BATCH];
+};
+template <int Q, int BITS>
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(Q <= 4 ? 5 : Q == 8 ? 3 : 2, Q <= 4 ? 6 : Q == 8 ? 4 : 2)))
+quantize_tile_tables_kernel(const QuantBatchArgs b) {
+    __shared__ __align__(16) unsigned char tiles[kWavesPerBlock * kTileBytes];
+    encode_table<Q, BITS>(b.job[wg_y()], tiles + (tid_x() / kWave) * kTileBytes);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Greedy range search (Approach 3), dim = 16 * L with L = 1, 2, 4, 8 or 16 lanes per row.  Bound by
 // vector-ALU issue: 1 + 2 * n_iter candidate ranges are tried per row.
@@ -837,6 +850,31 @@ void launch_tile(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
     hipLaunchKernelGGL((quantize_tile_kernel<Q, BITS>), dim3(grid), dim3(kBlock), 0, s, a);
 }
 
+// n small tables in one launch: as many workgroups per table as the largest needs, but no more in
+// all than are resident at once.
+template <int Q, int BITS>
+void launch_tile_tables(cnr_ctx *ctx, QuantBatchArgs &b, uint32_t n, hipStream_t s) {
+    const unsigned resident = cnr_resident_blocks_per_cu<quantize_tile_tables_kernel<Q, BITS>>();
+    uint64_t most = 0;
+    for (uint32_t i = 0; i < n; ++i)
+        if (b.job[i].n_max > most) most = b.job[i].n_max;
+    unsigned grid = cnr_grid(ctx, most, (uint64_t)TileShape<Q>::ROWS * kWavesPerBlock, resident);
+    const unsigned share = (unsigned)ctx->n_cu * resident / n;
+    if (grid > share) grid = share > 0 ? share : 1;
+    for (uint32_t i = 0; i < n; ++i) b.job[i].n_waves = grid * kWavesPerBlock;
+    hipLaunchKernelGGL((quantize_tile_tables_kernel<Q, BITS>), dim3(grid, n), dim3(kBlock), 0, s, b);
+}
+template <int BITS>
+void launch_tables_bits(cnr_ctx *ctx, QuantBatchArgs &b, uint32_t n, uint32_t dim, hipStream_t s) {
+    switch (dim) {
+        case 16: return launch_tile_tables<1, BITS>(ctx, b, n, s);
+        case 32: return launch_tile_tables<2, BITS>(ctx, b, n, s);
+        case 64: return launch_tile_tables<4, BITS>(ctx, b, n, s);
+        case 128: return launch_tile_tables<8, BITS>(ctx, b, n, s);
+        default: return launch_tile_tables<16, BITS>(ctx, b, n, s);
+    }
+}
+
 template <int L, int BITS>
 void launch_greedy(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
     const unsigned grid = cnr_grid(ctx, a.n_max, (uint64_t)(kWave / L) * kWavesPerBlock,
@@ -903,9 +941,44 @@ cnr_status cnr_quantize_rows_batch(cnr_ctx *ctx, const cnr_table_job *jobs, uint
     // traffic only while all waves of the grid sweep one table together, and one launch that walks
     // several tables lets them drift apart (measured: 86 against 82 us per 5 M x 64 table).
     hipStream_t s = as_stream(stream);
+    const uint32_t n_iter = mode == CNR_RANGE_GREEDY ? cnr_greedy_iterations(greedy->num_bins, greedy->ratio) : 0;
+    auto fill = [&](QuantArgs &a, const cnr_table_job &j) {
+        a.table = j.table; a.n_rows = j.n_rows; a.dim = dim; a.row_ids = j.row_ids;
+        a.n_dev = j.n_dirty_dev; a.n_max = j.capacity;
+        a.mode = (int)mode; a.n_iter = n_iter;
+        a.num_bins_f = mode == CNR_RANGE_GREEDY ? (float)greedy->num_bins : 1.0f;
+        a.scale = j.scale; a.bias = j.bias; a.row_min = j.row_min; a.row_max = j.row_max;
+        a.codes = j.codes_u8; a.packed = j.packed; a.err = ctx->dev_err;
+    };
+    // Small tables of a row length the tile kernel takes go side by side, up to CNR_MAX_BATCH per
+    // launch (not under the greedy search, which keeps even a small table busy for long).
+    const bool tile_dim = dim == 16 || dim == 32 || dim == 64 || dim == 128 || dim == 256;
+    auto small = [&](const cnr_table_job &j) {
+        return tile_dim && n_iter == 0 && j.capacity != 0 && j.capacity * 4ull * dim <= kSideBySideBytes;
+    };
+    uint32_t n_small = 0;
+    for (uint32_t i = 0; i < n_jobs; ++i) n_small += small(jobs[i]) ? 1u : 0u;
+    const bool side_by_side = n_small >= 2;
+    if (side_by_side) {
+        QuantBatchArgs b = {};
+        uint32_t n = 0;
+        for (uint32_t i = 0; i <= n_jobs; ++i) {
+            if (i < n_jobs && small(jobs[i])) fill(b.job[n++], jobs[i]);
+            if (n == CNR_MAX_BATCH || (i == n_jobs && n > 0)) {
+                switch (bits) {
+                    case 2: launch_tables_bits<2>(ctx, b, n, dim, s); break;
+                    case 3: launch_tables_bits<3>(ctx, b, n, dim, s); break;
+                    case 4: launch_tables_bits<4>(ctx, b, n, dim, s); break;
+                    default: launch_tables_bits<8>(ctx, b, n, dim, s); break;
+                }
+                if ((st = cnr_launch_status(ctx)) != CNR_OK) return st;
+                n = 0;
+            }
+        }
+    }
     for (uint32_t i = 0; i < n_jobs; ++i) {
         const cnr_table_job &j = jobs[i];
-        if (j.capacity == 0) continue;
+        if (j.capacity == 0 || (side_by_side && small(j))) continue;
         // A list whose length the host knows is encoded in slices (cnr_slice_rows).  Without an id
         // list a slice is the table from its first row on.
         const bool sliceable = !j.n_dirty_dev && (j.row_ids || j.capacity <= j.n_rows);
@@ -922,7 +995,7 @@ cnr_status cnr_quantize_rows_batch(cnr_ctx *ctx, const cnr_table_job *jobs, uint
             a.n_dev = j.n_dirty_dev;
             a.n_max = j.capacity - k0 < step ? j.capacity - k0 : step;
             a.mode = (int)mode;
-            a.n_iter = mode == CNR_RANGE_GREEDY ? cnr_greedy_iterations(greedy->num_bins, greedy->ratio) : 0;
+            a.n_iter = n_iter;
             a.num_bins_f = mode == CNR_RANGE_GREEDY ? (float)greedy->num_bins : 1.0f;
             a.scale = j.scale + k0; a.bias = j.bias + k0;
             a.row_min = j.row_min ? j.row_min + k0 : nullptr;

@@ -115,7 +115,7 @@ struct RestoreJob {
     uint32_t n_waves;  // waves of the grid
 };
 template <int Q, int BITS>
-__global__ void __launch_bounds__(kBlock) restore_rows16_kernel(const RestoreJob a, cnr_dev_errors *err) {
+__device__ __forceinline__ void restore_table(const RestoreJob &a, cnr_dev_errors *err) {
     using S = RestoreShape<Q>;
     constexpr int DIM = S::DIM, M = S::M, LR = S::LR;
     constexpr uint64_t ROWS = S::ROWS;
@@ -196,6 +196,20 @@ __global__ void __launch_bounds__(kBlock) restore_rows16_kernel(const RestoreJob
     }
 }
 
+template <int Q, int BITS>
+__global__ void __launch_bounds__(kBlock) restore_rows16_kernel(const RestoreJob a, cnr_dev_errors *err) {
+    restore_table<Q, BITS>(a, err);
+}
+
+// Several small tables side by side in one launch (grid y = table), as for the encode.
+struct RestoreBatch {
+    RestoreJob job[CNR_MAX_BATCH];
+};
+template <int Q, int BITS>
+__global__ void __launch_bounds__(kBlock) restore_rows16_tables_kernel(const RestoreBatch b, cnr_dev_errors *err) {
+    restore_table<Q, BITS>(b.job[wg_y()], err);
+}
+
 // Other row lengths: LPR lanes per row (a power of two, at least the row's number of 16-byte units up
 // to 64), 64 / LPR rows per wave and pass; lane j takes the units j, j + LPR, ... of its row: it reads
 // the unit's 4 * BITS code bits (one, two or four bytes; at 3 bits the three bytes that hold the
@@ -253,6 +267,29 @@ void launch_restore16(cnr_ctx *ctx, hipStream_t st, RestoreJob &a) {
                                    cnr_resident_blocks_per_cu<restore_rows16_kernel<Q, BITS>>());
     a.n_waves = grid * kWavesPerBlock;
     hipLaunchKernelGGL((restore_rows16_kernel<Q, BITS>), dim3(grid), dim3(kBlock), 0, st, a, ctx->dev_err);
+}
+
+template <int Q, int BITS>
+void launch_restore16_tables(cnr_ctx *ctx, hipStream_t st, RestoreBatch &b, uint32_t n) {
+    const unsigned resident = cnr_resident_blocks_per_cu<restore_rows16_tables_kernel<Q, BITS>>();
+    uint64_t most = 0;
+    for (uint32_t i = 0; i < n; ++i)
+        if (b.job[i].n_max > most) most = b.job[i].n_max;
+    unsigned grid = cnr_grid(ctx, most, (uint64_t)RestoreShape<Q>::ROWS * kWavesPerBlock, resident);
+    const unsigned share = (unsigned)ctx->n_cu * resident / n;
+    if (grid > share) grid = share > 0 ? share : 1;
+    for (uint32_t i = 0; i < n; ++i) b.job[i].n_waves = grid * kWavesPerBlock;
+    hipLaunchKernelGGL((restore_rows16_tables_kernel<Q, BITS>), dim3(grid, n), dim3(kBlock), 0, st, b, ctx->dev_err);
+}
+template <int BITS>
+void launch_restore_tables(cnr_ctx *ctx, hipStream_t st, uint32_t dim, RestoreBatch &b, uint32_t n) {
+    switch (dim) {
+        case 16: return launch_restore16_tables<1, BITS>(ctx, st, b, n);
+        case 32: return launch_restore16_tables<2, BITS>(ctx, st, b, n);
+        case 64: return launch_restore16_tables<4, BITS>(ctx, st, b, n);
+        case 128: return launch_restore16_tables<8, BITS>(ctx, st, b, n);
+        default: return launch_restore16_tables<16, BITS>(ctx, st, b, n);
+    }
 }
 
 template <int LPR, int BITS>
@@ -393,9 +430,39 @@ extern "C" cnr_status cnr_restore_rows_batch(cnr_ctx *ctx, const cnr_table_job *
             return CNR_E_ALIGN;
     }
     hipStream_t s = as_stream(stream);
-    for (uint32_t i = 0; i < n_jobs; ++i) {  // one launch per table, back to back (as for the encode)
+    // small tables side by side, as for the encode
+    const bool tile_dim = dim == 16 || dim == 32 || dim == 64 || dim == 128 || dim == 256;
+    auto small = [&](const cnr_table_job &j) {
+        return tile_dim && j.capacity != 0 && j.capacity * 4ull * dim <= kSideBySideBytes;
+    };
+    uint32_t n_small = 0;
+    for (uint32_t i = 0; i < n_jobs; ++i) n_small += small(jobs[i]) ? 1u : 0u;
+    const bool side_by_side = n_small >= 2;
+    if (side_by_side) {
+        RestoreBatch b = {};
+        uint32_t n = 0;
+        for (uint32_t i = 0; i <= n_jobs; ++i) {
+            if (i < n_jobs && small(jobs[i])) {
+                const cnr_table_job &j = jobs[i];
+                RestoreJob &a = b.job[n++];
+                a.table = j.table; a.n_rows = j.n_rows; a.row_ids = j.row_ids; a.n_dev = j.n_dirty_dev;
+                a.n_max = j.capacity; a.packed = j.packed; a.scale = j.scale; a.bias = j.bias;
+            }
+            if (n == CNR_MAX_BATCH || (i == n_jobs && n > 0)) {
+                switch (bits) {
+                    case 2: launch_restore_tables<2>(ctx, s, dim, b, n); break;
+                    case 3: launch_restore_tables<3>(ctx, s, dim, b, n); break;
+                    case 4: launch_restore_tables<4>(ctx, s, dim, b, n); break;
+                    default: launch_restore_tables<8>(ctx, s, dim, b, n); break;
+                }
+                if ((st = cnr_launch_status(ctx)) != CNR_OK) return st;
+                n = 0;
+            }
+        }
+    }
+    for (uint32_t i = 0; i < n_jobs; ++i) {  // the others: one launch per table, back to back (as for the encode)
         const cnr_table_job &j = jobs[i];
-        if (j.capacity == 0) continue;
+        if (j.capacity == 0 || (side_by_side && small(j))) continue;
         // slices when the host knows the length of the list, as for the encode
         const bool sliceable = !j.n_dirty_dev && (j.row_ids || j.capacity <= j.n_rows);
         const uint64_t step = sliceable ? cnr_slice_rows(j.capacity, dim) : j.capacity;

@@ -65,11 +65,16 @@ def _host(enc, n, dim, bits):
                 packed=packed, codes=O.unpack(packed, dim, bits))
 
 
+# small tables share one encode / restore launch, a table of more than 64 MB takes its own
+SIZES = {"small": ([70_001, 5_000, 33, 16_384, 1], [300_000, 2_000, 0, 9_000, 3]),   # look-ups: bulk, atomic, none, ...
+         "mixed": ([5_000, 300_007, 40_000, 140_000], [4_000, 200_000, 30_000, 90_000])}
+
+
 @pytest.mark.parametrize("bits", BITS)
-@pytest.mark.parametrize("dim", [64, 128])
-def test_batched_checkpoint_equals_oracle_and_single_calls(ctx, bits, dim):
-    sizes = [70_001, 5_000, 33, 16_384, 1]
-    n_idx = [300_000, 2_000, 0, 9_000, 3]                      # bulk route, atomic route, nothing, ...
+@pytest.mark.parametrize("dim,which", [(64, "small"), (128, "small"), (64, "mixed"), (256, "mixed"), (32, "small")])
+def test_batched_checkpoint_equals_oracle_and_single_calls(ctx, bits, dim, which):
+    sizes, n_idx = SIZES[which]
+    print("case batch %s dim=%d bits=%d" % (which, dim, bits), flush=True)
     T = _Tables(ctx, sizes, dim, seed=bits * 10 + dim, n_idx=n_idx)
     # --- batched path
     T.batch.clear()
