@@ -844,8 +844,7 @@ pack_kernel(const uint8_t *__restrict__ codes, const uint64_t *__restrict__ n_de
 
 template <int Q, int BITS>
 void launch_tile(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
-    const unsigned grid = cnr_grid(ctx, a.n_max, (uint64_t)TileShape<Q>::ROWS * kWavesPerBlock,
-                                   cnr_resident_blocks_per_cu<quantize_tile_kernel<Q, BITS>>());
+    const unsigned grid = cnr_row_grid(a.n_max, (uint64_t)TileShape<Q>::ROWS * kWavesPerBlock);
     a.n_waves = grid * kWavesPerBlock;
     hipLaunchKernelGGL((quantize_tile_kernel<Q, BITS>), dim3(grid), dim3(kBlock), 0, s, a);
 }

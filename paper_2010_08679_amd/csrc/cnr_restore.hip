@@ -263,8 +263,7 @@ __global__ void __launch_bounds__(kBlock) restore_strided_kernel(const RestoreJo
 
 template <int Q, int BITS>
 void launch_restore16(cnr_ctx *ctx, hipStream_t st, RestoreJob &a) {
-    const unsigned grid = cnr_grid(ctx, a.n_max, (uint64_t)RestoreShape<Q>::ROWS * kWavesPerBlock,
-                                   cnr_resident_blocks_per_cu<restore_rows16_kernel<Q, BITS>>());
+    const unsigned grid = cnr_row_grid(a.n_max, (uint64_t)RestoreShape<Q>::ROWS * kWavesPerBlock);
     a.n_waves = grid * kWavesPerBlock;
     hipLaunchKernelGGL((restore_rows16_kernel<Q, BITS>), dim3(grid), dim3(kBlock), 0, st, a, ctx->dev_err);
 }
