@@ -73,8 +73,9 @@ static inline uint64_t cnr_slice_rows(uint64_t n, uint32_t dim) {
 // resident workgroups, each striding through the whole list, lets them drift apart (measured on
 // 1.5 M rows of 64 floats: encode 80 -> 76 us, restore 98 -> 83 us; more on longer lists).  The row
 // count is only known on the device, so the grid follows n_max and is capped: workgroups beyond
-// the count leave at once, and 32 K of them cost about 5 us.
-constexpr uint64_t kRowKernelMaxBlocks = 32768;
+// the count leave at once, and 24 K of them cost about 4 us.  (Caps from 16 K to 32 K are within a
+// few per cent of each other from 5 % to 100 % of a 5 M-row table; 64 K and more lose on short lists.)
+constexpr uint64_t kRowKernelMaxBlocks = 24576;
 static inline unsigned cnr_row_grid(uint64_t n_max, uint64_t rows_per_block) {
     uint64_t need = (n_max + rows_per_block - 1) / rows_per_block;
     if (need < 1) need = 1;

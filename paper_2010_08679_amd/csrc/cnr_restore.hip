@@ -293,8 +293,7 @@ void launch_restore_tables(cnr_ctx *ctx, hipStream_t st, uint32_t dim, RestoreBa
 
 template <int LPR, int BITS>
 void launch_restore_strided(cnr_ctx *ctx, hipStream_t st, uint32_t dim, RestoreJob &a) {
-    const unsigned grid = cnr_grid(ctx, a.n_max, (uint64_t)(kWave / LPR) * kWavesPerBlock,
-                                   cnr_resident_blocks_per_cu<restore_strided_kernel<LPR, BITS>>());
+    const unsigned grid = cnr_row_grid(a.n_max, (uint64_t)(kWave / LPR) * kWavesPerBlock);
     a.n_waves = grid * kWavesPerBlock;
     hipLaunchKernelGGL((restore_strided_kernel<LPR, BITS>), dim3(grid), dim3(kBlock), 0, st, a, dim, ctx->dev_err);
 }
