@@ -41,8 +41,8 @@ ISSUE_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # one vector instruction per lane
 # per dirty row, valid only for the kernel source whose hash is recorded with it.
 TRAFFIC_PER_ROW = {
     # _kernel_hash() : (workload, bytes per dirty row)
-    # (2.000 * 190486.1 KiB FETCH_SIZE + 1.000 * 60145.5 KiB WRITE_SIZE) / 1,500,122 rows per launch
-    "97473828cfe1ac1e2857583f3b5bff6324d9656d03185199c05e9c3e58481b7c": ("cfg4/b4", 301.12),
+    # (2.000 * 190487.7 KiB FETCH_SIZE + 1.000 * 60727.9 KiB WRITE_SIZE) / 1,500,122 rows per launch
+    "97473828cfe1ac1e2857583f3b5bff6324d9656d03185199c05e9c3e58481b7c": ("cfg4/b4", 301.51),
 }
 
 
@@ -56,9 +56,9 @@ def _kernel_hash() -> str:
     return hashlib.sha256("".join(code.split()).encode()).hexdigest()
 
 
-# The same for the restore kernel: (2.000 * 32258.6 KiB + 1.000 * 375031.8 KiB) / 1,500,122 rows
+# The same for the restore kernel: (2.000 * 32257.6 KiB + 1.000 * 375046.6 KiB) / 1,500,122 rows
 RESTORE_TRAFFIC_PER_ROW = {
-    "7d0557b909bf569e399d3fe67cc73f16fd4ca0e83eeb139d6e75e1049fa89daf": ("cfg4/b4", 300.03),
+    "4b1d7b36c2c70baaa9a814b48269fcb5dee1b6410b65f524be5a07bb9a7deb7f": ("cfg4/b4", 300.05),
 }
 
 
