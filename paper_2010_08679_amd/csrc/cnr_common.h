@@ -86,6 +86,7 @@ static inline unsigned cnr_row_grid(uint64_t n_max, uint64_t rows_per_block) {
 // Workgroups of `Kernel` (kBlock threads, no dynamic LDS) that fit on one compute unit at once, at
 // most 8.  A persistent (grid-stride) kernel launched with more workgroups than are resident runs
 // them in rounds and leaves the last round under-filled, so grids are sized to exactly one round.
+// (A second, partial round is what hurts; the row kernels go far beyond it, see cnr_row_grid.)
 template <auto Kernel>
 static inline unsigned cnr_resident_blocks_per_cu() {
     static int cached = 0;
