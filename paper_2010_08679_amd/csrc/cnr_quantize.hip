@@ -28,7 +28,7 @@ struct QuantArgs {
     float *scale, *bias, *row_min, *row_max;
     uint8_t *codes, *packed;
     cnr_dev_errors *err;
-    uint32_t n_waves;  // waves of the grid (persistent kernels)
+    uint32_t n_waves;  // waves of the grid = the stride of a wave through the list, in passes
 };
 
 __device__ __forceinline__ uint64_t row_count(const QuantArgs &a) { return live_rows(a.n_dev, a.n_max); }
