@@ -228,7 +228,7 @@ def main() -> int:
     traffic = None
     rec = TRAFFIC_PER_ROW.get(_kernel_hash())
     if rec and rec[0] == "%s/b%d" % (w.name, bits):
-        traffic = rec[1] * rows_per_launch
+        traffic = round(rec[1] * rows_per_launch, 1)
     roofline = {"bound": "hbm", "kernel": "quantize_tile_kernel<%d, %d>" % (w.dim // 16, bits),
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
