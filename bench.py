@@ -141,6 +141,16 @@ def main() -> int:
     # ---- resident inputs ------------------------------------------------------------------------
     tables, streams, cks, encs = [], [], [], []
     batched = not args.per_table
+    # the batched form restores every table into a stale table of its own; where that does not fit the
+    # GPU's memory (configuration 5 at full size: 197 GB of tables), fall back to per-table calls
+    table_bytes = w.n_rows * w.dim * 4
+    per_row_extra = 12 + P.cnr_packed_row_bytes(w.dim, bits) + 1 + 8       # outputs, ids, mark scratch, look-ups (about)
+    need_batched = n_tables * (2 * table_bytes + w.n_rows * per_row_extra)
+    free_bytes = torch.cuda.mem_get_info()[0]
+    if batched and need_batched > 0.92 * free_bytes:
+        print("bench.py: the batched form needs about %.0f GB, %.0f GB are free: one call per table and stage instead"
+              % (need_batched / 1e9, free_bytes / 1e9), file=sys.stderr)
+        batched = False
     # per-table calls run one after the other and can share the scratch of the bulk mark
     # and the stale table that restore writes into; batched calls work on all tables at once
     shared_scratch = None if batched else P.TableCheckpointer.new_mark_scratch(w.n_rows, dev)
