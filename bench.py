@@ -228,11 +228,12 @@ def main() -> int:
     stage_ms = {k: v / args.steps for k, v in stage_timer.totals_ms().items()}
     launches = timer.counts()
 
-    # dominant kernel: the fused gather + quantize + pack, one launch per table.  A span of events
-    # holds one launch (per-table calls) or the n_tables back-to-back launches of one batched call.
-    launches_per_span = n_tables // launches_per_stage
+    # dominant kernel: the fused gather + quantize + pack.  A span of events holds one launch: one
+    # table (per-table calls), or all tables of the batched call (up to 16 tables per launch).
+    tables_per_launch = n_tables // launches_per_stage
+    launches_per_span = -(-tables_per_launch // P.CNR_MAX_BATCH)
     enc_launch_ms = timer.totals_ms()["encode"] / (launches["encode"] * launches_per_span)
-    rows_per_launch = sum(n_dirty) / n_tables
+    rows_per_launch = sum(n_dirty) / n_tables * tables_per_launch / launches_per_span
     enc_bytes = encode_bytes_per_row(w.dim, bits) * rows_per_launch
     achieved = enc_bytes / (enc_launch_ms * 1e-3) / 1e9
     traffic = None
@@ -243,6 +244,7 @@ def main() -> int:
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "bytes_per_launch": int(enc_bytes), "avg_launch_ms": round(enc_launch_ms, 5),
+                "tables_per_launch": tables_per_launch // launches_per_span,
                 "launches_per_event_span": launches_per_span, "empty_event_pair_ms": round(null_ms, 5)}
     res_ms = stage_timer.totals_ms()["restore"] / (stage_timer.counts()["restore"] * launches_per_span)
     res_bytes = restore_bytes_per_row(w.dim, bits) * rows_per_launch
@@ -256,6 +258,7 @@ def main() -> int:
                         "achieved": round(res_achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                         "frac": round(res_achieved / HBM_PEAK_GBPS, 4), "traffic": res_traffic,
                         "bytes_per_launch": int(res_bytes), "avg_launch_ms": round(res_ms, 5),
+                        "tables_per_launch": tables_per_launch // launches_per_span,
                         "launches_per_event_span": launches_per_span}
     stages = {k: round(v, 4) for k, v in stage_ms.items()}
     stages["encode_only_GBps_table_bytes"] = round(table_bytes / ((stage_ms["compact"] + stage_ms["encode"]) * 1e-3) / 1e9, 1)

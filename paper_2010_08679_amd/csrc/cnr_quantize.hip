@@ -342,27 +342,23 @@ __device__ __forceinline__ void encode_table(const QuantArgs &a, unsigned char *
     }
 }
 
-// The register budget is pinned to 5-6 / 3-4 / 2 waves per SIMD for rows of up to 64 / 128 / 256
+// One launch takes up to CNR_MAX_BATCH tables (grid y = table; a slice of a long list counts as a
+// table).  Workgroups are handed out x first, so the tables of a launch are swept one after the
+// other by all compute units, each on one moving front, with nothing idle between them; a table
+// that needs fewer workgroups than the largest of the launch sends the surplus home at once.
+// The register budget is pinned to 6 / 4 / 2 waves per SIMD for rows of up to 64 / 128 / 256
 // elements: left alone, the compiler lands a few registers to either side of those limits from one
 // small change to the next.
-template <int Q, int BITS>
-__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(Q <= 4 ? 5 : Q == 8 ? 3 : 2, Q <= 4 ? 6 : Q == 8 ? 4 : 2)))
-quantize_tile_kernel(const QuantArgs a) {
-    __shared__ __align__(16) unsigned char tiles[kWavesPerBlock * kTileBytes];
-    encode_table<Q, BITS>(a, tiles + (tid_x() / kWave) * kTileBytes);
-}
-
-// Several small tables side by side in one launch (grid y = table): a table of a few ten thousand
-// dirty rows does not fill the chip for the few microseconds a launch takes at the least, and a GPU
-// holds many such tables (Section 2.1).
 struct QuantBatchArgs {
     QuantArgs job[CNR_MAX_BATCH];
 };
 template <int Q, int BITS>
-__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(Q <= 4 ? 5 : Q == 8 ? 3 : 2, Q <= 4 ? 6 : Q == 8 ? 4 : 2)))
-quantize_tile_tables_kernel(const QuantBatchArgs b) {
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(Q <= 4 ? 6 : Q == 8 ? 4 : 2, Q <= 4 ? 6 : Q == 8 ? 4 : 2)))
+quantize_tile_kernel(const QuantBatchArgs b) {
     __shared__ __align__(16) unsigned char tiles[kWavesPerBlock * kTileBytes];
-    encode_table<Q, BITS>(b.job[wg_y()], tiles + (tid_x() / kWave) * kTileBytes);
+    const QuantArgs &a = b.job[wg_y()];
+    if (wg_x() * kWavesPerBlock >= a.n_waves) return;
+    encode_table<Q, BITS>(a, tiles + (tid_x() / kWave) * kTileBytes);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -842,35 +838,33 @@ pack_kernel(const uint8_t *__restrict__ codes, const uint64_t *__restrict__ n_de
     }
 }
 
+// n tables (or slices) in one launch: every one with the grid its own list calls for (cnr_row_grid).
 template <int Q, int BITS>
-void launch_tile(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
-    const unsigned grid = cnr_row_grid(a.n_max, (uint64_t)TileShape<Q>::ROWS * kWavesPerBlock);
-    a.n_waves = grid * kWavesPerBlock;
-    hipLaunchKernelGGL((quantize_tile_kernel<Q, BITS>), dim3(grid), dim3(kBlock), 0, s, a);
-}
-
-// n small tables in one launch: as many workgroups per table as the largest needs, but no more in
-// all than are resident at once.
-template <int Q, int BITS>
-void launch_tile_tables(cnr_ctx *ctx, QuantBatchArgs &b, uint32_t n, hipStream_t s) {
-    const unsigned resident = cnr_resident_blocks_per_cu<quantize_tile_tables_kernel<Q, BITS>>();
-    uint64_t most = 0;
-    for (uint32_t i = 0; i < n; ++i)
-        if (b.job[i].n_max > most) most = b.job[i].n_max;
-    unsigned grid = cnr_grid(ctx, most, (uint64_t)TileShape<Q>::ROWS * kWavesPerBlock, resident);
-    const unsigned share = (unsigned)ctx->n_cu * resident / n;
-    if (grid > share) grid = share > 0 ? share : 1;
-    for (uint32_t i = 0; i < n; ++i) b.job[i].n_waves = grid * kWavesPerBlock;
-    hipLaunchKernelGGL((quantize_tile_tables_kernel<Q, BITS>), dim3(grid, n), dim3(kBlock), 0, s, b);
+void launch_tile(QuantBatchArgs &b, uint32_t n, hipStream_t s) {
+    unsigned grid = 1;
+    for (uint32_t i = 0; i < n; ++i) {
+        const unsigned g = cnr_row_grid(b.job[i].n_max, (uint64_t)TileShape<Q>::ROWS * kWavesPerBlock);
+        b.job[i].n_waves = g * kWavesPerBlock;
+        if (g > grid) grid = g;
+    }
+    hipLaunchKernelGGL((quantize_tile_kernel<Q, BITS>), dim3(grid, n), dim3(kBlock), 0, s, b);
 }
 template <int BITS>
-void launch_tables_bits(cnr_ctx *ctx, QuantBatchArgs &b, uint32_t n, uint32_t dim, hipStream_t s) {
+void launch_tile_bits(QuantBatchArgs &b, uint32_t n, uint32_t dim, hipStream_t s) {
     switch (dim) {
-        case 16: return launch_tile_tables<1, BITS>(ctx, b, n, s);
-        case 32: return launch_tile_tables<2, BITS>(ctx, b, n, s);
-        case 64: return launch_tile_tables<4, BITS>(ctx, b, n, s);
-        case 128: return launch_tile_tables<8, BITS>(ctx, b, n, s);
-        default: return launch_tile_tables<16, BITS>(ctx, b, n, s);
+        case 16: return launch_tile<1, BITS>(b, n, s);
+        case 32: return launch_tile<2, BITS>(b, n, s);
+        case 64: return launch_tile<4, BITS>(b, n, s);
+        case 128: return launch_tile<8, BITS>(b, n, s);
+        default: return launch_tile<16, BITS>(b, n, s);
+    }
+}
+inline void launch_tile_any(QuantBatchArgs &b, uint32_t n, uint32_t dim, int bits, hipStream_t s) {
+    switch (bits) {
+        case 2: return launch_tile_bits<2>(b, n, dim, s);
+        case 3: return launch_tile_bits<3>(b, n, dim, s);
+        case 4: return launch_tile_bits<4>(b, n, dim, s);
+        default: return launch_tile_bits<8>(b, n, dim, s);
     }
 }
 
@@ -891,14 +885,16 @@ void launch_strided(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
     hipLaunchKernelGGL((quantize_strided_kernel<LPR, BITS>), dim3(grid), dim3(kBlock), 0, s, a);
 }
 
+// The kernels that take one table per launch: the greedy search at any row length, and min/max or
+// symmetric ranges at row lengths the tile kernel does not take.
 template <int BITS>
 void launch_bits(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
     const bool greedy = a.mode == kModeGreedy && a.n_iter > 0;  // zero iterations: plain min/max
-    if (a.dim == 16) return greedy ? launch_greedy<1, BITS>(ctx, a, s) : launch_tile<1, BITS>(ctx, a, s);
-    if (a.dim == 32) return greedy ? launch_greedy<2, BITS>(ctx, a, s) : launch_tile<2, BITS>(ctx, a, s);
-    if (a.dim == 64) return greedy ? launch_greedy<4, BITS>(ctx, a, s) : launch_tile<4, BITS>(ctx, a, s);
-    if (a.dim == 128) return greedy ? launch_greedy<8, BITS>(ctx, a, s) : launch_tile<8, BITS>(ctx, a, s);
-    if (a.dim == 256) return greedy ? launch_greedy<16, BITS>(ctx, a, s) : launch_tile<16, BITS>(ctx, a, s);
+    if (greedy && a.dim == 16) return launch_greedy<1, BITS>(ctx, a, s);
+    if (greedy && a.dim == 32) return launch_greedy<2, BITS>(ctx, a, s);
+    if (greedy && a.dim == 64) return launch_greedy<4, BITS>(ctx, a, s);
+    if (greedy && a.dim == 128) return launch_greedy<8, BITS>(ctx, a, s);
+    if (greedy && a.dim == 256) return launch_greedy<16, BITS>(ctx, a, s);
     if (greedy) {  // other row lengths, greedy: one wave per row
         const unsigned grid = cnr_grid(ctx, a.n_max, kWavesPerBlock, 8);
         hipLaunchKernelGGL((quantize_rows_generic_kernel<BITS>), dim3(grid), dim3(kBlock), 0, s, a.table,
@@ -937,80 +933,70 @@ cnr_status cnr_quantize_rows_batch(cnr_ctx *ctx, const cnr_table_job *jobs, uint
             ((uintptr_t)j.row_max % 4) || ((uintptr_t)j.row_ids % 16) || ((uintptr_t)j.n_dirty_dev % 8))
             return CNR_E_ALIGN;
     }
-    // One launch per table, back to back: the encode kernels run at the speed of their memory
-    // traffic only while all waves of the grid sweep one table together, and one launch that walks
-    // several tables lets them drift apart (measured: 86 against 82 us per 5 M x 64 table).
     hipStream_t s = as_stream(stream);
     const uint32_t n_iter = mode == CNR_RANGE_GREEDY ? cnr_greedy_iterations(greedy->num_bins, greedy->ratio) : 0;
-    auto fill = [&](QuantArgs &a, const cnr_table_job &j) {
-        a.table = j.table; a.n_rows = j.n_rows; a.dim = dim; a.row_ids = j.row_ids;
-        a.n_dev = j.n_dirty_dev; a.n_max = j.capacity;
+    const uint64_t prb = (uint64_t)dim * (uint64_t)bits / 8u;
+    // rows k0 .. k0 + m - 1 of job j's list as arguments of its own
+    auto part = [&](const cnr_table_job &j, uint64_t k0, uint64_t m) {
+        QuantArgs a = {};
+        a.dim = dim;
+        if (j.row_ids) {
+            a.table = j.table; a.n_rows = j.n_rows; a.row_ids = j.row_ids + k0;
+        } else {  // no id list: the table from row k0 on
+            a.table = j.table + k0 * dim; a.n_rows = j.n_rows - k0; a.row_ids = nullptr;
+        }
+        a.n_dev = j.n_dirty_dev; a.n_max = m;
         a.mode = (int)mode; a.n_iter = n_iter;
         a.num_bins_f = mode == CNR_RANGE_GREEDY ? (float)greedy->num_bins : 1.0f;
-        a.scale = j.scale; a.bias = j.bias; a.row_min = j.row_min; a.row_max = j.row_max;
-        a.codes = j.codes_u8; a.packed = j.packed; a.err = ctx->dev_err;
+        a.scale = j.scale + k0; a.bias = j.bias + k0;
+        a.row_min = j.row_min ? j.row_min + k0 : nullptr;
+        a.row_max = j.row_max ? j.row_max + k0 : nullptr;
+        a.codes = j.codes_u8 ? j.codes_u8 + k0 * dim : nullptr;
+        a.packed = j.packed ? j.packed + k0 * prb : nullptr;
+        a.err = ctx->dev_err;
+        return a;
     };
-    // Small tables of a row length the tile kernel takes go side by side, up to CNR_MAX_BATCH per
-    // launch (not under the greedy search, which keeps even a small table busy for long).
+    // The tile kernel takes up to CNR_MAX_BATCH tables per launch.  Small tables (rows of at most
+    // kSideBySideBytes at capacity) and large ones go into launches of their own kind, so that a
+    // small table is not given a large one's grid; a list whose length the host knows is cut into
+    // slices (cnr_slice_rows), each a table of the launch.
     const bool tile_dim = dim == 16 || dim == 32 || dim == 64 || dim == 128 || dim == 256;
-    auto small = [&](const cnr_table_job &j) {
-        return tile_dim && n_iter == 0 && j.capacity != 0 && j.capacity * 4ull * dim <= kSideBySideBytes;
-    };
-    uint32_t n_small = 0;
-    for (uint32_t i = 0; i < n_jobs; ++i) n_small += small(jobs[i]) ? 1u : 0u;
-    const bool side_by_side = n_small >= 2;
-    if (side_by_side) {
-        QuantBatchArgs b = {};
-        uint32_t n = 0;
-        for (uint32_t i = 0; i <= n_jobs; ++i) {
-            if (i < n_jobs && small(jobs[i])) fill(b.job[n++], jobs[i]);
-            if (n == CNR_MAX_BATCH || (i == n_jobs && n > 0)) {
-                switch (bits) {
-                    case 2: launch_tables_bits<2>(ctx, b, n, dim, s); break;
-                    case 3: launch_tables_bits<3>(ctx, b, n, dim, s); break;
-                    case 4: launch_tables_bits<4>(ctx, b, n, dim, s); break;
-                    default: launch_tables_bits<8>(ctx, b, n, dim, s); break;
-                }
-                if ((st = cnr_launch_status(ctx)) != CNR_OK) return st;
+    if (tile_dim && n_iter == 0) {
+        for (int large = 0; large < 2; ++large) {
+            QuantBatchArgs b = {};
+            uint32_t n = 0;
+            auto flush = [&]() -> cnr_status {
+                if (n == 0) return CNR_OK;
+                launch_tile_any(b, n, dim, bits, s);
                 n = 0;
+                return cnr_launch_status(ctx);
+            };
+            for (uint32_t i = 0; i < n_jobs; ++i) {
+                const cnr_table_job &j = jobs[i];
+                if (j.capacity == 0 || (j.capacity * 4ull * dim > kSideBySideBytes) != (large != 0)) continue;
+                const bool sliceable = !j.n_dirty_dev && (j.row_ids || j.capacity <= j.n_rows);
+                const uint64_t step = sliceable ? cnr_slice_rows(j.capacity, dim) : j.capacity;
+                for (uint64_t k0 = 0; k0 < j.capacity; k0 += step) {
+                    b.job[n++] = part(j, k0, j.capacity - k0 < step ? j.capacity - k0 : step);
+                    if (n == CNR_MAX_BATCH && (st = flush()) != CNR_OK) return st;
+                }
             }
+            if ((st = flush()) != CNR_OK) return st;
         }
+        return CNR_OK;
     }
+    // greedy search, other row lengths: one launch per table
     for (uint32_t i = 0; i < n_jobs; ++i) {
         const cnr_table_job &j = jobs[i];
-        if (j.capacity == 0 || (side_by_side && small(j))) continue;
-        // A list whose length the host knows is encoded in slices (cnr_slice_rows).  Without an id
-        // list a slice is the table from its first row on.
-        const bool sliceable = !j.n_dirty_dev && (j.row_ids || j.capacity <= j.n_rows);
-        const uint64_t step = sliceable ? cnr_slice_rows(j.capacity, dim) : j.capacity;
-        const uint64_t prb = (uint64_t)dim * (uint64_t)bits / 8u;
-        for (uint64_t k0 = 0; k0 < j.capacity; k0 += step) {
-            QuantArgs a = {};
-            a.dim = dim;
-            if (j.row_ids) {
-                a.table = j.table; a.n_rows = j.n_rows; a.row_ids = j.row_ids + k0;
-            } else {
-                a.table = j.table + k0 * dim; a.n_rows = j.n_rows - k0; a.row_ids = nullptr;
-            }
-            a.n_dev = j.n_dirty_dev;
-            a.n_max = j.capacity - k0 < step ? j.capacity - k0 : step;
-            a.mode = (int)mode;
-            a.n_iter = n_iter;
-            a.num_bins_f = mode == CNR_RANGE_GREEDY ? (float)greedy->num_bins : 1.0f;
-            a.scale = j.scale + k0; a.bias = j.bias + k0;
-            a.row_min = j.row_min ? j.row_min + k0 : nullptr;
-            a.row_max = j.row_max ? j.row_max + k0 : nullptr;
-            a.codes = j.codes_u8 ? j.codes_u8 + k0 * dim : nullptr;
-            a.packed = j.packed ? j.packed + k0 * prb : nullptr;
-            a.err = ctx->dev_err;
-            switch (bits) {
-                case 2: launch_bits<2>(ctx, a, s); break;
-                case 3: launch_bits<3>(ctx, a, s); break;
-                case 4: launch_bits<4>(ctx, a, s); break;
-                default: launch_bits<8>(ctx, a, s); break;
-            }
-            if ((st = cnr_launch_status(ctx)) != CNR_OK) return st;
+        if (j.capacity == 0) continue;
+        QuantArgs a = part(j, 0, j.capacity);
+        switch (bits) {
+            case 2: launch_bits<2>(ctx, a, s); break;
+            case 3: launch_bits<3>(ctx, a, s); break;
+            case 4: launch_bits<4>(ctx, a, s); break;
+            default: launch_bits<8>(ctx, a, s); break;
         }
+        if ((st = cnr_launch_status(ctx)) != CNR_OK) return st;
     }
     return CNR_OK;
 }

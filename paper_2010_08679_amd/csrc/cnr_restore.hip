@@ -196,18 +196,16 @@ __device__ __forceinline__ void restore_table(const RestoreJob &a, cnr_dev_error
     }
 }
 
-template <int Q, int BITS>
-__global__ void __launch_bounds__(kBlock) restore_rows16_kernel(const RestoreJob a, cnr_dev_errors *err) {
-    restore_table<Q, BITS>(a, err);
-}
-
-// Several small tables side by side in one launch (grid y = table), as for the encode.
+// One launch takes up to CNR_MAX_BATCH tables (grid y = table; a slice of a long list counts as a
+// table), swept one after the other because workgroups are handed out x first, as for the encode.
 struct RestoreBatch {
     RestoreJob job[CNR_MAX_BATCH];
 };
 template <int Q, int BITS>
-__global__ void __launch_bounds__(kBlock) restore_rows16_tables_kernel(const RestoreBatch b, cnr_dev_errors *err) {
-    restore_table<Q, BITS>(b.job[wg_y()], err);
+__global__ void __launch_bounds__(kBlock) restore_rows16_kernel(const RestoreBatch b, cnr_dev_errors *err) {
+    const RestoreJob &a = b.job[wg_y()];
+    if (wg_x() * kWavesPerBlock >= a.n_waves) return;  // fewer workgroups than the launch's largest table
+    restore_table<Q, BITS>(a, err);
 }
 
 // Other row lengths: LPR lanes per row (a power of two, at least the row's number of 16-byte units up
@@ -262,32 +260,23 @@ __global__ void __launch_bounds__(kBlock) restore_strided_kernel(const RestoreJo
 }
 
 template <int Q, int BITS>
-void launch_restore16(cnr_ctx *ctx, hipStream_t st, RestoreJob &a) {
-    const unsigned grid = cnr_row_grid(a.n_max, (uint64_t)RestoreShape<Q>::ROWS * kWavesPerBlock);
-    a.n_waves = grid * kWavesPerBlock;
-    hipLaunchKernelGGL((restore_rows16_kernel<Q, BITS>), dim3(grid), dim3(kBlock), 0, st, a, ctx->dev_err);
-}
-
-template <int Q, int BITS>
-void launch_restore16_tables(cnr_ctx *ctx, hipStream_t st, RestoreBatch &b, uint32_t n) {
-    const unsigned resident = cnr_resident_blocks_per_cu<restore_rows16_tables_kernel<Q, BITS>>();
-    uint64_t most = 0;
-    for (uint32_t i = 0; i < n; ++i)
-        if (b.job[i].n_max > most) most = b.job[i].n_max;
-    unsigned grid = cnr_grid(ctx, most, (uint64_t)RestoreShape<Q>::ROWS * kWavesPerBlock, resident);
-    const unsigned share = (unsigned)ctx->n_cu * resident / n;
-    if (grid > share) grid = share > 0 ? share : 1;
-    for (uint32_t i = 0; i < n; ++i) b.job[i].n_waves = grid * kWavesPerBlock;
-    hipLaunchKernelGGL((restore_rows16_tables_kernel<Q, BITS>), dim3(grid, n), dim3(kBlock), 0, st, b, ctx->dev_err);
+void launch_restore16(cnr_ctx *ctx, hipStream_t st, RestoreBatch &b, uint32_t n) {
+    unsigned grid = 1;
+    for (uint32_t i = 0; i < n; ++i) {
+        const unsigned g = cnr_row_grid(b.job[i].n_max, (uint64_t)RestoreShape<Q>::ROWS * kWavesPerBlock);
+        b.job[i].n_waves = g * kWavesPerBlock;
+        if (g > grid) grid = g;
+    }
+    hipLaunchKernelGGL((restore_rows16_kernel<Q, BITS>), dim3(grid, n), dim3(kBlock), 0, st, b, ctx->dev_err);
 }
 template <int BITS>
-void launch_restore_tables(cnr_ctx *ctx, hipStream_t st, uint32_t dim, RestoreBatch &b, uint32_t n) {
+void launch_restore16_bits(cnr_ctx *ctx, hipStream_t st, uint32_t dim, RestoreBatch &b, uint32_t n) {
     switch (dim) {
-        case 16: return launch_restore16_tables<1, BITS>(ctx, st, b, n);
-        case 32: return launch_restore16_tables<2, BITS>(ctx, st, b, n);
-        case 64: return launch_restore16_tables<4, BITS>(ctx, st, b, n);
-        case 128: return launch_restore16_tables<8, BITS>(ctx, st, b, n);
-        default: return launch_restore16_tables<16, BITS>(ctx, st, b, n);
+        case 16: return launch_restore16<1, BITS>(ctx, st, b, n);
+        case 32: return launch_restore16<2, BITS>(ctx, st, b, n);
+        case 64: return launch_restore16<4, BITS>(ctx, st, b, n);
+        case 128: return launch_restore16<8, BITS>(ctx, st, b, n);
+        default: return launch_restore16<16, BITS>(ctx, st, b, n);
     }
 }
 
@@ -298,13 +287,9 @@ void launch_restore_strided(cnr_ctx *ctx, hipStream_t st, uint32_t dim, RestoreJ
     hipLaunchKernelGGL((restore_strided_kernel<LPR, BITS>), dim3(grid), dim3(kBlock), 0, st, a, dim, ctx->dev_err);
 }
 
+// other row lengths: one table per launch
 template <int BITS>
 void launch_restore(cnr_ctx *ctx, hipStream_t st, uint32_t dim, RestoreJob &a) {
-    if (dim == 16) return launch_restore16<1, BITS>(ctx, st, a);
-    if (dim == 32) return launch_restore16<2, BITS>(ctx, st, a);
-    if (dim == 64) return launch_restore16<4, BITS>(ctx, st, a);
-    if (dim == 128) return launch_restore16<8, BITS>(ctx, st, a);
-    if (dim == 256) return launch_restore16<16, BITS>(ctx, st, a);
     const uint32_t n4 = dim / 4;
     if (n4 <= 4) return launch_restore_strided<4, BITS>(ctx, st, dim, a);
     if (n4 <= 8) return launch_restore_strided<8, BITS>(ctx, st, dim, a);
@@ -428,61 +413,60 @@ extern "C" cnr_status cnr_restore_rows_batch(cnr_ctx *ctx, const cnr_table_job *
             return CNR_E_ALIGN;
     }
     hipStream_t s = as_stream(stream);
-    // small tables side by side, as for the encode
-    const bool tile_dim = dim == 16 || dim == 32 || dim == 64 || dim == 128 || dim == 256;
-    auto small = [&](const cnr_table_job &j) {
-        return tile_dim && j.capacity != 0 && j.capacity * 4ull * dim <= kSideBySideBytes;
+    const uint64_t prb = (uint64_t)dim * (uint64_t)bits / 8u;
+    auto part = [&](const cnr_table_job &j, uint64_t k0, uint64_t m) {  // rows k0 .. k0 + m - 1 of j's list
+        RestoreJob a = {};
+        if (j.row_ids) {
+            a.table = j.table; a.n_rows = j.n_rows; a.row_ids = j.row_ids + k0;
+        } else {
+            a.table = j.table + k0 * dim; a.n_rows = j.n_rows - k0; a.row_ids = nullptr;
+        }
+        a.n_dev = j.n_dirty_dev; a.n_max = m;
+        a.packed = j.packed + k0 * prb; a.scale = j.scale + k0; a.bias = j.bias + k0;
+        return a;
     };
-    uint32_t n_small = 0;
-    for (uint32_t i = 0; i < n_jobs; ++i) n_small += small(jobs[i]) ? 1u : 0u;
-    const bool side_by_side = n_small >= 2;
-    if (side_by_side) {
-        RestoreBatch b = {};
-        uint32_t n = 0;
-        for (uint32_t i = 0; i <= n_jobs; ++i) {
-            if (i < n_jobs && small(jobs[i])) {
-                const cnr_table_job &j = jobs[i];
-                RestoreJob &a = b.job[n++];
-                a.table = j.table; a.n_rows = j.n_rows; a.row_ids = j.row_ids; a.n_dev = j.n_dirty_dev;
-                a.n_max = j.capacity; a.packed = j.packed; a.scale = j.scale; a.bias = j.bias;
-            }
-            if (n == CNR_MAX_BATCH || (i == n_jobs && n > 0)) {
+    // launches of up to CNR_MAX_BATCH small tables, then of large ones and slices, as for the encode
+    const bool tile_dim = dim == 16 || dim == 32 || dim == 64 || dim == 128 || dim == 256;
+    if (tile_dim) {
+        for (int large = 0; large < 2; ++large) {
+            RestoreBatch b = {};
+            uint32_t n = 0;
+            auto flush = [&]() -> cnr_status {
+                if (n == 0) return CNR_OK;
                 switch (bits) {
-                    case 2: launch_restore_tables<2>(ctx, s, dim, b, n); break;
-                    case 3: launch_restore_tables<3>(ctx, s, dim, b, n); break;
-                    case 4: launch_restore_tables<4>(ctx, s, dim, b, n); break;
-                    default: launch_restore_tables<8>(ctx, s, dim, b, n); break;
+                    case 2: launch_restore16_bits<2>(ctx, s, dim, b, n); break;
+                    case 3: launch_restore16_bits<3>(ctx, s, dim, b, n); break;
+                    case 4: launch_restore16_bits<4>(ctx, s, dim, b, n); break;
+                    default: launch_restore16_bits<8>(ctx, s, dim, b, n); break;
                 }
-                if ((st = cnr_launch_status(ctx)) != CNR_OK) return st;
                 n = 0;
+                return cnr_launch_status(ctx);
+            };
+            for (uint32_t i = 0; i < n_jobs; ++i) {
+                const cnr_table_job &j = jobs[i];
+                if (j.capacity == 0 || (j.capacity * 4ull * dim > kSideBySideBytes) != (large != 0)) continue;
+                const bool sliceable = !j.n_dirty_dev && (j.row_ids || j.capacity <= j.n_rows);
+                const uint64_t step = sliceable ? cnr_slice_rows(j.capacity, dim) : j.capacity;
+                for (uint64_t k0 = 0; k0 < j.capacity; k0 += step) {
+                    b.job[n++] = part(j, k0, j.capacity - k0 < step ? j.capacity - k0 : step);
+                    if (n == CNR_MAX_BATCH && (st = flush()) != CNR_OK) return st;
+                }
             }
+            if ((st = flush()) != CNR_OK) return st;
         }
+        return CNR_OK;
     }
-    for (uint32_t i = 0; i < n_jobs; ++i) {  // the others: one launch per table, back to back (as for the encode)
+    for (uint32_t i = 0; i < n_jobs; ++i) {  // other row lengths: one launch per table
         const cnr_table_job &j = jobs[i];
-        if (j.capacity == 0 || (side_by_side && small(j))) continue;
-        // slices when the host knows the length of the list, as for the encode
-        const bool sliceable = !j.n_dirty_dev && (j.row_ids || j.capacity <= j.n_rows);
-        const uint64_t step = sliceable ? cnr_slice_rows(j.capacity, dim) : j.capacity;
-        const uint64_t prb = (uint64_t)dim * (uint64_t)bits / 8u;
-        for (uint64_t k0 = 0; k0 < j.capacity; k0 += step) {
-            RestoreJob a = {};
-            if (j.row_ids) {
-                a.table = j.table; a.n_rows = j.n_rows; a.row_ids = j.row_ids + k0;
-            } else {
-                a.table = j.table + k0 * dim; a.n_rows = j.n_rows - k0; a.row_ids = nullptr;
-            }
-            a.n_dev = j.n_dirty_dev;
-            a.n_max = j.capacity - k0 < step ? j.capacity - k0 : step;
-            a.packed = j.packed + k0 * prb; a.scale = j.scale + k0; a.bias = j.bias + k0;
-            switch (bits) {
-                case 2: launch_restore<2>(ctx, s, dim, a); break;
-                case 3: launch_restore<3>(ctx, s, dim, a); break;
-                case 4: launch_restore<4>(ctx, s, dim, a); break;
-                default: launch_restore<8>(ctx, s, dim, a); break;
-            }
-            if ((st = cnr_launch_status(ctx)) != CNR_OK) return st;
+        if (j.capacity == 0) continue;
+        RestoreJob a = part(j, 0, j.capacity);
+        switch (bits) {
+            case 2: launch_restore<2>(ctx, s, dim, a); break;
+            case 3: launch_restore<3>(ctx, s, dim, a); break;
+            case 4: launch_restore<4>(ctx, s, dim, a); break;
+            default: launch_restore<8>(ctx, s, dim, a); break;
         }
+        if ((st = cnr_launch_status(ctx)) != CNR_OK) return st;
     }
     return CNR_OK;
 }
