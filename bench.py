@@ -41,8 +41,8 @@ ISSUE_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # one vector instruction per lane
 # per dirty row, valid only for the kernel source whose hash is recorded with it.
 TRAFFIC_PER_ROW = {
     # _kernel_hash() : (workload, bytes per dirty row)
-    # (2.000 * 190487.7 KiB FETCH_SIZE + 1.000 * 60727.9 KiB WRITE_SIZE) / 1,500,122 rows per launch
-    "97473828cfe1ac1e2857583f3b5bff6324d9656d03185199c05e9c3e58481b7c": ("cfg4/b4", 301.51),
+    # (2.000 * 1523629.9 KiB FETCH_SIZE + 1.000 * 480022.0 KiB WRITE_SIZE) / 12,000,978 rows per launch of 8 tables
+    "a2e6a8cd8520d9e7bb6344cdfd2a382c27d08e95db09fef0a95bfb9a9a5ff999": ("cfg4/b4", 300.97),
 }
 
 
@@ -56,9 +56,9 @@ def _kernel_hash() -> str:
     return hashlib.sha256("".join(code.split()).encode()).hexdigest()
 
 
-# The same for the restore kernel: (2.000 * 32257.6 KiB + 1.000 * 375046.6 KiB) / 1,500,122 rows
+# The same for the restore kernel: (2.000 * 257878.7 KiB + 1.000 * 3000264.0 KiB) / 12,000,978 rows
 RESTORE_TRAFFIC_PER_ROW = {
-    "4b1d7b36c2c70baaa9a814b48269fcb5dee1b6410b65f524be5a07bb9a7deb7f": ("cfg4/b4", 300.05),
+    "0e52e4246431f8c331da57ab97848044ce96d019c483ca3778fe5050bd57ce3b": ("cfg4/b4", 300.01),
 }
 
 
