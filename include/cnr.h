@@ -238,9 +238,11 @@ cnr_status cnr_select_greedy_params(cnr_ctx *ctx, const float *table, uint64_t n
  * does.  Where a call is short -- the per-iteration mark of a few ten thousand indices, the clear,
  * the compaction -- the jobs run side by side in one launch per kernel (and per CNR_MAX_BATCH
  * jobs), which is what the batch calls are for; the encode and restore kernels, which are bound by
- * memory bandwidth and sweep a table best with the whole GPU, are launched once per job, back to
- * back, except that the small tables of a call (rows of at most 64 MB at `capacity`) share one
- * launch.  Results are identical to those of the single-table calls.  Buffers of different jobs
+ * memory bandwidth and sweep a table best with the whole GPU, take up to CNR_MAX_BATCH jobs per
+ * launch as well and work through them one after the other without a gap (small tables, rows of at
+ * most 64 MB at `capacity`, and large ones in launches of their own kind; the greedy search and
+ * row lengths other than 16, 32, 64, 128 and 256 one job per launch).  Results are identical to
+ * those of the single-table calls.  Buffers of different jobs
  * of one call must not overlap (mark scratch included: one per job).  Every field has the meaning, layout and alignment of the
  * argument of the same name of the single-table call; a call reads only the fields listed for it.
  *   cnr_clear_bitmap_batch    bitmap, n_rows
