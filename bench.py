@@ -121,6 +121,9 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--no-host-copy", action="store_true", help="skip the chunked encode-to-host extra")
     ap.add_argument("--no-full", action="store_true", help="skip the full-checkpoint extra")
+    ap.add_argument("--iterations", type=int, default=0,
+                    help="look-up iterations per table of a Zipf workload (0 = the workload's own count, "
+                         "stopping early at the share of dirty rows it names)")
     ap.add_argument("--seed", type=int, default=4)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -154,15 +157,38 @@ def main() -> int:
     # per-table calls run one after the other and can share the scratch of the bulk mark
     # and the stale table that restore writes into; batched calls work on all tables at once
     shared_scratch = None if batched else P.TableCheckpointer.new_mark_scratch(w.n_rows, dev)
+    # Look-up streams first.  A Zipf workload runs its own number of iterations (rounds of 16 M look-ups
+    # for the until-coverage kind, at most 64) and stops early once the share of dirty rows it names is
+    # reached, measured with the library's own mark + compact on a probe bitmap; --iterations overrides
+    # the count (and then nothing stops early).  What was run is spelled out in config.workload.
+    iters_run, probe_dirty = [], []
     for ti in range(n_tables):
-        tables.append(synth.make_table(w, ti, args.seed, dev))
         if w.lookups == "bernoulli":
             batches = list(synth.lookup_batches(w, ti, args.seed, dev))
         else:
-            batches = list(synth.lookup_batches(w, ti, args.seed, dev, iterations=min(w.iterations or 8, 64)))
+            limit = args.iterations if args.iterations > 0 else (w.iterations or 64)
+            target = w.dirty_fraction * w.n_rows if (w.dirty_fraction and args.iterations <= 0) else None
+            probe = P.TableCheckpointer(ctx, w.n_rows, w.dim, device=dev, mark_scratch=shared_scratch)
+            probe.clear()
+            batches = []
+            for idx in synth.lookup_batches(w, ti, args.seed, dev, iterations=limit):
+                batches.append(idx)
+                if target is not None:
+                    probe.mark(idx)
+                    probe.compact()
+                    if int(probe.n_dirty.item()) >= target:
+                        break
+            del probe
+        iters_run.append(len(batches))
         streams.append(torch.cat([b.reshape(-1) for b in batches]))
+        del batches
+    for ti in range(n_tables):
+        tables.append(synth.make_table(w, ti, args.seed, dev))
         scratch = P.TableCheckpointer.new_mark_scratch(w.n_rows, dev) if batched else shared_scratch
-        ck = P.TableCheckpointer(ctx, w.n_rows, w.dim, device=dev, mark_scratch=scratch)
+        # room for 1.25 x the share of dirty rows the workload names (all rows when it names none)
+        cap = w.n_rows if not w.dirty_fraction or args.iterations > 0 else min(
+            w.n_rows, (int(1.25 * w.dirty_fraction * w.n_rows) + 1023) & ~1023)
+        ck = P.TableCheckpointer(ctx, w.n_rows, w.dim, capacity=cap, device=dev, mark_scratch=scratch)
         cks.append(ck)
         encs.append(ck.alloc_output(bits))
     stale = [torch.zeros((w.n_rows, w.dim), dtype=torch.float32, device=dev) for _ in range(n_tables if batched else 1)]
@@ -265,14 +291,22 @@ def main() -> int:
     stages["restore_hbm_GBps"] = round(res_bytes / (res_ms * 1e-3) / 1e9, 1)
     stages["mark_Gidx_per_s"] = round(sum(s.numel() for s in streams) / (stage_ms["mark"] * 1e-3) / 1e9, 2)
 
+    if w.lookups == "bernoulli":
+        lookups_desc = "Bernoulli(%.2f) row selection with repeats" % w.dirty_fraction
+    else:
+        per = "%d x %d" % (w.batch, w.pooling) if w.lookups == "zipf_batches" else "%d" % (streams[0].numel() // iters_run[0])
+        stop = ("--iterations %d" % args.iterations if args.iterations > 0 else
+                "stopped at %.0f%% coverage" % (100 * w.dirty_fraction) if w.dirty_fraction else "the workload's count")
+        lookups_desc = "Zipf(%.2f) look-ups, %d-%d iterations of %s per table (%s)" % (
+            w.zipf_s, min(iters_run), max(iters_run), per, stop)
     out = {
         "metric": "checkpoint encode GB/s (fp32 table bytes)", "value": round(value, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "%s: %d tables x %d rows x dim %d, %s values, %.1f%% dirty, %d-bit min/max "
+        "config": {"workload": "%s: %d tables x %d rows x dim %d, %s values, %s, %.1f%% dirty, %d-bit min/max "
                                "range, step = clear+mark+compact+encode+restore of all tables, %s"
-                               % (w.name, n_tables, w.n_rows, w.dim, w.values,
+                               % (w.name, n_tables, w.n_rows, w.dim, w.values, lookups_desc,
                                   100.0 * sum(n_dirty) / (n_tables * w.n_rows), bits,
                                   "one batched call per stage" if batched else "one call per table and stage"),
                    "dirty_rows": sum(n_dirty), "lookups_per_step": int(sum(s.numel() for s in streams)),

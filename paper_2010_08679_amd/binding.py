@@ -77,15 +77,21 @@ _lock = threading.Lock()
 _lib = None
 
 
+def ensure_built() -> str:
+    """Path of a libcnr.so that matches the sources in this tree: compiles it when there is none, or
+    when the one there was built from other sources (a stale library would be tested silently)."""
+    if _build.is_stale():
+        _build.build_lib(force=True)
+    return _build.LIB
+
+
 def load() -> ctypes.CDLL:
-    """Loads libcnr.so, compiling it first only when no built library is there."""
+    """Loads libcnr.so, compiling it first only when no up-to-date library is there."""
     global _lib
     with _lock:
         if _lib is not None:
             return _lib
-        if not os.path.exists(_build.LIB):
-            _build.build_lib(force=True)
-        lib = ctypes.CDLL(_build.LIB)
+        lib = ctypes.CDLL(ensure_built())
         vp, u64, u32, i32, f32 = (ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int,
                                   ctypes.c_float)
         sz = ctypes.c_size_t

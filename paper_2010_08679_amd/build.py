@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import glob
+import hashlib
 import os
 import subprocess
 
@@ -9,6 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcnr.so")
+STAMP = LIB + ".srchash"   # hash of what LIB was built from, written next to it
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -28,12 +30,30 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
+def dependencies():
+    return sources() + sorted(glob.glob(os.path.join(CSRC, "*.h"))) + [os.path.join(ROOT, "include", "cnr.h")]
+
+
+def source_hash() -> str:
+    """Hash of the compiler flags and of every file the library is built from."""
+    h = hashlib.sha256(" ".join(HIPCC_FLAGS).encode())
+    for path in dependencies():
+        h.update(os.path.basename(path).encode())
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
 def is_stale() -> bool:
+    """True when there is no built library, or it was built from other sources than the ones here:
+    by the hash recorded at build time, or, where that record is missing, by modification times."""
     if not os.path.exists(LIB):
         return True
+    if os.path.exists(STAMP):
+        with open(STAMP, "r") as f:
+            return f.read().strip() != source_hash()
     t = os.path.getmtime(LIB)
-    deps = sources() + glob.glob(os.path.join(CSRC, "*.h")) + [os.path.join(ROOT, "include", "cnr.h")]
-    return any(os.path.getmtime(d) > t for d in deps)
+    return any(os.path.getmtime(d) > t for d in dependencies())
 
 
 def build_lib(force: bool = True, verbose: bool = False) -> str:
@@ -45,8 +65,11 @@ def build_lib(force: bool = True, verbose: bool = False) -> str:
     cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", tmp, *sources()]
     if verbose:
         print(" ".join(cmd), flush=True)
+    built_from = source_hash()
     subprocess.check_call(cmd)
     os.replace(tmp, LIB)
+    with open(STAMP, "w") as f:
+        f.write(built_from + "\n")
     return LIB
 
 

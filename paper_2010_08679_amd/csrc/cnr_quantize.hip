@@ -504,8 +504,16 @@ __global__ void __launch_bounds__(kBlock) quantize_greedy_kernel(const QuantArgs
         };
         const float s0 = (hi - lo) * INV_QMAX;
         const bool odd_scale = s0 != 0.0f && !(s0 >= 0x1p-100f && s0 <= 0x1p100f);
+        // The bounds are moved by cumulative fp32 additions, each rounded to the spacing of the bounds'
+        // magnitude, so after k moves a bound sits up to k/2 spacings off the exact lattice.  Where the
+        // step is not many spacings wide (a row whose span is tiny against its magnitude) a candidate
+        // range can close or turn inside out before the search ends, and there the median-of-three
+        // clip of the fast sequence is no longer min(max(x, lo), hi): such rows take the sequence as
+        // F_Q is written.  Safe when range >= num_bins^2 spacings (twice the drift num_bins moves allow).
+        const float mag = fmaxf(fabsf(lo), fabsf(hi));
+        const bool narrow = hi != lo && (hi - lo) < a.num_bins_f * a.num_bins_f * (mag * 0x1p-23f);
         // the last candidates are up to num_bins times narrower than the first
-        if (__builtin_amdgcn_ballot_w64(odd_scale) != 0 || a.num_bins_f > 0x1p20f)
+        if (__builtin_amdgcn_ballot_w64(odd_scale || narrow) != 0 || a.num_bins_f > 0x1p20f)
             search(std::false_type{});
         else
             search(std::true_type{});

@@ -45,7 +45,7 @@ def _encoded_sample(enc, pos, dim, bits):
     return out
 
 
-def _check_table(ctx, w, table, batches, bits_list, greedy=None, sample=100_000, greedy_sample=4_000,
+def _check_table(ctx, w, table, batches, bits_list, greedy=None, sample=100_000, greedy_sample=None,
                  scratch=None, what=""):
     n_rows, dim = table.shape
     ck = P.TableCheckpointer(ctx, n_rows, dim, device=DEV, mark_scratch=scratch)
@@ -65,7 +65,7 @@ def _check_table(ctx, w, table, batches, bits_list, greedy=None, sample=100_000,
     pos = _sample_positions(n, sample, 1)
     rows_t = table.index_select(0, torch.from_numpy(ids[pos].astype(np.int64)).to(DEV))
     rows = rows_t.cpu().numpy()
-    stale = torch.full_like(table, -3.0) if table.numel() * 4 < 8e9 else None
+    stale = torch.full_like(table, -3.0)      # one reusable stale table, whatever the size (up to 20.5 GB)
     for bits in bits_list:
         enc = ck.alloc_output(bits, want_range=True)
         for _, call in ck.prepare_step(torch.zeros(1, dtype=torch.int64, device=DEV), table, enc)[3:]:
@@ -74,16 +74,19 @@ def _check_table(ctx, w, table, batches, bits_list, greedy=None, sample=100_000,
         got = _encoded_sample(enc, pos, dim, bits)
         ora = O.quantize_rows(rows, None, bits, n_threads=8)
         compare_quantized(rows, got, ora, bits, what="%s b%d" % (what, bits))
-        if stale is not None:
-            ck.restore(stale, enc)
-            torch.cuda.synchronize()
-            back = stale.index_select(0, torch.from_numpy(ids[pos].astype(np.int64)).to(DEV)).cpu().numpy()
-            assert np.array_equal(back, O.dequantize(got["codes"], got["scale"], got["bias"])), what + " restore"
-            untouched = np.setdiff1d(np.arange(0, n_rows, max(1, n_rows // 50_000)), ids)
-            assert torch.all(stale.index_select(0, torch.from_numpy(untouched).to(DEV)) == -3.0)
-            stale.fill_(-3.0)
+        ck.restore(stale, enc)
+        torch.cuda.synchronize()
+        back = stale.index_select(0, torch.from_numpy(ids[pos].astype(np.int64)).to(DEV)).cpu().numpy()
+        assert np.array_equal(back, O.dequantize(got["codes"], got["scale"], got["bias"])), what + " restore"
+        untouched = np.setdiff1d(np.arange(0, n_rows, max(1, n_rows // 50_000)), ids)
+        assert torch.all(stale.index_select(0, torch.from_numpy(untouched).to(DEV)) == -3.0)
+        # every listed row was written and no other: the restored table differs from the stale fill in
+        # exactly the dirty rows (a row of a real table never de-quantizes to -3.0 throughout)
+        assert int((stale != -3.0).any(dim=1).sum().item()) == n, what + " rows written"
+        stale.fill_(-3.0)
         if greedy is not None:
-            gpos = pos[:: max(1, len(pos) // greedy_sample)]
+            # the whole sample when greedy_sample is None (>= 100,000 rows: enough to resolve the 1e-4 bars)
+            gpos = pos if greedy_sample is None else pos[:: max(1, len(pos) // greedy_sample)]
             ck.encode(table, enc, mode=P.CNR_RANGE_GREEDY, greedy=greedy)
             torch.cuda.synchronize()
             sel = np.searchsorted(pos, gpos)
@@ -100,7 +103,7 @@ def test_cfg4_table_full_size(ctx):
     table = synth.make_table(w, 0, 4, DEV)
     scratch = P.TableCheckpointer.new_mark_scratch(w.n_rows, DEV)
     _check_table(ctx, w, table, list(synth.lookup_batches(w, 0, 4, DEV)), (4,), greedy=(w.num_bins, w.ratio),
-                 scratch=scratch, what="cfg4 table 0")
+                 sample=125_000, scratch=scratch, what="cfg4 table 0")
     assert not scratch.any()
 
 

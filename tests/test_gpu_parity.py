@@ -7,7 +7,8 @@ import torch
 import oracle as O
 import paper_2010_08679_amd as P
 from paper_2010_08679_amd import synth
-from util_parity import (GpuTable, compare_quantized, gpu_encode_all_outputs, u32)
+from util_parity import (CODE_MISMATCH_FRACTION, GpuTable, assert_near_ties, compare_quantized,
+                         gpu_encode_all_outputs, u32)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -277,12 +278,10 @@ def test_special_rows(ctx):
             for k in ("scale", "bias", "row_min", "row_max"):
                 assert np.array_equal(got[k].view(np.uint32), ora[k].view(np.uint32)), (bits, mode, k)
             # codes come from a reciprocal multiply on the GPU and a division in the oracle: they may
-            # differ by one step where the quotient falls within rounding distance of a half-integer
+            # differ by one step, and only where the quotient is shown to sit at a half-integer (rows 2
+            # and 7 are built to put many quotients exactly there)
             diff = np.abs(got["codes"].astype(np.int16) - ora["codes"].astype(np.int16))
-            assert diff.max() <= 1 and np.count_nonzero(diff) <= 2, (bits, mode, np.argwhere(diff))
-            for r, e in np.argwhere(diff):
-                t = (np.float64(rows[r, e]) - np.float64(ora["bias"][r])) / np.float64(ora["scale"][r])
-                assert abs(abs(t - np.floor(t)) - 0.5) < 1e-5, (bits, mode, r, e, t)
+            assert_near_ties(rows, ora, diff, what="special rows b%d mode %d" % (bits, mode))
 
 
 @pytest.mark.parametrize("bits", (2, 3, 4))
@@ -303,6 +302,35 @@ def test_greedy_encode(ctx, bits, dim, params):
     # the search must have moved a fair share of the outlier rows off their min/max range
     plain = O.quantize_rows(gt.host, ids, bits)
     assert np.mean(got["scale"] < plain["scale"]) > 0.2
+
+
+@pytest.mark.parametrize("dim", [64, 128, 16, 40])
+def test_greedy_on_rows_spanning_a_few_float_spacings(ctx, dim):
+    # rows a few representable values wide around a large magnitude: the cumulative bounds of the
+    # search move by whole spacings and late candidate ranges close or turn inside out; the result
+    # must still be the oracle's, bit for bit
+    rng = np.random.default_rng(dim)
+    blocks = []
+    for mag in (1.0, 1000.0, 3e-3, -7.5):
+        base = np.float32(mag)
+        u = np.spacing(np.abs(base))
+        for span in (1, 2, 4, 7, 20, 100, 3000, 40000):
+            x = (base + u * rng.integers(0, span + 1, size=(24, dim)).astype(np.float32)).astype(np.float32)
+            x[:, 0], x[:, 1] = base, base + u * span
+            blocks.append(x)
+    blocks.append(np.float32(rng.normal(0, 0.02, size=(40, dim))))     # ordinary rows in the same waves
+    rows = np.concatenate(blocks)[rng.permutation(sum(b.shape[0] for b in blocks))]
+    gt = GpuTable(ctx, torch.from_numpy(rows).to(DEV))
+    n = rows.shape[0]
+    for bits in (2, 3, 4):
+        if (dim * bits) % 8:
+            continue
+        for params in ((3, 1.0), (6, 1.0), (25, 1.0), (100, 1.0), (45, 0.6)):
+            got = gpu_encode_all_outputs(gt, bits, mode=P.CNR_RANGE_GREEDY, greedy=params, row_ids=None, n=n)
+            ora = O.quantize_rows(rows, None, bits, mode=O.RANGE_GREEDY, num_bins=params[0], ratio=params[1])
+            for k in ("scale", "bias", "row_min", "row_max"):
+                assert np.array_equal(got[k].view(np.uint32), ora[k].view(np.uint32)), (bits, params, k)
+            assert np.array_equal(got["codes"], ora["codes"]), (bits, params)
 
 
 def test_greedy_zero_ratio_is_minmax(ctx):
@@ -777,7 +805,7 @@ def test_seeded_random_cases_against_the_oracle(ctx):
     # width, range mode, list length, with or without a row list, device-side count below n_max
     rng = np.random.default_rng(20240607)
     dims = [4, 8, 16, 24, 32, 40, 64, 72, 96, 128, 160, 256, 264, 512, 1024]
-    n_cases = 0
+    n_cases = n_diff = n_elements = 0
     for case in range(160):
         dim = int(rng.choice(dims))
         bits = int(rng.choice(BITS))
@@ -811,10 +839,15 @@ def test_seeded_random_cases_against_the_oracle(ctx):
         assert np.array_equal(got["scale"].view(np.uint32), ora["scale"].view(np.uint32)), what
         assert np.array_equal(got["bias"].view(np.uint32), ora["bias"].view(np.uint32)), what
         diff = np.abs(got["codes"].astype(np.int16) - ora["codes"].astype(np.int16))
-        assert diff.max(initial=0) <= 1 and np.count_nonzero(diff) <= max(1, diff.size // 2000), what
+        # cases are far too small for a share of 1e-4 to allow one element: every differing code has to
+        # be a proven near-tie, and the share is checked over the whole sweep
+        n_diff += assert_near_ties(host[ids_np[:n_live].astype(np.int64)], ora, diff, what=what)
+        n_elements += diff.size
         want = np.full_like(host, -3.0)
         O.restore_rows(want, ids_np[:n_live], bits, packed.cpu().numpy()[:n_live * prb].reshape(n_live, prb), got["scale"], got["bias"])
         assert np.array_equal(stale.cpu().numpy(), want), what
         n_cases += 1
     assert n_cases > 100
+    assert n_diff <= CODE_MISMATCH_FRACTION * n_elements, (n_diff, n_elements)
+    print("random sweep: %d cases, %d of %d codes differ (all near-ties)" % (n_cases, n_diff, n_elements), flush=True)
     _poll_clean(ctx)

@@ -3,6 +3,7 @@ arithmetic agrees with the oracle's, the binding refuses what it must, and the p
 route into the oracle.  No kernel is launched here."""
 import os
 import re
+import time
 
 import numpy as np
 import pytest
@@ -134,3 +135,46 @@ def test_bit_width_selection_equals_the_oracle():
     for expected in list(range(0, 30)) + [99, 100, 101, 10_000]:
         for observed in (0, 1, expected, expected + 1):
             assert P.cnr_select_bits(expected, observed) == O.select_bits(expected, observed)
+
+
+def test_a_library_built_from_other_sources_is_rebuilt_before_loading(tmp_path, monkeypatch):
+    # The built library ships to the GPU machine with the tree; one left over from older kernels must
+    # not be loaded as if it were current.  Works on a copy of the sources and never compiles.
+    import shutil
+    from paper_2010_08679_amd import build as B
+    csrc = tmp_path / "csrc"
+    shutil.copytree(B.CSRC, csrc)
+    lib = tmp_path / "libcnr.so"
+    monkeypatch.setattr(B, "CSRC", str(csrc))
+    monkeypatch.setattr(B, "LIB", str(lib))
+    monkeypatch.setattr(B, "STAMP", str(lib) + ".srchash")
+    built = []
+
+    def fake_build(force=True, verbose=False):
+        built.append(B.source_hash())
+        lib.write_bytes(b"not a library")
+        with open(B.STAMP, "w") as f:
+            f.write(built[-1] + "\n")
+        return str(lib)
+    monkeypatch.setattr(B, "build_lib", fake_build)
+
+    assert B.is_stale()                                        # nothing built yet
+    assert binding.ensure_built() == str(lib) and len(built) == 1
+    assert not B.is_stale()
+    binding.ensure_built()
+    assert len(built) == 1                                     # up to date: loaded as it is
+    src = sorted(csrc.glob("*.hip"))[0]
+    os.utime(src, (time.time() + 100, time.time() + 100))
+    assert not B.is_stale()                                    # same content, whatever the clock says
+    src.write_text(src.read_text() + "\n// changed\n")
+    assert B.is_stale()
+    binding.ensure_built()
+    assert len(built) == 2 and not B.is_stale()
+    # without the recorded hash (a library that arrived on its own) modification times decide
+    os.remove(B.STAMP)
+    os.utime(lib, (time.time() + 200, time.time() + 200))
+    assert not B.is_stale()
+    os.utime(src, (time.time() + 300, time.time() + 300))      # a source touched after the build
+    assert B.is_stale()
+    binding.ensure_built()
+    assert len(built) == 3

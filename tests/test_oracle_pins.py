@@ -435,6 +435,37 @@ def test_greedy_follows_an_independently_evaluated_path():
     assert agree >= 8
 
 
+def test_greedy_on_rows_whose_span_is_a_few_float_spacings():
+    # Rows that span only a few representable values around a large magnitude: the step is under one
+    # spacing, the cumulative bounds move by whole spacings, and late candidate ranges are empty or
+    # inverted.  Whatever such candidates score, iteration 0 (the un-shrunk range) is a candidate, so
+    # the result can never be worse than plain min/max, the stored range stays inside the row's, and
+    # the stored scale is never negative.  Errors are evaluated here with numpy.
+    rng = np.random.default_rng(7)
+    for mag in (1.0, 1000.0, 3e-3):
+        base = np.float32(mag)
+        u = np.spacing(base)
+        for span in (2, 4, 7, 20, 100):
+            x = (base + u * rng.integers(0, span + 1, size=(64, 16)).astype(np.float32)).astype(np.float32)
+            x[:, 0], x[:, 1] = base, base + u * span
+            for num_bins in (3, 6, 25):
+                for bits in (2, 3, 4):
+                    g = O.quantize_rows(x, None, bits, mode=O.RANGE_GREEDY, num_bins=num_bins, ratio=1.0)
+                    p = O.quantize_rows(x, None, bits)
+
+                    def err(q):
+                        # de-quantized as a resume would see it: fp32 product, then fp32 sum (at this
+                        # scale the two roundings are the error)
+                        back = q["scale"][:, None] * q["codes"].astype(np.float32) + q["bias"][:, None]
+                        assert back.dtype == np.float32
+                        return np.linalg.norm(x.astype(np.float64) - back.astype(np.float64), axis=1)
+                    assert np.all(g["scale"] >= 0)
+                    assert np.all(g["bias"] >= p["row_min"])
+                    hi = g["bias"].astype(np.float64) + g["scale"].astype(np.float64) * ((1 << bits) - 1)
+                    assert np.all(hi <= p["row_max"].astype(np.float64) + u)
+                    assert np.all(err(g) <= err(p) * (1 + 1e-9))
+
+
 def test_greedy_beats_minmax_on_outlier_rows_more_at_low_bits():
     # Approach 3's motivation: one element of large magnitude inflates the scale.  Section 5.2
     # also reports a larger gain at lower bit-widths.

@@ -18,6 +18,7 @@ import oracle as O
 import paper_2010_08679_amd as P
 
 CODE_MISMATCH_FRACTION = 1e-4
+OFF_PATH_ROW_FRACTION = 1e-4   # greedy rows whose search left the oracle's path at a near-tie
 L2_REL_TOL = 1e-6
 
 
@@ -57,28 +58,43 @@ def compare_quantized(host_rows: np.ndarray, gpu: dict, ora: dict, bits: int, *,
         assert ulp_distance(gpu["bias"], ora["bias"]).max(initial=0) <= 1, what + " bias beyond 1 ulp"
         same_range = np.ones(n, dtype=bool)
     else:
-        # a greedy search may leave the oracle's path at a numerical near-tie between two candidate
-        # ranges; such rows are judged by their error alone and must stay rare
+        # A greedy search may leave the oracle's path at a numerical near-tie between two candidate
+        # ranges.  Such rows must stay rare (the same share the codes are allowed), their codes are not
+        # comparable one by one (another range means another grid), and they are held to the error bar
+        # like every other row.
         same_range = (ulp_distance(gpu["scale"], ora["scale"]) <= 1) & (ulp_distance(gpu["bias"], ora["bias"]) <= 1)
-        assert np.mean(~same_range) <= 1e-3, "%s: %d of %d rows took another greedy path" % (
+        assert np.mean(~same_range) <= OFF_PATH_ROW_FRACTION, "%s: %d of %d rows took another greedy path" % (
             what, int((~same_range).sum()), n)
     diff = np.abs(gpu["codes"].astype(np.int16) - ora["codes"].astype(np.int16))
     assert diff[same_range].max(initial=0) <= 1, what + " code off by more than 1 LSB"
-    frac = float(np.count_nonzero(diff[same_range])) / max(1, int(same_range.sum()) * dim)
+    frac = float(np.count_nonzero(diff[same_range])) / max(1, n * dim)
     assert frac <= CODE_MISMATCH_FRACTION, "%s: %.3g of the codes differ" % (what, frac)
     assert gpu["codes"].max(initial=0) <= (1 << bits) - 1
-    # per-row l2 error of what would be restored
+    # per-row l2 error of what would be restored: every row, whichever range it took
     e_gpu, _ = O.row_l2(host_rows, O.dequantize(gpu["codes"], gpu["scale"], gpu["bias"]))
     e_ora, _ = O.row_l2(host_rows, O.dequantize(ora["codes"], ora["scale"], ora["bias"]))
     rel = np.abs(e_gpu - e_ora) / np.maximum(e_ora, np.finfo(np.float64).tiny)
     rel[(e_gpu == 0) & (e_ora == 0)] = 0
-    if greedy:
-        rel = rel[same_range]
-    assert rel.max(initial=0) <= L2_REL_TOL, "%s: per-row l2 error off by %.3g relative" % (what, rel.max())
+    assert rel.max(initial=0) <= L2_REL_TOL, "%s: per-row l2 error off by %.3g relative (row %d)" % (
+        what, rel.max(), int(rel.argmax()))
     print("%s: %d rows x %d, codes differing %.2e, rows off the oracle's greedy path %d, "
           "max relative l2-error difference %.1e" % (what, n, dim, frac, int((~same_range).sum()),
                                                      rel.max(initial=0)), flush=True)
     return frac
+
+
+def assert_near_ties(rows: np.ndarray, ora: dict, diff: np.ndarray, what=""):
+    """Every element whose code differs (by one step) must be a proven near-tie: the exact quotient
+    (x - lo) / scale lies within a few fp32 roundings of a half-integer, where the order in which a
+    correct implementation rounds (divide, or multiply by the reciprocal) decides the code.  The
+    allowance: half an ulp for the subtraction, half for the division or 1.5 for the reciprocal
+    product, all relative to the quotient, so 4 ulp of it covers both sides."""
+    for r, e in np.argwhere(diff):
+        assert diff[r, e] == 1, (what, r, e)
+        t = (np.float64(rows[r, e]) - np.float64(ora["bias"][r])) / np.float64(ora["scale"][r])
+        tol = 4.0 * float(np.spacing(np.float32(max(abs(t), 0.5))))
+        assert abs(abs(t - np.floor(t)) - 0.5) <= tol, (what, r, e, t)
+    return int(np.count_nonzero(diff))
 
 
 def gpu_encode_all_outputs(gt: GpuTable, bits: int, mode=P.CNR_RANGE_MINMAX, greedy=None,
