@@ -18,6 +18,7 @@
  *                      back over a stale baseline table (Sections 5.1 and 6.2)
  * Around the path:
  *   cnr_*_batch        every stage for several tables per call (Sections 2.1, 4.1)
+ *   cnr_compact_dirty_noalloc   the compaction for callers that cannot allocate: no scratch argument
  *   cnr_quant_error    the l2 error metric of Section 5.2
  *   cnr_select_greedy_params   greedy parameters by profiling a sample (Section 5.2)
  *   cnr_host_writer_*, cnr_encode_to_host   chunked encode into host memory with the copy of one
@@ -78,7 +79,8 @@ typedef enum {
     CNR_E_CAPACITY = 5,    /* device: more dirty rows than `capacity` (poll only) */
     CNR_E_INDEX_RANGE = 6, /* device: look-up indices outside [0, n_rows) were skipped (poll only) */
     CNR_E_ROW_ID = 7,      /* device: a row id >= n_rows was skipped (poll only) */
-    CNR_E_HIP = 8          /* a HIP runtime call failed; see cnr_last_hip_error */
+    CNR_E_HIP = 8,         /* a HIP runtime call failed; see cnr_last_hip_error */
+    CNR_E_TOO_LARGE = 9    /* a size beyond the fixed maximum of an entry point that allocates nothing */
 } cnr_status;
 
 typedef enum { CNR_IDX_I32 = 0, CNR_IDX_I64 = 1 } cnr_index_type;
@@ -155,6 +157,23 @@ cnr_status cnr_mark_touched(cnr_ctx *ctx, uint32_t *bitmap, uint64_t n_rows, con
 cnr_status cnr_compact_dirty(cnr_ctx *ctx, const uint32_t *bitmap, uint64_t n_rows,
                              uint32_t *row_ids, uint64_t capacity, uint64_t *n_dirty_dev,
                              void *scratch, void *stream);
+
+/* cnr_compact_dirty for callers that cannot allocate device memory and have none to pass as scratch:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * results and device-side conditions as cnr_compact_dirty, minus `scratch`: the per-tile counts of the
+ * compaction go to a fixed array that is part of the loaded library's device image
+ * (CNR_NOALLOC_SCRATCH_BYTES on every GPU the library runs on, held until the process ends), whose
+ * address on the context's device cnr_create looked up once.  The call allocates and frees nothing.
+ *   n_rows   at most CNR_NOALLOC_MAX_ROWS, else CNR_E_TOO_LARGE is returned and nothing is launched
+ * Every context of one GPU shares that GPU's array: calls that overlap on one GPU (two streams, two
+ * contexts, two host threads) race and give wrong lists; calls on one stream are ordered and safe.
+ * The array keeps the last call's contents; nothing in it has to start at zero (the count kernel
+ * writes every entry the scatter kernel reads). */
+#define CNR_NOALLOC_MAX_ROWS (1ull << 30)
+#define CNR_NOALLOC_SCRATCH_BYTES ((CNR_NOALLOC_MAX_ROWS / 16384u) * 4u + 8u)
+cnr_status cnr_compact_dirty_noalloc(cnr_ctx *ctx, const uint32_t *bitmap, uint64_t n_rows,
+                                     uint32_t *row_ids, uint64_t capacity, uint64_t *n_dirty_dev,
+                                     void *stream);
 
 /* ---- quantization (Section 5.2) ---------------------------------------------------------- */
 

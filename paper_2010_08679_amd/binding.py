@@ -19,7 +19,8 @@ from . import build as _build
 
 CNR_OK = 0
 CNR_E_INVALID, CNR_E_BITS, CNR_E_DIM, CNR_E_ALIGN = 1, 2, 3, 4
-CNR_E_CAPACITY, CNR_E_INDEX_RANGE, CNR_E_ROW_ID, CNR_E_HIP = 5, 6, 7, 8
+CNR_E_CAPACITY, CNR_E_INDEX_RANGE, CNR_E_ROW_ID, CNR_E_HIP, CNR_E_TOO_LARGE = 5, 6, 7, 8, 9
+CNR_NOALLOC_MAX_ROWS = 1 << 30
 CNR_IDX_I32, CNR_IDX_I64 = 0, 1
 CNR_RANGE_MINMAX, CNR_RANGE_GREEDY, CNR_RANGE_SYMMETRIC = 0, 1, 2
 CNR_FLAG_CAPACITY, CNR_FLAG_ROW_ID = 1, 2
@@ -30,7 +31,7 @@ CNR_MAX_BATCH = 16
 EXPORTS = (
     "cnr_create", "cnr_destroy", "cnr_bitmap_words", "cnr_packed_row_bytes", "cnr_scratch_bytes",
     "cnr_mark_scratch_bytes",
-    "cnr_greedy_iterations", "cnr_clear_bitmap", "cnr_mark_touched", "cnr_compact_dirty",
+    "cnr_greedy_iterations", "cnr_clear_bitmap", "cnr_mark_touched", "cnr_compact_dirty", "cnr_compact_dirty_noalloc",
     "cnr_quantize_rows", "cnr_pack", "cnr_restore_rows", "cnr_quant_error", "cnr_poll_errors", "cnr_status_str",
     "cnr_last_hip_error", "cnr_full_checkpoint_due", "cnr_policy_init", "cnr_policy_next", "cnr_select_bits",
     "cnr_clear_bitmap_batch", "cnr_mark_touched_batch", "cnr_compact_dirty_batch", "cnr_quantize_rows_batch",
@@ -106,6 +107,7 @@ def load() -> ctypes.CDLL:
             "cnr_clear_bitmap": (i32, [vp, vp, u64, vp]),
             "cnr_mark_touched": (i32, [vp, vp, u64, vp, u64, i32, vp, vp]),
             "cnr_compact_dirty": (i32, [vp, vp, u64, vp, u64, vp, vp, vp]),
+            "cnr_compact_dirty_noalloc": (i32, [vp, vp, u64, vp, u64, vp, vp]),
             "cnr_quantize_rows": (i32, [vp, vp, u64, u32, vp, vp, u64, i32, i32,
                                         ctypes.POINTER(cnr_greedy_params), vp, vp, vp, vp, vp, vp, vp]),
             "cnr_pack": (i32, [vp, vp, vp, u64, u32, i32, vp, vp]),
@@ -240,6 +242,15 @@ def cnr_compact_dirty(ctx, bitmap, n_rows: int, row_ids, capacity: int, n_dirty_
                                     _dev(n_dirty_dev, U64, "n_dirty_dev"),
                                     _dev(scratch, scratch.dtype, "scratch"), _stream(stream)),
            "cnr_compact_dirty")
+
+
+def cnr_compact_dirty_noalloc(ctx, bitmap, n_rows: int, row_ids, capacity: int, n_dirty_dev, stream=None) -> None:
+    if row_ids is not None and row_ids.numel() < capacity:
+        raise ValueError("row_ids shorter than capacity")
+    _check(load().cnr_compact_dirty_noalloc(ctx, _dev(bitmap, U32, "bitmap"), n_rows,
+                                            _dev(row_ids, U32, "row_ids"), capacity,
+                                            _dev(n_dirty_dev, U64, "n_dirty_dev"), _stream(stream)),
+           "cnr_compact_dirty_noalloc")
 
 
 def cnr_quantize_rows(ctx, table, n_rows: int, dim: int, row_ids, n_dev, n_max: int, bits: int,

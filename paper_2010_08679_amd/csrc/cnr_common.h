@@ -19,6 +19,7 @@ struct cnr_ctx {
     cnr_dev_errors *dev_err;   // device
     cnr_dev_errors *host_err;  // pinned host mirror used by cnr_poll_errors
     double *host_scalar;       // pinned host double (behind host_err) for results read back one at a time
+    void *static_scratch;      // this device's copy of the library's fixed compaction scratch
     int last_hip_error;
 };
 
@@ -35,6 +36,9 @@ static inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream
 cnr_status cnr_enter(cnr_ctx *ctx);
 // Records a HIP failure in the context and maps it to a status.
 cnr_status cnr_hip_status(cnr_ctx *ctx, hipError_t e);
+// Looks up, on ctx's device (which must be current), the address of the fixed scratch array that
+// cnr_compact_dirty_noalloc uses, and keeps it in the context.
+cnr_status cnr_bind_static_scratch(cnr_ctx *ctx);
 // Status of the launch that was just enqueued.
 static inline cnr_status cnr_launch_status(cnr_ctx *ctx) { return cnr_hip_status(ctx, hipGetLastError()); }
 

@@ -39,6 +39,7 @@ cnr_status cnr_create(cnr_ctx **out, int device) {
     ctx->dev_err = nullptr;
     ctx->host_err = nullptr;
     ctx->host_scalar = nullptr;
+    ctx->static_scratch = nullptr;
     hipError_t e = hipSetDevice(device);
     hipDeviceProp_t prop;
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, device);
@@ -51,6 +52,7 @@ cnr_status cnr_create(cnr_ctx **out, int device) {
         if (e == hipSuccess) ctx->host_scalar = reinterpret_cast<double *>(ctx->host_err + 1);
     }
     if (e == hipSuccess) e = hipMemset(ctx->dev_err, 0, sizeof(cnr_dev_errors));
+    if (e == hipSuccess && cnr_bind_static_scratch(ctx) != CNR_OK) e = (hipError_t)ctx->last_hip_error;
     if (e != hipSuccess) {
         if (ctx->dev_err) (void)hipFree(ctx->dev_err);
         if (ctx->host_err) (void)hipHostFree(ctx->host_err);
@@ -127,6 +129,7 @@ const char *cnr_status_str(cnr_status s) {
         case CNR_E_INDEX_RANGE: return "look-up indices outside the table were skipped";
         case CNR_E_ROW_ID: return "row id outside the table was skipped";
         case CNR_E_HIP: return "HIP runtime error";
+        case CNR_E_TOO_LARGE: return "size beyond the fixed maximum of a call that allocates nothing";
     }
     return "unknown status";
 }

@@ -8,6 +8,12 @@
 
 #include <type_traits>
 
+// Per-tile counts of cnr_compact_dirty_noalloc: a fixed array in the library's device image instead
+// of a buffer from the caller.  Every GPU that loads the library holds its own copy at its own
+// address.  In host code this name is only a handle for hipGetSymbolAddress, never a device address:
+// kernels get the looked-up pointer (cnr_ctx::static_scratch) as an argument like any other scratch.
+static __device__ __align__(256) uint32_t scratch[CNR_NOALLOC_SCRATCH_BYTES / sizeof(uint32_t)];
+
 namespace {
 
 struct TrackJob {
@@ -587,4 +593,26 @@ cnr_status cnr_compact_dirty(cnr_ctx *ctx, const uint32_t *bitmap, uint64_t n_ro
     return cnr_compact_dirty_batch(ctx, &j, 1, stream);
 }
 
+cnr_status cnr_compact_dirty_noalloc(cnr_ctx *ctx, const uint32_t *bitmap, uint64_t n_rows,
+                                     uint32_t *row_ids, uint64_t capacity, uint64_t *n_dirty_dev,
+                                     void *stream) {
+    if (!ctx) return CNR_E_INVALID;
+    if (n_rows > CNR_NOALLOC_MAX_ROWS) return CNR_E_TOO_LARGE;
+    static_assert(CNR_NOALLOC_SCRATCH_BYTES >= (CNR_NOALLOC_MAX_ROWS / kCompactRowsPerBlock) * sizeof(uint32_t) + 8u,
+                  "the fixed scratch holds one count per tile of the largest table");
+    if (!ctx->static_scratch || cnr_scratch_bytes(n_rows) > CNR_NOALLOC_SCRATCH_BYTES) return CNR_E_INVALID;
+    // from here on the plain call with this device's array as its scratch: argument checks and two
+    // kernel launches, no allocation
+    return cnr_compact_dirty(ctx, bitmap, n_rows, row_ids, capacity, n_dirty_dev, ctx->static_scratch, stream);
+}
+
 }  // extern "C"
+
+cnr_status cnr_bind_static_scratch(cnr_ctx *ctx) {
+    void *p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return cnr_hip_status(ctx, e);
+    if (!p) return cnr_hip_status(ctx, hipErrorInvalidSymbol);
+    ctx->static_scratch = p;
+    return CNR_OK;
+}

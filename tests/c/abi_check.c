@@ -18,7 +18,8 @@ int main(void) {
         (fn)cnr_compact_dirty_batch, (fn)cnr_quantize_rows_batch, (fn)cnr_restore_rows_batch,
         (fn)cnr_host_writer_device_bytes, (fn)cnr_host_writer_create, (fn)cnr_host_writer_destroy,
         (fn)cnr_encode_to_host, (fn)cnr_host_writer_wait, (fn)cnr_select_scratch_bytes,
-        (fn)cnr_select_greedy_params, (fn)cnr_select_bits, (fn)cnr_restore_from_host};
+        (fn)cnr_select_greedy_params, (fn)cnr_select_bits, (fn)cnr_restore_from_host,
+        (fn)cnr_compact_dirty_noalloc};
     size_t i, n_exports = sizeof(exports) / sizeof(exports[0]);
     for (i = 0; i < n_exports; ++i)
         if (!exports[i]) return 10;
@@ -64,6 +65,8 @@ int main(void) {
                 job.n_rows = (uint64_t)1 << 32;
                 if (cnr_mark_touched_batch(ctx, &job, 1, CNR_IDX_I64, NULL) != CNR_E_INVALID) return 25;
             }
+            if (cnr_compact_dirty_noalloc(ctx, NULL, CNR_NOALLOC_MAX_ROWS + 1, NULL, 0, NULL, NULL) != CNR_E_TOO_LARGE)
+                return 28;
             if (cnr_destroy(ctx) != CNR_OK) return 21;
         } else if (st != CNR_E_HIP || ctx != NULL) {
             return 22;
