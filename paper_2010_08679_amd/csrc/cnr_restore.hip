@@ -31,25 +31,46 @@ struct RestoreShape {
     static constexpr int ROWS = 4 * (kWave / LR);  // rows per wave and pass
 };
 
-// What one group of LR lanes needs to restore its four rows k0 .. k0+3: ids, scales and biases
-// (the same 16 bytes for every lane of the group, one load each) and this lane's share of the packed
-// codes, fetched in the layout the encoder stored them in: quad lane j of quad q holds the codes of
-// the 16 consecutive elements 64c + 16q .. of row k0 + j (w[c][0..]: 16*BITS bits).
+// How the packed codes of a pass reach the lanes.  Quad lane j of quad q needs the codes of the 16
+// consecutive elements 64c + 16q .. of row k0 + j, for every chunk c: 2 * BITS bytes per chunk.
+//   direct  one load per lane, straight from memory: rows of one chunk at 2, 4 or 8 bits, where the
+//           lanes of a wave together read every byte of the pass's codes exactly once;
+//   staged  rows of several chunks (one load per chunk would have the wave pass over the same lines
+//           once per chunk) and every row at 3 bits (a lane's 6 bytes straddle dword boundaries): the
+//           codes of the pass's ROWS rows are contiguous in memory, ROWS * P bytes, so the wave fetches
+//           them 16 bytes per lane, each line once, parks them in its own piece of LDS and every lane
+//           picks its words from there.  (Measured on 4 M rows of 128 floats with cold inputs: 3 bits
+//           495 -> 456 us, the other widths 2 % faster; on rows of 64 floats 3 bits 410 -> 373 us.)
+template <int Q, int BITS>
+struct CodeFetch {
+    using S = RestoreShape<Q>;
+    static constexpr int P = S::DIM * BITS / 8;                  // packed bytes per row
+    static constexpr bool STAGED = S::M >= 2 || BITS == 3;
+    static constexpr int BLOCK = S::ROWS * P;                    // packed bytes per pass, a multiple of 16
+    static constexpr int LOADS = STAGED ? (BLOCK + 1023) / 1024 : 1;   // 16-byte loads per lane and pass
+    static constexpr int STAGE_BYTES = STAGED ? LOADS * 1024 : 0;      // LDS per wave
+    static constexpr int WORDS = BITS == 8 ? 4 : BITS == 4 ? 2 : BITS == 3 ? 2 : 1;  // per lane and chunk
+};
+
+// What one group of LR lanes needs to restore its four rows k0 .. k0+3: ids, scales and biases (the
+// same 16 bytes for every lane of the group, one load each) and the packed codes, as this lane's words
+// (direct) or as this lane's 16-byte units of the pass's block (staged).
 template <int Q, int BITS>
 struct RestoreInput {
     uint4 ids;
     float4 scale, bias;
-    uint32_t w[RestoreShape<Q>::M][BITS == 8 ? 4 : BITS == 4 ? 2 : BITS == 3 ? 3 : 1];
+    u32x4 raw[CodeFetch<Q, BITS>::LOADS];
 };
 
 template <int Q, int BITS>
 __device__ __forceinline__ void fetch_restore_input(const uint32_t *__restrict__ row_ids,
                                                     const uint8_t *__restrict__ packed,
                                                     const float *__restrict__ scale,
-                                                    const float *__restrict__ bias, uint64_t n_max, uint64_t k0,
-                                                    int q, int j, RestoreInput<Q, BITS> &in) {
-    constexpr int M = RestoreShape<Q>::M;
-    constexpr uint64_t P = (uint64_t)RestoreShape<Q>::DIM * BITS / 8;
+                                                    const float *__restrict__ bias, uint64_t n_max, uint64_t pass_row0,
+                                                    int lane, int g, int q, int j, RestoreInput<Q, BITS> &in) {
+    using F = CodeFetch<Q, BITS>;
+    constexpr uint64_t P = F::P;
+    const uint64_t k0 = pass_row0 + 4u * (uint64_t)g;
     if (k0 + 3 < n_max) {  // every buffer holds n_max rows: whole 16-byte loads
         in.ids = row_ids ? *reinterpret_cast<const uint4 *>(row_ids + k0)
                          : make_uint4((uint32_t)k0, (uint32_t)k0 + 1, (uint32_t)k0 + 2, (uint32_t)k0 + 3);
@@ -69,41 +90,95 @@ __device__ __forceinline__ void fetch_restore_input(const uint32_t *__restrict__
         in.scale = make_float4(sc[0], sc[1], sc[2], sc[3]);
         in.bias = make_float4(bi[0], bi[1], bi[2], bi[3]);
     }
-    const bool row_in_buffer = k0 + (uint64_t)j < n_max;
-    const uint8_t *row = packed + (k0 + (uint64_t)j) * P;
+    if constexpr (F::STAGED) {
+        // the buffer holds n_max rows: the pass's block, or what is left of the buffer
+        const uint64_t left = n_max - pass_row0;  // >= 1
+        const uint32_t bytes = left < (uint64_t)F::S::ROWS ? (uint32_t)(left * P) : (uint32_t)F::BLOCK;
+        const uint8_t *src = packed + pass_row0 * P;
 #pragma unroll
-    for (int c = 0; c < M; ++c) {
+        for (int i = 0; i < F::LOADS; ++i) {
+            const uint32_t off = (uint32_t)(i * kWave + lane) * 16u;
+            u32x4 v = {0, 0, 0, 0};
+            if (off + 16u <= bytes) {
+                v = load_stream<u32x4>(src + off);
+            } else if (off < bytes) {  // the buffer ends inside this unit (P is even): halfword by halfword
+                uint32_t h[8];
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+                    h[t] = off + 2u * t < bytes ? (uint32_t)*reinterpret_cast<const uint16_t *>(src + off + 2 * t) : 0u;
+                v = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+            }
+            in.raw[i] = v;
+        }
+    } else {  // one chunk per row, 2 * BITS bytes per lane
+        const bool row_in_buffer = k0 + (uint64_t)j < n_max;
+        const uint8_t *src = packed + (k0 + (uint64_t)j) * P + 2 * BITS * q;
+        u32x4 v = {0, 0, 0, 0};
         if constexpr (BITS == 8) {
-            const u32x4 v = row_in_buffer ? load_stream<u32x4>(row + 64 * c + 16 * q) : u32x4{0, 0, 0, 0};
-            in.w[c][0] = v.x; in.w[c][1] = v.y; in.w[c][2] = v.z; in.w[c][3] = v.w;
+            if (row_in_buffer) v = load_stream<u32x4>(src);
         } else if constexpr (BITS == 4) {
-            const u32x2 v = row_in_buffer ? load_stream<u32x2>(row + 32 * c + 8 * q) : u32x2{0, 0};
-            in.w[c][0] = v.x; in.w[c][1] = v.y;
+            if (row_in_buffer) {
+                const u32x2 t = load_stream<u32x2>(src);
+                v.x = t.x; v.y = t.y;
+            }
+        } else {
+            if (row_in_buffer) v.x = load_stream<uint32_t>(src);
+        }
+        in.raw[0] = v;
+    }
+}
+
+// This lane's words of chunk c: from its registers (direct), or from the wave's LDS stage, which
+// park_codes filled with the pass's block.  w[0 .. WORDS) = 16 * BITS code bits of the elements
+// 64c + 16q .. of row k0 + j, first element lowest; at 3 bits they start at bit 16 * (q & 1) of w[0].
+template <int Q, int BITS>
+__device__ __forceinline__ void park_codes(unsigned char *stage, int lane, const RestoreInput<Q, BITS> &in) {
+    using F = CodeFetch<Q, BITS>;
+    if constexpr (F::STAGED) {
+        __builtin_amdgcn_wave_barrier();  // the reads of the pass before are done (LDS is in order per wave)
+#pragma unroll
+        for (int i = 0; i < F::LOADS; ++i) *reinterpret_cast<u32x4 *>(stage + (i * kWave + lane) * 16) = in.raw[i];
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+template <int Q, int BITS>
+__device__ __forceinline__ void chunk_words(const unsigned char *stage, int c, int g, int q, int j,
+                                            const RestoreInput<Q, BITS> &in, uint32_t (&w)[CodeFetch<Q, BITS>::WORDS]) {
+    using F = CodeFetch<Q, BITS>;
+    if constexpr (!F::STAGED) {
+        w[0] = in.raw[0].x;
+        if constexpr (F::WORDS >= 2) w[1] = in.raw[0].y;
+        if constexpr (F::WORDS >= 4) { w[2] = in.raw[0].z; w[3] = in.raw[0].w; }
+    } else {
+        const unsigned char *row = stage + (4 * g + j) * F::P;
+        if constexpr (BITS == 8) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(row + 64 * c + 16 * q);
+            w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+        } else if constexpr (BITS == 4) {
+            const uint2 v = *reinterpret_cast<const uint2 *>(row + 32 * c + 8 * q);
+            w[0] = v.x; w[1] = v.y;
         } else if constexpr (BITS == 2) {
-            in.w[c][0] = row_in_buffer ? load_stream<uint32_t>(row + 16 * c + 4 * q) : 0u;
-        } else if constexpr (Q == 1) {  // 3 bits, one quad per row: its 48 bits, at a two-byte boundary
-            const uint16_t *src = reinterpret_cast<const uint16_t *>(row);
-            const uint32_t h0 = row_in_buffer ? load_stream<uint16_t>(src) : 0u;
-            const uint32_t h1 = row_in_buffer ? load_stream<uint16_t>(src + 1) : 0u;
-            const uint32_t h2 = row_in_buffer ? load_stream<uint16_t>(src + 2) : 0u;
-            in.w[c][0] = h0 | (h1 << 16);
-            in.w[c][1] = h2;
-            in.w[c][2] = 0u;
-        } else {  // 3 bits: even quads fetch 12 bytes = their own 48 bits and the next quad's
-            const uint32_t *src = reinterpret_cast<const uint32_t *>(row + 24 * c + 12 * (q >> 1));
-            const bool fetch = row_in_buffer && !(q & 1);
-            in.w[c][0] = fetch ? load_stream<uint32_t>(src) : 0u;
-            in.w[c][1] = fetch ? load_stream<uint32_t>(src + 1) : 0u;
-            in.w[c][2] = fetch ? load_stream<uint32_t>(src + 2) : 0u;
+            w[0] = *reinterpret_cast<const uint32_t *>(row + 16 * c + 4 * q);
+        } else if constexpr (Q == 1) {  // 3 bits, rows of 6 bytes: at a two-byte boundary
+            const uint16_t *h = reinterpret_cast<const uint16_t *>(row);
+            w[0] = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+            w[1] = h[2];
+        } else {
+            // 3 bits: a quad's 48 bits start at byte 24c + 6q of the row, which is a dword boundary for
+            // even quads and two bytes past one for odd quads: the two dwords around them
+            const uint32_t *d = reinterpret_cast<const uint32_t *>(row + 24 * c + 6 * q - 2 * (q & 1));
+            w[0] = d[0];
+            w[1] = d[1];
         }
     }
 }
 
 // Fast path, dim = 16 * Q in {16, 32, 64, 128, 256}: the mirror image of the encoder.  LR lanes share
-// a row, four rows per group; packed codes arrive as whole words per lane and a 4x4 transpose inside
-// each quad turns them into "lane l owns elements 64c + 4l .. + 3 of each of the four rows", so the
-// fp32 rows leave as 16-byte streaming stores that cover up to 256 contiguous bytes per row.  The input of the next batch
-// is requested before the current batch is de-quantized and stored.
+// a row, four rows per group; every lane gets the codes of 16 consecutive elements of one row and
+// chunk (CodeFetch) and a 4x4 transpose inside each quad turns them into "lane l owns elements
+// 64c + 4l .. + 3 of each of the four rows", so the fp32 rows leave as 16-byte streaming stores that
+// cover up to 256 contiguous bytes per row.  The input of the next batch is requested before the
+// current batch is de-quantized and stored.
 struct RestoreJob {
     float *table;
     uint64_t n_rows;
@@ -115,8 +190,10 @@ struct RestoreJob {
     uint32_t n_waves;  // waves of the grid
 };
 template <int Q, int BITS>
-__device__ __forceinline__ void restore_table(const RestoreJob &a, cnr_dev_errors *err) {
+__device__ __forceinline__ void restore_table(const RestoreJob &a, cnr_dev_errors *err,
+                                              unsigned char *stage /* this wave's STAGE_BYTES of LDS */) {
     using S = RestoreShape<Q>;
+    using F = CodeFetch<Q, BITS>;
     constexpr int DIM = S::DIM, M = S::M, LR = S::LR;
     constexpr uint64_t ROWS = S::ROWS;
     constexpr uint32_t MASK = (1u << BITS) - 1u;
@@ -136,12 +213,12 @@ __device__ __forceinline__ void restore_table(const RestoreJob &a, cnr_dev_error
     uint64_t batch = wave_in_grid();
     if (batch * ROWS >= n) return;
     RestoreInput<Q, BITS> cur, nxt;
-    fetch_restore_input<Q, BITS>(row_ids, packed, scale, bias, n_max, batch * ROWS + 4u * (uint64_t)g, q, j, cur);
+    fetch_restore_input<Q, BITS>(row_ids, packed, scale, bias, n_max, batch * ROWS, lane, g, q, j, cur);
     for (;;) {
         const uint64_t next = batch + n_waves;
         const bool has_next = next * ROWS < n;  // uniform over the wave
-        if (has_next)
-            fetch_restore_input<Q, BITS>(row_ids, packed, scale, bias, n_max, next * ROWS + 4u * (uint64_t)g, q, j, nxt);
+        if (has_next) fetch_restore_input<Q, BITS>(row_ids, packed, scale, bias, n_max, next * ROWS, lane, g, q, j, nxt);
+        park_codes<Q, BITS>(stage, lane, cur);
 
         const uint64_t k0 = batch * ROWS + 4u * (uint64_t)g;
         const uint32_t rid[4] = {cur.ids.x, cur.ids.y, cur.ids.z, cur.ids.w};
@@ -149,26 +226,21 @@ __device__ __forceinline__ void restore_table(const RestoreJob &a, cnr_dev_error
         const float b[4] = {cur.bias.x, cur.bias.y, cur.bias.z, cur.bias.w};
 #pragma unroll
         for (int c = 0; c < M; ++c) {
+            uint32_t w[F::WORDS];
+            chunk_words<Q, BITS>(stage, c, g, q, j, cur, w);
             // t[i] = 4*BITS code bits of elements 64c + 16q + 4i .. + 3 of row k0 + j
             uint32_t t[4];
             if constexpr (BITS == 8) {
-                t[0] = cur.w[c][0]; t[1] = cur.w[c][1]; t[2] = cur.w[c][2]; t[3] = cur.w[c][3];
+                t[0] = w[0]; t[1] = w[1]; t[2] = w[2]; t[3] = w[3];
             } else if constexpr (BITS == 4) {
-                t[0] = cur.w[c][0] & 0xFFFFu; t[1] = cur.w[c][0] >> 16;
-                t[2] = cur.w[c][1] & 0xFFFFu; t[3] = cur.w[c][1] >> 16;
+                t[0] = w[0] & 0xFFFFu; t[1] = w[0] >> 16;
+                t[2] = w[1] & 0xFFFFu; t[3] = w[1] >> 16;
             } else if constexpr (BITS == 2) {
-                t[0] = cur.w[c][0] & 0xFFu; t[1] = (cur.w[c][0] >> 8) & 0xFFu;
-                t[2] = (cur.w[c][0] >> 16) & 0xFFu; t[3] = cur.w[c][0] >> 24;
-            } else if constexpr (Q == 1) {
-                const uint32_t lo32 = cur.w[c][0], hi16 = cur.w[c][1];
-                t[0] = lo32 & 0xFFFu; t[1] = (lo32 >> 12) & 0xFFFu;
-                t[2] = (lo32 >> 24) | ((hi16 & 0xFu) << 8); t[3] = hi16 >> 4;
-            } else {
-                // odd quads take bits 48..95 of the 96 their left neighbour quad fetched
-                const uint32_t p1 = (uint32_t)dpp_i<0x114>((int)cur.w[c][1]);  // row_shr:4 = lane - 4
-                const uint32_t p2 = (uint32_t)dpp_i<0x114>((int)cur.w[c][2]);
-                const uint32_t lo32 = (q & 1) ? ((p1 >> 16) | (p2 << 16)) : cur.w[c][0];
-                const uint32_t hi16 = (q & 1) ? (p2 >> 16) : (cur.w[c][1] & 0xFFFFu);
+                t[0] = w[0] & 0xFFu; t[1] = (w[0] >> 8) & 0xFFu;
+                t[2] = (w[0] >> 16) & 0xFFu; t[3] = w[0] >> 24;
+            } else {  // the 48 bits start at bit 16 of w[0] in odd quads
+                const uint32_t lo32 = (q & 1) ? ((w[0] >> 16) | (w[1] << 16)) : w[0];
+                const uint32_t hi16 = (q & 1) ? (w[1] >> 16) : (w[1] & 0xFFFFu);
                 t[0] = lo32 & 0xFFFu; t[1] = (lo32 >> 12) & 0xFFFu;
                 t[2] = (lo32 >> 24) | ((hi16 & 0xFu) << 8); t[3] = hi16 >> 4;
             }
@@ -177,12 +249,12 @@ __device__ __forceinline__ void restore_table(const RestoreJob &a, cnr_dev_error
             for (int u = 0; u < 4; ++u) {
                 const bool live = k0 + u < n && rid[u] < n_rows;
                 if (!live) continue;
-                const uint32_t w = t[u];
+                const uint32_t cw = t[u];
                 f32x4 v;
-                v.x = s[u] * (float)(w & MASK) + b[u];
-                v.y = s[u] * (float)((w >> BITS) & MASK) + b[u];
-                v.z = s[u] * (float)((w >> (2 * BITS)) & MASK) + b[u];
-                v.w = s[u] * (float)((w >> (3 * BITS)) & MASK) + b[u];
+                v.x = s[u] * (float)(cw & MASK) + b[u];
+                v.y = s[u] * (float)((cw >> BITS) & MASK) + b[u];
+                v.z = s[u] * (float)((cw >> (2 * BITS)) & MASK) + b[u];
+                v.w = s[u] * (float)((cw >> (3 * BITS)) & MASK) + b[u];
                 store_stream<f32x4>(table + (uint64_t)rid[u] * DIM + 64 * c + 4 * l, v);
             }
         }
@@ -203,9 +275,11 @@ struct RestoreBatch {
 };
 template <int Q, int BITS>
 __global__ void __launch_bounds__(kBlock) restore_rows16_kernel(const RestoreBatch b, cnr_dev_errors *err) {
+    constexpr int kStage = CodeFetch<Q, BITS>::STAGE_BYTES;
+    __shared__ __align__(16) unsigned char stages[kStage ? kWavesPerBlock * kStage : 16];
     const RestoreJob &a = b.job[wg_y()];
     if (wg_x() * kWavesPerBlock >= a.n_waves) return;  // fewer workgroups than the launch's largest table
-    restore_table<Q, BITS>(a, err);
+    restore_table<Q, BITS>(a, err, stages + (tid_x() / kWave) * kStage);
 }
 
 // Other row lengths: LPR lanes per row (a power of two, at least the row's number of 16-byte units up

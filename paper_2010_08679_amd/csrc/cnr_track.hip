@@ -95,35 +95,83 @@ __global__ void __launch_bounds__(kBlock) mark_kernel(const TrackBatch b, cnr_de
 // the bitmap 32 rows per thread, with plain read-modify-write because every bitmap word has exactly
 // one owner there, and zeroes the bytes it found set so that the scratch is clean again.
 // ---------------------------------------------------------------------------------------------
+// Most look-ups of a skewed stream repeat a row that the same compute unit has flagged already, and a
+// scattered byte store is the expensive part (each one is a request of its own to the L2, about 17 ps
+// of the whole chip's time).  So a workgroup keeps, in 128 KB of LDS, a direct-mapped table of the
+// rows it has flagged lately: h = row * odd constant (a bijection on 32 bits), slot = high 16 bits of
+// h, and the slot holds the low 16 bits, so slot and content together name exactly one row.  A
+// look-up that finds its own row there is dropped, any other one takes the slot over and stores its
+// flag byte.  A row found in the table has had its store issued (or about to be issued, in program
+// order) by the lane that put it there, so nothing is ever lost; collisions only cost a repeated
+// store.  The content 0xFFFF marks an empty slot; the one row in 65,536 whose own low bits are
+// 0xFFFF bypasses the table.  One workgroup of kSeenThreads threads per compute unit (the table
+// fills the LDS; two smaller tables per unit do worse, each sees half the repeats); the stream is
+// read as 16-byte vectors.
+constexpr int kSeenThreads = 1024;
+constexpr uint32_t kSeenSlots = 65536;
+
 template <typename IdxT>
-__global__ void __launch_bounds__(kBlock) mark_flags_kernel(const TrackBatch b, cnr_dev_errors *err) {
+__global__ void __launch_bounds__(kSeenThreads) mark_flags_kernel(const TrackBatch b, cnr_dev_errors *err) {
+    constexpr int kVec = 16 / (int)sizeof(IdxT);
+    typedef IdxT vec_t __attribute__((ext_vector_type(kVec)));
+    constexpr int kUnroll = 4;
+    __shared__ uint16_t seen[kSeenSlots];
     const TrackJob &t = b.job[wg_y()];
     uint8_t *__restrict__ flags = t.flags;
-    const IdxT *__restrict__ idx = static_cast<const IdxT *>(t.idx);
-    const uint64_t n_rows = t.n_rows, n = t.n_idx;
-    constexpr int kUnroll = 4;
-    const uint64_t stride = (uint64_t)b.grid_x * kBlock;
-    uint64_t i = (uint64_t)wg_x() * kBlock + tid_x();
+    const uint32_t n_rows = (uint32_t)t.n_rows;  // the host checks n_rows < 2^32
+    const uint32_t tid = tid_x();
+    for (uint32_t i = tid; i < kSeenSlots / 2; i += kSeenThreads) reinterpret_cast<uint32_t *>(seen)[i] = 0xFFFFFFFFu;
+    __syncthreads();
+
+    // the stream as [head][16-byte vectors][tail]: head and tail are fewer than kVec elements each
+    const IdxT *idx = static_cast<const IdxT *>(t.idx);
+    const uint64_t n = t.n_idx;
+    uint64_t head = ((16u - (uint32_t)((uintptr_t)idx & 15u)) & 15u) / sizeof(IdxT);
+    if (head > n) head = n;
+    const vec_t *vecs = reinterpret_cast<const vec_t *>(idx + head);
+    const uint64_t n_vec = (n - head) / kVec;
+    const uint64_t tail = head + n_vec * kVec;
+
     unsigned bad = 0;
-    for (; i < n; i += stride * kUnroll) {
-        IdxT v[kUnroll];
+    auto look_up = [&](IdxT v) {
+        bool valid = (uint32_t)v < n_rows;
+        if constexpr (sizeof(IdxT) == 8) valid = valid && ((uint64_t)v >> 32) == 0;
+        else valid = valid && v >= 0;
+        if (!valid) {
+            ++bad;
+            return;
+        }
+        const uint32_t r = (uint32_t)v;
+        const uint32_t h = r * 0x9E3779B1u;
+        const uint32_t slot = h >> 16, low = h & 0xFFFFu;
+        if (seen[slot] != low || low == 0xFFFFu) {
+            seen[slot] = (uint16_t)low;
+            flags[r] = 1;
+        }
+    };
+    const uint64_t stride = (uint64_t)b.grid_x * kSeenThreads;
+    for (uint64_t p = (uint64_t)wg_x() * kSeenThreads + tid; p < n_vec; p += stride * kUnroll) {
+        vec_t v[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const uint64_t p = i + (uint64_t)u * stride;
-            v[u] = p < n ? idx[p] : (IdxT)-1;
+            const uint64_t q = p + (uint64_t)u * stride;
+            if (q < n_vec) v[u] = load_stream<vec_t>(vecs + q);
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const uint64_t p = i + (uint64_t)u * stride;
-            const int64_t r = (int64_t)v[u];
-            if (r >= 0 && (uint64_t)r < n_rows)
-                flags[r] = 1;
-            else if (p < n)
-                ++bad;
+            const uint64_t q = p + (uint64_t)u * stride;
+            if (q < n_vec) {
+#pragma unroll
+                for (int e = 0; e < kVec; ++e) look_up(v[u][e]);
+            }
         }
     }
+    if (wg_x() == 0) {
+        if (tid < head) look_up(idx[tid]);
+        else if (tid - head < n - tail) look_up(idx[tail + (tid - head)]);
+    }
     for (int off = 32; off > 0; off >>= 1) bad += __shfl_xor(bad, off);
-    if (bad && (tid_x() & (kWave - 1)) == 0) atomicAdd(&err->n_bad_indices, (unsigned long long)bad);
+    if (bad && (tid & (kWave - 1)) == 0) atomicAdd(&err->n_bad_indices, (unsigned long long)bad);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -508,12 +556,13 @@ cnr_status cnr_mark_touched_batch(cnr_ctx *ctx, const cnr_table_job *jobs, uint3
             if ((st = cnr_launch_status(ctx)) != CNR_OK) return st;
         }
         if (n_bulk) {
-            bulk.grid_x = batch_grid_x(ctx, bulk_idx, (uint64_t)kBlock * 4, 8, n_bulk);
+            // one workgroup per compute unit in all (each fills a unit's LDS), shared out over the tables
+            bulk.grid_x = batch_grid_x(ctx, bulk_idx, (uint64_t)kSeenThreads * 8, 1, n_bulk);
             const dim3 grid(bulk.grid_x, n_bulk);
             if (type == CNR_IDX_I64)
-                hipLaunchKernelGGL(mark_flags_kernel<int64_t>, grid, dim3(kBlock), 0, s, bulk, ctx->dev_err);
+                hipLaunchKernelGGL(mark_flags_kernel<int64_t>, grid, dim3(kSeenThreads), 0, s, bulk, ctx->dev_err);
             else
-                hipLaunchKernelGGL(mark_flags_kernel<int32_t>, grid, dim3(kBlock), 0, s, bulk, ctx->dev_err);
+                hipLaunchKernelGGL(mark_flags_kernel<int32_t>, grid, dim3(kSeenThreads), 0, s, bulk, ctx->dev_err);
             if ((st = cnr_launch_status(ctx)) != CNR_OK) return st;
             bulk.grid_x = batch_grid_x(ctx, bulk_words, kBlock, 8, n_bulk);
             hipLaunchKernelGGL(fold_flags_kernel, dim3(bulk.grid_x, n_bulk), dim3(kBlock), 0, s, bulk);
