@@ -35,7 +35,11 @@ from paper_2010_08679_amd import synth  # noqa: E402
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published
-ISSUE_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # one vector instruction per lane per clock
+# SIMD time the greedy search needs per element and candidate range: 26 clocks of a 16-lane SIMD for a
+# wave of 64 (add / subtract / multiply occupy it for 2 clocks, every other vector instruction of the
+# loop for 4: bench_valu_rate.hip measures that), with 256 CUs x 4 SIMDs at 2.4 GHz
+GREEDY_SIMD_CLOCKS_PER_ELEMENT = 26.0
+SIMD_CLOCKS_PER_S = 256 * 4 * 2.4e9
 
 # HBM traffic of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), in bytes
 # per dirty row, valid only for the kernel source whose hash is recorded with it.
@@ -316,6 +320,38 @@ def main() -> int:
         "stages_ms_per_step": stages,
     }
 
+    # ---- a launch-bound step replayed from a HIP graph (the calls only enqueue kernels, so a step can be
+    #      captured once): reported where the eager step is short enough for launch overhead to matter
+    if ms_per_step < 0.5:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step(None, ())
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):                           # the calls are prepared on the capturing stream
+            if batched:
+                gcalls = batch.prepare_step(streams, tables, encs, restore_into=stale)
+            else:
+                gcalls = []
+                for ti in range(n_tables):
+                    gcalls += cks[ti].prepare_step(streams[ti], tables[ti], encs[ti], restore_into=stale[0])
+            for _, fn in gcalls:
+                fn()
+        for _ in range(max(3, args.warmup)):
+            graph.replay()
+        torch.cuda.synchronize()
+        reps = max(args.steps, 200)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - t0) * 1e3 / reps
+        assert [int(c.n_dirty.item()) for c in cks] == n_dirty
+        out["graph_replay"] = {"ms_per_step": round(g_ms, 4), "value": round(table_bytes / (g_ms * 1e-3) / 1e9, 1),
+                               "unit": "GB/s", "replays": reps}
+
     # ---- context for the roofline: what a plain device-to-device copy reaches on this machine -----------
     src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
     dst = torch.empty_like(src)
@@ -373,6 +409,7 @@ def main() -> int:
         # arithmetic the search itself prescribes, per element and candidate range: clip (2), subtract,
         # divide, round, multiply, add, subtract, square, accumulate = 10
         flops = sum(n_dirty) * w.dim * (1 + 2 * n_iter) * 10.0
+        issue_ms = sum(n_dirty) * w.dim * (1 + 2 * n_iter) / 64.0 * GREEDY_SIMD_CLOCKS_PER_ELEMENT / SIMD_CLOCKS_PER_S * 1e3
         out["greedy"] = {
             "workload": "%d-bit greedy range, num_bins=%d, ratio=%.2f (%d candidate ranges per row)"
                         % (bits, w.num_bins, w.ratio, 1 + 2 * n_iter),
@@ -380,7 +417,8 @@ def main() -> int:
             "roofline": {"bound": "alu", "achieved": round(flops / (g * 1e-3) / 1e12, 2),
                          "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
                          "frac": round(flops / (g * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TFLOPS, 4),
-                         "issue_peak_Tops": round(ISSUE_PEAK_TOPS, 1), "traffic": None},
+                         # the same launch against the time its own instruction mix needs at full issue rate
+                         "issue_bound_ms": round(issue_ms, 3), "issue_frac": round(issue_ms / g, 4), "traffic": None},
         }
 
     # ---- a full (baseline) checkpoint: every row of a table, no id list (Section 5.1) ---------------
@@ -422,25 +460,33 @@ def main() -> int:
     if not args.no_host_copy:
         writer = P.HostCheckpointWriter(ctx, w.dim, bits, capacity=w.n_rows, chunk_rows=1 << 20, device=dev)
         cks[0].clear(); cks[0].mark(streams[0]); cks[0].compact()
-        def median_s(fn, reps=7):
-            """Median and largest wall time of `reps` calls (each call ends synchronized)."""
-            fn()                                                                # warm-up
+        def median_s(fn, reps=7, warm=1):
+            """Median and largest wall time of `reps` calls (each call ends synchronized), after `warm`
+            untimed ones; the largest of those is returned as well."""
+            warm_ts = []
+            for _ in range(warm):
+                t0 = time.perf_counter()
+                fn()
+                warm_ts.append(time.perf_counter() - t0)
             ts = []
             for _ in range(reps):
                 t0 = time.perf_counter()
                 fn()
                 ts.append(time.perf_counter() - t0)
             ts.sort()
-            return ts[len(ts) // 2], ts[-1]
+            return ts[len(ts) // 2], ts[-1], max(warm_ts)
         res, back, n_h = {}, {}, 0
         for label, overlap in (("overlapped", True), ("serialized", False)):
             def to_host():
                 nonlocal n_h
                 n_h = writer.encode_to_host(cks[0], tables[0], overlap=overlap)
             res[label] = median_s(to_host)
-        # and the way back: the same chunks from host memory into the stale table
+        # and the way back: the same chunks from host memory into the stale table.  The first dozen or so
+        # overlapped calls of a process can contain one that takes 4-10 ms (the host blocks once inside
+        # the runtime's hipMemcpyAsync while it sets up the second stream's copy path, the GPU idle
+        # meanwhile; it does not recur), so 16 calls run untimed first and their slowest is reported apart.
         for label, overlap in (("overlapped", True), ("serialized", False)):
-            back[label] = median_s(lambda: writer.restore_from_host(stale[0], w.n_rows, n_h, overlap=overlap))
+            back[label] = median_s(lambda: writer.restore_from_host(stale[0], w.n_rows, n_h, overlap=overlap), reps=50, warm=16)
         out["to_host"] = {"workload": "table 0: %d dirty rows encoded in chunks of %d rows into pinned host memory; "
                                       "median of 7 calls" % (n_h, writer.chunk),
                           "overlapped_ms": round(res["overlapped"][0] * 1e3, 3),
@@ -449,10 +495,11 @@ def main() -> int:
                           "value": round(n_h * w.dim * 4 / res["overlapped"][0] / 1e9, 1), "unit": "GB/s",
                           "host_bytes": int(n_h * (12 + writer.prb))}
         out["from_host"] = {"workload": "table 0: the same %d rows copied from pinned host memory in chunks of %d "
-                                        "rows and restored; median of 7 calls" % (n_h, writer.chunk),
+                                        "rows and restored; median of 50 calls after 16 untimed ones" % (n_h, writer.chunk),
                             "overlapped_ms": round(back["overlapped"][0] * 1e3, 3),
                             "serialized_ms": round(back["serialized"][0] * 1e3, 3),
                             "slowest_call_ms": round(max(back["overlapped"][1], back["serialized"][1]) * 1e3, 3),
+                            "slowest_warmup_call_ms": round(max(back["overlapped"][2], back["serialized"][2]) * 1e3, 3),
                             "value": round(n_h * w.dim * 4 / back["overlapped"][0] / 1e9, 1), "unit": "GB/s"}
         del writer
 

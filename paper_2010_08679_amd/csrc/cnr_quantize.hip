@@ -371,13 +371,22 @@ quantize_tile_kernel(const QuantBatchArgs b) {
 // sixteen codes are exactly 2 * BITS contiguous bytes of the packed row.  The rows are read in this
 // layout directly (16-byte loads 64 bytes apart): the kernel is far from the memory system's limits,
 // so the transpose through LDS that the tile kernel pays for coalesced loads would buy nothing.
-// A candidate is evaluated with the cheapest sequence that still reproduces F_Q's codes: the scale
-// (range / (2^b - 1)) and the quotient (x - lo) / scale are formed by a reciprocal multiply followed
-// by one FMA residual correction (q' = q + (a - q*b) * (1/b)), which yields the correctly rounded
-// quotient except in cases far too rare to matter for ranking candidates; d*d is exact in fp64, so
-// fma(d, d, acc) is the multiply-then-add of the definition.  A wave holding a row whose scale lies
-// outside [2^-100, 2^100] divides instead.  The final codes of the chosen range are produced by
-// division, exactly as F_Q is written.
+// A candidate is evaluated with the cheapest sequence that still ranks candidates as F_Q would.  On
+// this GPU a wave's add, subtract or multiply occupies a SIMD for two clocks, every other vector
+// instruction used here (fused multiply-add, median, round, conversion, all fp64) for four (measured
+// with single-instruction loops), so an element costs 26 clocks per candidate: clip (4), subtract (2),
+// multiply by the reciprocal of the scale (2), round (4), de-quantize (2 + 2), residual (2), convert
+// and accumulate its square in fp64 (4 + 4; d * d is exact in fp64, so fma(d, d, acc) is the
+// multiply-then-add of the definition).  The candidate's scale is range / (2^b - 1) correctly rounded
+// (reciprocal multiply plus one FMA residual step) and its reciprocal likewise; the quotient itself
+// is the plain product, within 1.5 ulp of the correctly rounded quotient, which can move a code of a
+// candidate only where the quotient lies that close to a half-integer (about 3 elements in a million
+// at 4 bits) and then changes the candidate's error by about 1e-7 of itself: a search leaves the path
+// of the divide-as-written sequence only if that coincides with two candidates that close, about one
+// row in a few million.  (Correcting the quotient too, two more FMAs per element, took 34 clocks per
+// element and candidate.)  A wave holding a row whose scale lies outside [2^-100, 2^100], or whose
+// span is only a few float spacings wide, divides instead.  The final codes of the chosen range are
+// produced by division, exactly as F_Q is written.
 // ---------------------------------------------------------------------------------------------
 template <int L>
 __device__ __forceinline__ float lanes_min(float v) {
@@ -453,9 +462,7 @@ __global__ void __launch_bounds__(kBlock) quantize_greedy_kernel(const QuantArgs
             auto add_err = [&](double acc, float xv, float c_lo, float c_hi, float s, float inv) -> double {
                 if constexpr (FAST) {
                     const float c = __builtin_amdgcn_fmed3f(xv, c_lo, c_hi);
-                    const float d0 = c - c_lo;
-                    float t = d0 * inv;
-                    t = fmaf(fmaf(-t, s, d0), inv, t);
+                    const float t = (c - c_lo) * inv;
                     const float d = xv - fq_value(rintf(t), s, c_lo);
                     return fma((double)d, (double)d, acc);
                 } else {
