@@ -37,41 +37,40 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector, published
 # SIMD time the greedy search needs per element and candidate range: 26 clocks of a 16-lane SIMD for a
 # wave of 64 (add / subtract / multiply occupy it for 2 clocks, every other vector instruction of the
-# loop for 4: bench_valu_rate.hip measures that), with 256 CUs x 4 SIMDs at 2.4 GHz
+# loop for 4: bench_ceilings.hip measures that), with 256 CUs x 4 SIMDs at 2.4 GHz
 GREEDY_SIMD_CLOCKS_PER_ELEMENT = 26.0
 SIMD_CLOCKS_PER_S = 256 * 4 * 2.4e9
 
-# HBM traffic of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), in bytes
-# per dirty row, valid only for the kernel source whose hash is recorded with it.
+# HBM traffic of the two bandwidth-bound kernels from rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each
+# scaled by what a 1 GiB device copy reads on the same counter: 2.000 and 1.000), in bytes per dirty row,
+# valid only for the kernel source whose hash is recorded with it (profiles/hbm_traffic.txt).
 TRAFFIC_PER_ROW = {
-    # _kernel_hash() : (workload, bytes per dirty row)
-    # (2.000 * 1523629.9 KiB FETCH_SIZE + 1.000 * 480022.0 KiB WRITE_SIZE) / 12,000,978 rows per launch of 8 tables
-    "a2e6a8cd8520d9e7bb6344cdfd2a382c27d08e95db09fef0a95bfb9a9a5ff999": ("cfg4/b4", 300.97),
+    # _kernel_hash() : {workload/bits : bytes per dirty row}
+    "a2e6a8cd8520d9e7bb6344cdfd2a382c27d08e95db09fef0a95bfb9a9a5ff999": {"cfg4/b4": 300.96, "cfg3/b2": 558.96, "cfg3/b3": 581.12, "cfg5/b8": 659.02, "cfg5/b4": 592.55},
 }
+RESTORE_TRAFFIC_PER_ROW = {
+    "de4cce8a762a5a42205dd6f32d9093d91b2705c740b7c41c24c31a0cdef0ea17": {"cfg4/b4": 300.01, "cfg3/b2": 556.09, "cfg3/b3": 572.08, "cfg5/b8": 652.08, "cfg5/b4": 588.04},
+}
+
+
+def _source_hash(name: str, upto: str | None = None) -> str:
+    """Hash of a kernel source file (up to the line that starts the section `upto`), without comments
+    and white space."""
+    with open(os.path.join(ROOT, "paper_2010_08679_amd", "csrc", name), "r") as f:
+        text = f.read()
+    if upto is not None:
+        text = text[:text.index(upto)]
+    code = "".join(line.split("//")[0] for line in text.splitlines(True))
+    return hashlib.sha256("".join(code.split()).encode()).hexdigest()
 
 
 def _kernel_hash() -> str:
-    """Hash of the tile kernel's source (everything in its file above the greedy kernel's section),
-    without comments and white space."""
-    with open(os.path.join(ROOT, "paper_2010_08679_amd", "csrc", "cnr_quantize.hip"), "r") as f:
-        text = f.read()
-    text = text[:text.index("// Greedy range search")]
-    code = "".join(line.split("//")[0] for line in text.splitlines(True))
-    return hashlib.sha256("".join(code.split()).encode()).hexdigest()
-
-
-# The same for the restore kernel: (2.000 * 257878.7 KiB + 1.000 * 3000264.0 KiB) / 12,000,978 rows
-RESTORE_TRAFFIC_PER_ROW = {
-    "0e52e4246431f8c331da57ab97848044ce96d019c483ca3778fe5050bd57ce3b": ("cfg4/b4", 300.01),
-}
+    """The tile kernel's source: everything in its file above the greedy kernel's section."""
+    return _source_hash("cnr_quantize.hip", "// Greedy range search")
 
 
 def _restore_kernel_hash() -> str:
-    """Hash of the restore kernels' source file, without comments and white space."""
-    with open(os.path.join(ROOT, "paper_2010_08679_amd", "csrc", "cnr_restore.hip"), "r") as f:
-        text = f.read()
-    code = "".join(line.split("//")[0] for line in text.splitlines(True))
-    return hashlib.sha256("".join(code.split()).encode()).hexdigest()
+    return _source_hash("cnr_restore.hip")
 
 
 def encode_bytes_per_row(dim: int, bits: int) -> int:
@@ -267,9 +266,9 @@ def main() -> int:
     enc_bytes = encode_bytes_per_row(w.dim, bits) * rows_per_launch
     achieved = enc_bytes / (enc_launch_ms * 1e-3) / 1e9
     traffic = None
-    rec = TRAFFIC_PER_ROW.get(_kernel_hash())
-    if rec and rec[0] == "%s/b%d" % (w.name, bits):
-        traffic = round(rec[1] * rows_per_launch, 1)
+    rec = TRAFFIC_PER_ROW.get(_kernel_hash(), {}).get("%s/b%d" % (w.name, bits))
+    if rec:
+        traffic = round(rec * rows_per_launch, 1)
     roofline = {"bound": "hbm", "kernel": "quantize_tile_kernel<%d, %d>" % (w.dim // 16, bits),
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
@@ -280,9 +279,9 @@ def main() -> int:
     res_bytes = restore_bytes_per_row(w.dim, bits) * rows_per_launch
     res_achieved = res_bytes / (res_ms * 1e-3) / 1e9
     res_traffic = None
-    rec = RESTORE_TRAFFIC_PER_ROW.get(_restore_kernel_hash())
-    if rec and rec[0] == "%s/b%d" % (w.name, bits):
-        res_traffic = round(rec[1] * rows_per_launch, 1)
+    rec = RESTORE_TRAFFIC_PER_ROW.get(_restore_kernel_hash(), {}).get("%s/b%d" % (w.name, bits))
+    if rec:
+        res_traffic = round(rec * rows_per_launch, 1)
     # the other long kernel of a step, measured the same way (from the per-stage run)
     roofline_restore = {"bound": "hbm", "kernel": "restore_rows16_kernel<%d, %d>" % (w.dim // 16, bits),
                         "achieved": round(res_achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",

@@ -273,8 +273,12 @@ __device__ __forceinline__ void restore_table(const RestoreJob &a, cnr_dev_error
 struct RestoreBatch {
     RestoreJob job[CNR_MAX_BATCH];
 };
+// The register budget is pinned to eight waves per SIMD (64 registers), which every shape meets without
+// spilling except rows of 256 floats at 8 bits (left to the compiler: 84 registers, five waves): left
+// alone, a few shapes land two registers above the step.
 template <int Q, int BITS>
-__global__ void __launch_bounds__(kBlock) restore_rows16_kernel(const RestoreBatch b, cnr_dev_errors *err) {
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(Q == 16 && BITS == 8 ? 5 : 8, 8)))
+restore_rows16_kernel(const RestoreBatch b, cnr_dev_errors *err) {
     constexpr int kStage = CodeFetch<Q, BITS>::STAGE_BYTES;
     __shared__ __align__(16) unsigned char stages[kStage ? kWavesPerBlock * kStage : 16];
     const RestoreJob &a = b.job[wg_y()];

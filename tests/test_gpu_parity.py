@@ -123,6 +123,46 @@ def test_bulk_mark_any_stream_alignment_and_length(ctx, dtype, offset, length):
     _poll_clean(ctx)
 
 
+@pytest.mark.parametrize("dtype", [torch.int64, torch.int32])
+@pytest.mark.parametrize("offset,length", [(0, 400_000), (1, 400_001), (3, 399_998)])
+def test_flag_route_mark_with_heavy_repeats(ctx, dtype, offset, length):
+    # tables beyond the slice route: look-ups go through a table of lately flagged rows that drops
+    # repeats.  A stream that is mostly repeats of a few thousand hot rows (in bursts and spread out),
+    # rows whose slot content is the empty marker (they bypass the table), rows that collide in one
+    # slot, indices outside the table, any alignment and length; and a second call on top of the first
+    n_rows = FLAG_ROUTE_ROWS + 17
+    print("case flag route repeats dtype=%s offset=%d length=%d" % (dtype, offset, length), flush=True)
+    rng = np.random.default_rng(length + offset)
+    hot = rng.choice(n_rows, size=3000, replace=False)
+    h = (np.arange(n_rows, dtype=np.uint64) * np.uint64(0x9E3779B1)) & np.uint64(0xFFFFFFFF)
+    bypass = np.flatnonzero((h & np.uint64(0xFFFF)) == np.uint64(0xFFFF))[:50]            # empty-marker rows
+    same_slot = np.flatnonzero((h >> np.uint64(16)) == (h[hot[0]] >> np.uint64(16)))[:40]   # collide with a hot row
+    parts = [hot[rng.integers(0, 3000, size=length // 2)], np.repeat(hot[:200], 100), np.repeat(bypass, 20),
+             np.tile(same_slot, 30), rng.integers(0, n_rows, size=length // 8), np.array([-1, -5, n_rows, n_rows + 7, n_rows - 1, 0])]
+    stream = np.concatenate(parts)
+    rng.shuffle(stream[: length // 2])                                                     # keep the bursts that follow
+    stream = np.resize(stream, offset + length + 3).astype(np.int64)
+    if dtype == torch.int32:
+        stream[5] = -(2 ** 31)                                                             # looks like a row when cast to unsigned
+    base = torch.from_numpy(stream).to(DEV).to(dtype)
+    idx = base[offset:offset + length]
+    scratch = P.TableCheckpointer.new_mark_scratch(n_rows, DEV)
+    ck = P.TableCheckpointer(ctx, n_rows, 64, capacity=600_000, device=DEV, mark_scratch=scratch)
+    ck.clear()
+    ck.mark(idx)
+    second = torch.from_numpy(rng.integers(0, n_rows, size=length)).to(DEV).to(dtype)
+    ck.mark(second)
+    ck.compact()
+    torch.cuda.synchronize()
+    bm, ids, n, skipped = _oracle_track(n_rows, [idx.cpu().numpy(), second.cpu().numpy()])
+    assert skipped >= 4
+    assert np.array_equal(u32(ck.bitmap)[:bm.size], bm)
+    assert int(ck.n_dirty.item()) == n and np.array_equal(u32(ck.row_ids)[:n], ids)
+    assert not scratch.any()
+    st, bad, flags = P.cnr_poll_errors(ctx)
+    assert st == P.CNR_E_INDEX_RANGE and bad == skipped and flags == 0
+
+
 def test_mark_skips_and_counts_out_of_range(ctx):
     n_rows = 5000
     ck = P.TableCheckpointer(ctx, n_rows, 64, device=DEV)
