@@ -255,7 +255,11 @@ __device__ __forceinline__ void restore_table(const RestoreJob &a, cnr_dev_error
                 v.y = s[u] * (float)((cw >> BITS) & MASK) + b[u];
                 v.z = s[u] * (float)((cw >> (2 * BITS)) & MASK) + b[u];
                 v.w = s[u] * (float)((cw >> (3 * BITS)) & MASK) + b[u];
-                store_stream<f32x4>(table + (uint64_t)rid[u] * DIM + 64 * c + 4 * l, v);
+                float *dst = table + (uint64_t)rid[u] * DIM + 64 * c + 4 * l;
+                if constexpr (M == 1 && BITS <= 4)  // one instruction writes the whole row: straight to memory
+                    store_stream_through(dst, v);
+                else
+                    store_stream<f32x4>(dst, v);
             }
         }
 #pragma unroll
