@@ -46,10 +46,10 @@ SIMD_CLOCKS_PER_S = 256 * 4 * 2.4e9
 # valid only for the kernel source whose hash is recorded with it (profiles/hbm_traffic.txt).
 TRAFFIC_PER_ROW = {
     # _kernel_hash() : {workload/bits : bytes per dirty row}
-    "a2e6a8cd8520d9e7bb6344cdfd2a382c27d08e95db09fef0a95bfb9a9a5ff999": {"cfg4/b4": 300.96, "cfg3/b2": 558.96, "cfg3/b3": 581.12, "cfg5/b8": 659.02, "cfg5/b4": 592.55},
+    "a2e6a8cd8520d9e7bb6344cdfd2a382c27d08e95db09fef0a95bfb9a9a5ff999": {"cfg4/b4": 300.96, "cfg3/b2": 558.98, "cfg3/b3": 581.12, "cfg5/b8": 658.98, "cfg5/b4": 592.55},
 }
 RESTORE_TRAFFIC_PER_ROW = {
-    "de4cce8a762a5a42205dd6f32d9093d91b2705c740b7c41c24c31a0cdef0ea17": {"cfg4/b4": 300.01, "cfg3/b2": 556.09, "cfg3/b3": 572.08, "cfg5/b8": 652.08, "cfg5/b4": 588.04},
+    "0a151c3fed73be1daf849a41a37f121a6c0b73202cd2806cb848ad2850c9bc6b": {"cfg4/b4": 300.01, "cfg3/b2": 556.09, "cfg3/b3": 572.08, "cfg5/b8": 652.09, "cfg5/b4": 588.04},
 }
 
 
