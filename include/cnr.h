@@ -139,10 +139,12 @@ cnr_status cnr_clear_bitmap(cnr_ctx *ctx, uint32_t *bitmap, uint64_t n_rows, voi
  *            zero again, so one buffer sized for the largest table can serve all tables marked on
  *            the same stream.  With a scratch buffer, long index streams are marked without one
  *            device-scope atomic per index: through bitmap slices held in on-chip memory whose
- *            partial bitmaps pass through the scratch (tables of up to about 21 M rows), or
- *            through one flag byte per row (larger tables), each followed by a fold into the
- *            bitmap.  Short streams, and all streams when scratch is NULL, use atomic ORs on the
- *            bitmap directly.  The resulting bitmap is the same whichever way. */
+ *            partial bitmaps pass through the scratch (tables of up to about 21 M rows, when
+ *            several tables are marked in one call), or through one flag byte per row with
+ *            repeated look-ups dropped on chip (larger tables, and one or two tables marked
+ *            alone), each followed by a fold into the bitmap.  Short streams, and all streams
+ *            when scratch is NULL, use atomic ORs on the bitmap directly.  The resulting bitmap is
+ *            the same whichever way. */
 cnr_status cnr_mark_touched(cnr_ctx *ctx, uint32_t *bitmap, uint64_t n_rows, const void *indices,
                             uint64_t n_indices, cnr_index_type type, void *scratch, void *stream);
 

@@ -513,11 +513,33 @@ cnr_status cnr_mark_touched_batch(cnr_ctx *ctx, const cnr_table_job *jobs, uint3
     hipStream_t s = as_stream(stream);
     for (uint32_t first = 0; first < n_jobs; first += CNR_MAX_BATCH) {
         // Three routes.  Short streams: atomic ORs on the bitmap (about 16 G atomics/s; the other two
-        // pay a pass over n_rows bytes).  Long streams into tables of at most kSliceTeamMax slices:
-        // bitmap slices in LDS (every look-up is read by as many workgroups as the table has slices,
-        // which beats the flag bytes' one 32-byte memory write per look-up up to there).  Long
-        // streams into larger tables: one flag byte per row, then a fold.
+        // pay a pass over n_rows bytes).  Long streams: bitmap slices in LDS, or one flag byte per row
+        // and a fold.  The slices cost every workgroup of a table its part of the stream (an eighth,
+        // at the 60 GB/s one compute unit reads), whatever the stream holds, and all tables of a call
+        // run side by side as long as their 8 x slices workgroups fit the chip; the flag bytes cost
+        // one scattered store per look-up that gets past the table of lately flagged rows (about 17 ps
+        // of the whole chip's time each, a third of the look-ups on the skewed streams that embedding
+        // look-ups are), one table after the other.  So one or two tables marked alone are faster
+        // through flag bytes (a 5 M-row table, 20 M Zipf look-ups: 67-121 against 250-445 us) and a
+        // batch of many tables through slices (8 x 5 M rows, 3 M look-ups each: 89 against 385 us); the
+        // call takes, for all its tables of up to kSliceTeamMax slices together, the route this
+        // estimate makes the cheaper one.  Larger tables always take the flag bytes.
         constexpr uint64_t kSliceTeamMax = 16;
+        constexpr double kSlicePsPerByte = 1e12 / 60e9 / kStreamParts;  // a workgroup's part of the stream at 60 GB/s
+        constexpr double kFlagPsPerLookup = 6.0;                         // 17 ps x about a third that become stores
+        uint64_t elig_wgs = 0, elig_max_idx = 0, elig_sum_idx = 0;
+        for (uint32_t i = first; i < n_jobs && i < first + CNR_MAX_BATCH; ++i) {
+            const cnr_table_job &j = jobs[i];
+            const uint64_t team = (j.n_rows + kSliceRows - 1) / kSliceRows;
+            if (j.n_indices == 0 || !(j.mark_scratch && j.n_rows && j.n_indices > j.n_rows / 256 + 65536) || team > kSliceTeamMax)
+                continue;
+            elig_wgs += kStreamParts * team;
+            elig_sum_idx += j.n_indices;
+            if (j.n_indices > elig_max_idx) elig_max_idx = j.n_indices;
+        }
+        const uint64_t rounds = (elig_wgs + (uint64_t)ctx->n_cu - 1) / (uint64_t)ctx->n_cu;
+        const bool slices_pay = (double)elig_max_idx * (type == CNR_IDX_I64 ? 8.0 : 4.0) * kSlicePsPerByte * (double)rounds <
+                                (double)elig_sum_idx * kFlagPsPerLookup;
         TrackBatch slices = {}, bulk = {}, direct = {};
         uint32_t n_slices = 0, n_bulk = 0, n_direct = 0;
         uint64_t slices_words = 0, slices_team = 0, bulk_idx = 0, bulk_words = 0, direct_idx = 0;
@@ -526,7 +548,7 @@ cnr_status cnr_mark_touched_batch(cnr_ctx *ctx, const cnr_table_job *jobs, uint3
             if (j.n_indices == 0) continue;
             const bool long_stream = j.mark_scratch && j.n_rows && j.n_indices > j.n_rows / 256 + 65536;
             const uint64_t team = (j.n_rows + kSliceRows - 1) / kSliceRows;
-            const bool use_slices = long_stream && team <= kSliceTeamMax;
+            const bool use_slices = long_stream && team <= kSliceTeamMax && slices_pay;
             TrackJob &t = use_slices ? slices.job[n_slices++] : long_stream ? bulk.job[n_bulk++] : direct.job[n_direct++];
             t.bitmap = j.bitmap;
             t.n_rows = j.n_rows;
