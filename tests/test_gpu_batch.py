@@ -119,10 +119,11 @@ def test_batched_checkpoint_equals_oracle_and_single_calls(ctx, bits, dim, which
 @pytest.mark.parametrize("dtype", [torch.int64, torch.int32])
 def test_batched_mark_takes_each_table_by_its_own_route(ctx, dtype):
     # one batch whose tables need all three routes of the mark: bitmap slices in LDS with teams of one,
-    # two and three workgroups, flag bytes for a table too large for that, atomics for short streams
+    # two and three workgroups (four tables with long streams, so that the call's estimate favours the
+    # slices for them), flag bytes for a table too large for that, atomics for short streams
     slice_rows = 32 * 40960
-    sizes = [3 * slice_rows - 5, 100, 16 * slice_rows + 77, slice_rows + 1, 40_000, slice_rows]
-    n_idx = [400_001, 50, 500_003, 300_000, 100, 0]
+    sizes = [3 * slice_rows - 5, 100, 16 * slice_rows + 77, slice_rows + 1, 40_000, slice_rows, 2 * slice_rows + 3, slice_rows - 1]
+    n_idx = [400_001, 50, 500_003, 300_000, 100, 0, 390_000, 380_003]
     print("case mixed-route mark dtype=%s" % dtype, flush=True)
     g = torch.Generator(device=DEV).manual_seed(77)
     cks = [P.TableCheckpointer(ctx, n, 16, device=DEV, mark_scratch=P.TableCheckpointer.new_mark_scratch(n, DEV))
