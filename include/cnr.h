@@ -23,7 +23,8 @@
  *   cnr_select_greedy_params   greedy parameters by profiling a sample (Section 5.2)
  *   cnr_host_writer_*, cnr_encode_to_host   chunked encode into host memory with the copy of one
  *                      chunk overlapping the encode of the next (Sections 4.4, 5.2)
- *   cnr_restore_from_host   the way back: chunked copy from host memory overlapping the restore
+ *   cnr_restore_from_host   the way back: the restore reads pinned host memory itself over the host
+ *                      link, or takes it chunk by chunk with the copy overlapping the restore
  *   cnr_policy_*       the incremental-checkpoint policies (Section 5.1), host only
  *   cnr_select_bits    the code width for an expected number of resumes (Section 6.2.1), host only
  *
@@ -80,7 +81,8 @@ typedef enum {
     CNR_E_INDEX_RANGE = 6, /* device: look-up indices outside [0, n_rows) were skipped (poll only) */
     CNR_E_ROW_ID = 7,      /* device: a row id >= n_rows was skipped (poll only) */
     CNR_E_HIP = 8,         /* a HIP runtime call failed; see cnr_last_hip_error */
-    CNR_E_TOO_LARGE = 9    /* a size beyond the fixed maximum of an entry point that allocates nothing */
+    CNR_E_TOO_LARGE = 9,   /* a size beyond the fixed maximum of an entry point that allocates nothing */
+    CNR_E_HOST_MEMORY = 10 /* a host buffer that a kernel was to read itself is not pinned, device-accessible memory */
 } cnr_status;
 
 typedef enum { CNR_IDX_I32 = 0, CNR_IDX_I64 = 1 } cnr_index_type;
@@ -330,13 +332,26 @@ cnr_status cnr_restore_rows_batch(cnr_ctx *ctx, const cnr_table_job *jobs /* hos
  * cnr_restore_from_host is the way back (Section 5.1: resume = baseline + incremental checkpoint;
  * Section 6.2: the checkpoint is de-quantized when it is loaded): the same staging sets take the n
  * rows of a checkpoint from host memory chunk by chunk, and every chunk is de-quantized and
- * written over `table` as cnr_restore_rows does; with `overlap` != 0 the copy of one chunk runs on
- * the writer's stream while the chunk before it is restored on `stream`.  The copies start after
- * everything enqueued on `stream` before the call.  It only enqueues work; the host buffers may be
- * reused after cnr_host_writer_wait.
+ * written over `table` as cnr_restore_rows does; with `overlap` == CNR_HOST_OVERLAP the copy of one
+ * chunk runs on the writer's stream while the chunk before it is restored on `stream`, with
+ * CNR_HOST_SERIAL the copies run on `stream` too.  The copies start after everything enqueued on
+ * `stream` before the call.  With CNR_HOST_DIRECT nothing is copied and nothing staged: one restore
+ * kernel on `stream` reads ids, scale, bias and codes from the host buffers over the host link while
+ * it writes the rows (each byte crosses the link once and is never written to device memory first);
+ * the host buffers must then be pinned, device-accessible memory (hipHostMalloc and what wraps it),
+ * 16-byte aligned, else CNR_E_HOST_MEMORY or CNR_E_ALIGN is returned and nothing is launched.
+ * The call only enqueues work; the host buffers may be reused after cnr_host_writer_wait.
  *   host_row_ids    host uint32 [n]; NULL means rows 0 .. n-1 of the table (a full checkpoint)
- *   host_scale, host_bias, host_packed   as cnr_encode_to_host wrote them */
+ *   host_scale, host_bias, host_packed   as cnr_encode_to_host wrote them
+ *   overlap         a cnr_host_path; cnr_encode_to_host takes CNR_HOST_SERIAL or CNR_HOST_OVERLAP
+ *                   (CNR_E_INVALID otherwise) */
 typedef struct cnr_host_writer cnr_host_writer; /* opaque */
+
+typedef enum cnr_host_path {
+    CNR_HOST_SERIAL = 0,  /* copies on the caller's stream, in order with the kernels */
+    CNR_HOST_OVERLAP = 1, /* copies on the writer's stream, overlapping the kernels of the neighbouring chunk */
+    CNR_HOST_DIRECT = 2   /* cnr_restore_from_host only: the kernel reads the pinned host buffers itself */
+} cnr_host_path;
 
 size_t cnr_host_writer_device_bytes(uint32_t dim, int bits, uint64_t chunk_rows);
 cnr_status cnr_host_writer_create(cnr_ctx *ctx, uint32_t dim, int bits, uint64_t chunk_rows, cnr_host_writer **out);

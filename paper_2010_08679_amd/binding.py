@@ -19,7 +19,8 @@ from . import build as _build
 
 CNR_OK = 0
 CNR_E_INVALID, CNR_E_BITS, CNR_E_DIM, CNR_E_ALIGN = 1, 2, 3, 4
-CNR_E_CAPACITY, CNR_E_INDEX_RANGE, CNR_E_ROW_ID, CNR_E_HIP, CNR_E_TOO_LARGE = 5, 6, 7, 8, 9
+CNR_E_CAPACITY, CNR_E_INDEX_RANGE, CNR_E_ROW_ID, CNR_E_HIP, CNR_E_TOO_LARGE, CNR_E_HOST_MEMORY = 5, 6, 7, 8, 9, 10
+CNR_HOST_SERIAL, CNR_HOST_OVERLAP, CNR_HOST_DIRECT = 0, 1, 2
 CNR_NOALLOC_MAX_ROWS = 1 << 30
 CNR_IDX_I32, CNR_IDX_I64 = 0, 1
 CNR_RANGE_MINMAX, CNR_RANGE_GREEDY, CNR_RANGE_SYMMETRIC = 0, 1, 2
@@ -424,8 +425,9 @@ def _host(t, dtype, name: str, n_items: int):
 
 
 def cnr_encode_to_host(writer, table, n_rows: int, dim: int, bits: int, row_ids, n: int, mode: int, greedy,
-                       host_row_ids, host_scale, host_bias, host_packed, overlap: bool = True, stream=None) -> None:
-    """``dim`` and ``bits`` are the writer's (used here to check the host buffers' sizes)."""
+                       host_row_ids, host_scale, host_bias, host_packed, overlap=CNR_HOST_OVERLAP, stream=None) -> None:
+    """``dim`` and ``bits`` are the writer's (used here to check the host buffers' sizes); ``overlap`` is
+    CNR_HOST_SERIAL or CNR_HOST_OVERLAP (False and True mean the same)."""
     gp = None
     if greedy is not None:
         gp = ctypes.pointer(cnr_greedy_params(int(greedy[0]), float(greedy[1])))
@@ -437,19 +439,20 @@ def cnr_encode_to_host(writer, table, n_rows: int, dim: int, bits: int, row_ids,
                                      gp, _host(host_row_ids, U32, "host_row_ids", n),
                                      _host(host_scale, F32, "host_scale", n), _host(host_bias, F32, "host_bias", n),
                                      _host(host_packed, U8, "host_packed", n * cnr_packed_row_bytes(dim, bits)),
-                                     1 if overlap else 0, _stream(stream)), "cnr_encode_to_host")
+                                     int(overlap), _stream(stream)), "cnr_encode_to_host")
 
 
 def cnr_restore_from_host(writer, table, n_rows: int, dim: int, bits: int, host_row_ids, host_scale, host_bias,
-                          host_packed, n: int, overlap: bool = True, stream=None) -> None:
-    """``dim`` and ``bits`` are the writer's (used here to check the buffers' sizes)."""
+                          host_packed, n: int, overlap=CNR_HOST_OVERLAP, stream=None) -> None:
+    """``dim`` and ``bits`` are the writer's (used here to check the buffers' sizes); ``overlap`` is
+    CNR_HOST_SERIAL, CNR_HOST_OVERLAP (False and True mean the same) or CNR_HOST_DIRECT."""
     if table.numel() < n_rows * dim:
         raise ValueError("table smaller than n_rows * dim")
     _check(load().cnr_restore_from_host(writer, _dev(table, F32, "table"), n_rows,
                                         _host(host_row_ids, U32, "host_row_ids", n),
                                         _host(host_scale, F32, "host_scale", n), _host(host_bias, F32, "host_bias", n),
                                         _host(host_packed, U8, "host_packed", n * cnr_packed_row_bytes(dim, bits)),
-                                        n, 1 if overlap else 0, _stream(stream)), "cnr_restore_from_host")
+                                        n, int(overlap), _stream(stream)), "cnr_restore_from_host")
 
 
 def cnr_host_writer_wait(writer, stream=None) -> None:

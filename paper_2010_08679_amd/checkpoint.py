@@ -272,11 +272,14 @@ class HostCheckpointWriter:
         B.cnr_host_writer_wait(self.writer, main)
         return n_rows
 
-    def restore_from_host(self, table: torch.Tensor, n_rows: int, n: int, overlap: bool = True,
+    def restore_from_host(self, table: torch.Tensor, n_rows: int, n: int, overlap=B.CNR_HOST_DIRECT,
                           with_ids: bool = True) -> None:
         """Writes the first ``n`` rows held in the pinned host buffers (as :meth:`encode_to_host` left
-        them, or as a loader filled them) over ``table``: the copy of chunk c+1 from host memory
-        overlaps the de-quantize-and-scatter of chunk c.  Synchronises at the end."""
+        them, or as a loader filled them) over ``table``.  By default the restore kernel reads the
+        pinned buffers itself over the host link (``CNR_HOST_DIRECT``); with ``CNR_HOST_OVERLAP`` (or
+        True) the copy of chunk c+1 from host memory overlaps the de-quantize-and-scatter of chunk c,
+        with ``CNR_HOST_SERIAL`` (or False) copies and kernels alternate on one stream.  Synchronises
+        at the end."""
         main = torch.cuda.current_stream()
         B.cnr_restore_from_host(self.writer, table, n_rows, self.dim, self.bits,
                                 self.host["row_ids"] if with_ids else None, self.host["scale"], self.host["bias"],

@@ -130,6 +130,7 @@ const char *cnr_status_str(cnr_status s) {
         case CNR_E_ROW_ID: return "row id outside the table was skipped";
         case CNR_E_HIP: return "HIP runtime error";
         case CNR_E_TOO_LARGE: return "size beyond the fixed maximum of a call that allocates nothing";
+        case CNR_E_HOST_MEMORY: return "host buffer is not pinned, device-accessible memory";
     }
     return "unknown status";
 }

@@ -9,7 +9,11 @@
 //
 // The way back (Section 5.1, resume: baseline + incremental checkpoint; Section 6.2: de-quantize
 // on load) runs through the same staging sets in the other direction: chunk c + 1 is copied from
-// host memory while chunk c is de-quantized and scattered into the table.
+// host memory while chunk c is de-quantized and scattered into the table.  When the host buffers are
+// pinned there is a shorter way: the restore kernel reads them itself.  Its loads cross the host link
+// while its stores go to the table, so the link is busy from the first wave to the last, no byte is
+// written to device memory before it is used, and no copy engine, second stream or event is involved
+// (measured 56-57 GB/s against 50 GB/s for the copies of the staged way).
 #include <new>
 
 #include "cnr_common.h"
@@ -32,6 +36,21 @@ struct cnr_host_writer {
 };
 
 namespace {
+
+// The address under which a kernel reaches pinned host memory, or nullptr (and *ok cleared) when p is
+// not such memory.  A failed query leaves its error code with the runtime: it is taken out again, so
+// that the next call of the caller does not report it.
+template <typename T>
+const T *device_view(const T *p, bool *ok) {
+    if (!p) return nullptr;
+    void *d = nullptr;
+    if (hipHostGetDevicePointer(&d, const_cast<T *>(p), 0) != hipSuccess || !d) {
+        (void)hipGetLastError();
+        *ok = false;
+        return nullptr;
+    }
+    return static_cast<const T *>(d);
+}
 
 void release(cnr_host_writer *w) {
     for (int b = 0; b < 2; ++b) {
@@ -114,8 +133,9 @@ cnr_status cnr_encode_to_host(cnr_host_writer *w, const float *table, uint64_t n
     if (n == 0) return CNR_OK;
     if (!host_scale || !host_bias || !host_packed || (row_ids && !host_row_ids)) return CNR_E_INVALID;
     if (!row_ids && n > n_rows) return CNR_E_INVALID;  // without a row list the rows are 0 .. n-1 of the table
+    if (overlap != CNR_HOST_SERIAL && overlap != CNR_HOST_OVERLAP) return CNR_E_INVALID;
     hipStream_t main = as_stream(stream);
-    hipStream_t copier = overlap ? w->copy : main;
+    hipStream_t copier = overlap == CNR_HOST_OVERLAP ? w->copy : main;
     hipError_t e = hipSuccess;
     uint64_t c = 0;
     for (uint64_t k0 = 0; k0 < n && e == hipSuccess; k0 += w->chunk_rows, ++c) {
@@ -162,8 +182,18 @@ cnr_status cnr_restore_from_host(cnr_host_writer *w, float *table, uint64_t n_ro
     if (n == 0) return CNR_OK;
     if (!table || !host_scale || !host_bias || !host_packed || n_rows == 0) return CNR_E_INVALID;
     if (!host_row_ids && n > n_rows) return CNR_E_INVALID;  // without ids the rows are 0 .. n-1 of the table
+    if (overlap < CNR_HOST_SERIAL || overlap > CNR_HOST_DIRECT) return CNR_E_INVALID;
+    if (overlap == CNR_HOST_DIRECT) {
+        bool pinned = true;
+        const uint32_t *ids = device_view(host_row_ids, &pinned);
+        const float *scale = device_view(host_scale, &pinned);
+        const float *bias = device_view(host_bias, &pinned);
+        const uint8_t *packed = device_view(host_packed, &pinned);
+        if (!pinned) return CNR_E_HOST_MEMORY;
+        return cnr_restore_rows(ctx, table, n_rows, w->dim, ids, nullptr, n, w->bits, packed, scale, bias, stream);
+    }
     hipStream_t main = as_stream(stream);
-    hipStream_t copier = overlap ? w->copy : main;
+    hipStream_t copier = overlap == CNR_HOST_OVERLAP ? w->copy : main;
     hipError_t e = hipSuccess;
     if (copier != main) {
         // whatever the caller's stream still does with the staging sets or the host buffers comes first

@@ -545,13 +545,16 @@ def test_chunked_encode_to_host_equals_one_shot_encode(ctx, overlap):
     _poll_clean(ctx)
 
 
-@pytest.mark.parametrize("overlap", [True, False])
+@pytest.mark.parametrize("overlap", [True, False, "direct"])
 @pytest.mark.parametrize("with_ids", [True, False])
 def test_round_trip_through_host_memory(ctx, overlap, with_ids):
     # checkpoint to host memory in chunks, then the way back: the table restored from the host buffers
-    # chunk by chunk equals the one restored by a single call from the device-side encode, and the oracle's
+    # (chunk by chunk through the staging sets, or by a kernel that reads the pinned buffers itself)
+    # equals the one restored by a single call from the device-side encode, and the oracle's
     n_rows, dim, bits = 60_017, 64, 4
     print("case host round trip overlap=%s with_ids=%s" % (overlap, with_ids), flush=True)
+    back_path = P.CNR_HOST_DIRECT if overlap == "direct" else overlap
+    overlap = overlap is not False
     table = synth.table_outlier_mix(n_rows, dim, 0.02, 41, DEV)
     ck = P.TableCheckpointer(ctx, n_rows, dim, device=DEV)
     ck.clear()
@@ -576,7 +579,7 @@ def test_round_trip_through_host_memory(ctx, overlap, with_ids):
     ck.restore(direct, enc)
     for rep in range(2):                                        # twice: the staging sets are reused
         back = torch.full_like(table, -3.0)
-        writer.restore_from_host(back, n_rows, n, overlap=overlap, with_ids=with_ids)
+        writer.restore_from_host(back, n_rows, n, overlap=back_path, with_ids=with_ids)
         assert torch.equal(back, direct)
     want = np.full((n_rows, dim), -3.0, dtype=np.float32)
     O.restore_rows(want, ids, bits, writer.host["packed"][:n * writer.prb].numpy().reshape(n, -1),
@@ -586,16 +589,87 @@ def test_round_trip_through_host_memory(ctx, overlap, with_ids):
     main = torch.cuda.current_stream()
     back.fill_(-3.0)
     P.cnr_restore_from_host(writer.writer, back, n_rows, dim, bits, writer.host["row_ids"] if with_ids else None,
-                            writer.host["scale"], writer.host["bias"], writer.host["packed"], n, overlap, main)
+                            writer.host["scale"], writer.host["bias"], writer.host["packed"], n, back_path, main)
     assert writer.encode_to_host(ck, back, overlap=overlap) == n   # encodes the table just restored
     again = torch.full_like(table, -3.0)
-    writer.restore_from_host(again, n_rows, n, overlap=overlap, with_ids=with_ids)
+    writer.restore_from_host(again, n_rows, n, overlap=back_path, with_ids=with_ids)
     torch.cuda.synchronize()
     q = O.quantize_rows(want, ids, bits, n_threads=4)           # the oracle's encode of its own restored table
     want2 = np.full((n_rows, dim), -3.0, dtype=np.float32)
     O.restore_rows(want2, ids, bits, O.pack(q["codes"], bits), q["scale"], q["bias"])
     got2 = again.cpu().numpy()
     assert np.mean(got2 != want2) <= 1e-4 and np.array_equal(got2[want2 == -3.0], want2[want2 == -3.0])
+    writer.close()
+    _poll_clean(ctx)
+
+
+@pytest.mark.parametrize("dim,bits", [(64, 2), (64, 3), (64, 8), (128, 4), (128, 8), (256, 3), (32, 4), (8, 8)])
+def test_restore_reading_pinned_host_memory_itself(ctx, dim, bits):
+    # every restore kernel shape with its inputs in pinned host memory: the same table as from the
+    # device-side copies of those inputs, and as the oracle's restore; a ragged row count, twice
+    n_rows = 20_011
+    print("case restore straight from host dim=%d bits=%d" % (dim, bits), flush=True)
+    table = synth.table_outlier_mix(n_rows, dim, 0.02, 43, DEV)
+    ck = P.TableCheckpointer(ctx, n_rows, dim, device=DEV)
+    ck.clear()
+    ck.mark(synth.bernoulli_lookup_stream(n_rows, 0.35, 9, DEV))
+    ck.compact()
+    writer = P.HostCheckpointWriter(ctx, dim, bits, capacity=n_rows, chunk_rows=4096, device=DEV)
+    n = writer.encode_to_host(ck, table)
+    enc = ck.alloc_output(bits)
+    ck.encode(table, enc)
+    from_device = torch.full_like(table, 7.0)
+    ck.restore(from_device, enc)
+    for rep in range(2):
+        back = torch.full_like(table, 7.0)
+        writer.restore_from_host(back, n_rows, n, overlap=P.CNR_HOST_DIRECT)
+        assert torch.equal(back, from_device)
+    ids = writer.host["row_ids"][:n].numpy().view(np.uint32)
+    want = np.full((n_rows, dim), 7.0, dtype=np.float32)
+    O.restore_rows(want, ids, bits, writer.host["packed"][:n * writer.prb].numpy().reshape(n, -1),
+                   writer.host["scale"][:n].numpy(), writer.host["bias"][:n].numpy())
+    assert np.array_equal(back.cpu().numpy(), want)
+    writer.close()
+    _poll_clean(ctx)
+
+
+def test_restore_straight_from_host_refuses_pageable_memory(ctx):
+    # a buffer the GPU cannot reach is refused on the host, nothing is launched, the table stays as it
+    # was, and the runtime is left without a pending error: the same call with copies then works
+    n_rows, dim, bits = 5_003, 64, 4
+    print("case restore straight from host, pageable buffers", flush=True)
+    table = synth.table_normal(n_rows, dim, 0.02, 45, DEV)
+    ck = P.TableCheckpointer(ctx, n_rows, dim, device=DEV)
+    ck.clear()
+    ck.mark(synth.bernoulli_lookup_stream(n_rows, 0.5, 11, DEV))
+    ck.compact()
+    writer = P.HostCheckpointWriter(ctx, dim, bits, capacity=n_rows, chunk_rows=1024, device=DEV)
+    n = writer.encode_to_host(ck, table)
+    pinned = writer.host
+    pageable = {k: v.clone() for k, v in pinned.items()}          # plain host memory
+    assert not any(v.is_pinned() for v in pageable.values())
+    main = torch.cuda.current_stream()
+    for bad in ("row_ids", "scale", "bias", "packed"):
+        bufs = dict(pinned)
+        bufs[bad] = pageable[bad]
+        back = torch.full_like(table, 7.0)
+        with pytest.raises(P.CnrError) as e:
+            P.cnr_restore_from_host(writer.writer, back, n_rows, dim, bits, bufs["row_ids"], bufs["scale"], bufs["bias"],
+                                    bufs["packed"], n, P.CNR_HOST_DIRECT, main)
+        assert e.value.status == P.CNR_E_HOST_MEMORY, bad
+        torch.cuda.synchronize()
+        assert bool((back == 7.0).all())
+    want = torch.full_like(table, 7.0)
+    writer.restore_from_host(want, n_rows, n, overlap=P.CNR_HOST_DIRECT)
+    back = torch.full_like(table, 7.0)
+    P.cnr_restore_from_host(writer.writer, back, n_rows, dim, bits, pageable["row_ids"], pageable["scale"],
+                            pageable["bias"], pageable["packed"], n, P.CNR_HOST_SERIAL, main)
+    P.cnr_host_writer_wait(writer.writer, main)
+    assert torch.equal(back, want)
+    with pytest.raises(P.CnrError) as e:                          # the encode has no such path
+        P.cnr_encode_to_host(writer.writer, table, n_rows, dim, bits, ck.row_ids, n, P.CNR_RANGE_MINMAX, None,
+                             pinned["row_ids"], pinned["scale"], pinned["bias"], pinned["packed"], P.CNR_HOST_DIRECT, main)
+    assert e.value.status == P.CNR_E_INVALID
     writer.close()
     _poll_clean(ctx)
 

@@ -64,8 +64,8 @@ def test_policy_predictor_matches_oracle():
 
 
 def test_status_strings():
-    seen = {P.status_str(s) for s in range(10)}
-    assert len(seen) == 10 and "ok" in seen
+    seen = {P.status_str(s) for s in range(11)}
+    assert len(seen) == 11 and "ok" in seen
 
 
 def test_binding_refuses_host_tensors_and_wrong_dtypes():
