@@ -10,6 +10,9 @@
 //      (Sections 5.1, 5.2): rows of 256 bytes, 30 % of a 20 M-row table in ascending order, gathered
 //      (read only) and scattered (written only) with the kernels' lane mapping (16 lanes per row, 16
 //      bytes per lane), next to a sequential read, write and copy of the same table.
+//   3. what the host link sustains for 64 MiB of pinned host memory (the size of one table's
+//      incremental checkpoint, Sections 4.4 and 5.1): read and written by a kernel directly, and
+//      moved by the runtime's asynchronous copies.
 //
 //   hipcc --offload-arch=gfx950 -O3 -std=c++17 bench_ceilings.hip -o bench_ceilings && ./bench_ceilings
 #include <hip/hip_runtime.h>
@@ -124,14 +127,14 @@ __global__ void __launch_bounds__(256) stream_kernel(const f32x4 *__restrict__ a
     if (acc == 123.456f) out[0] = acc;
 }
 template <typename F>
-static float time_us(F launch, int reps) {
+static float time_us(F launch, int reps, hipStream_t stream = 0) {
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return -1;
     launch();
     launch();
-    if (hipDeviceSynchronize() != hipSuccess || hipEventRecord(e0) != hipSuccess) return -1;
+    if (hipDeviceSynchronize() != hipSuccess || hipEventRecord(e0, stream) != hipSuccess) return -1;
     for (int i = 0; i < reps; ++i) launch();
-    if (hipEventRecord(e1) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) return -1;
+    if (hipEventRecord(e1, stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) return -1;
     float ms = 0;
     if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) return -1;
     return ms / reps * 1e3f;
@@ -170,6 +173,37 @@ static int memory_ceilings(float *out) {
     return 0;
 }
 
+static int host_link_ceilings(float *out) {
+    const uint64_t bytes = 64ull << 20, n16 = bytes / 16;
+    void *host = nullptr, *host_dev = nullptr;
+    float *dev = nullptr;
+    if (hipHostMalloc(&host, bytes, hipHostMallocDefault) != hipSuccess || hipHostGetDevicePointer(&host_dev, host, 0) != hipSuccess ||
+        hipMalloc(&dev, bytes) != hipSuccess || hipMemset(dev, 0, bytes) != hipSuccess)
+        return 1;
+    for (uint64_t i = 0; i < bytes / 4; ++i) ((float *)host)[i] = 1.0f;
+    for (unsigned grid : {256u, 1024u, 4096u}) {
+        const float r = time_us([&] { stream_kernel<2><<<grid, 256>>>((const f32x4 *)host_dev, (f32x4 *)dev, n16, out); }, 5);
+        const float w = time_us([&] { stream_kernel<2><<<grid, 256>>>((const f32x4 *)dev, (f32x4 *)host_dev, n16, out); }, 5);
+        if (r < 0 || w < 0) return 1;
+        printf("64 MiB of pinned host memory, %4u workgroups: a kernel reads it at %5.1f GB/s, writes it at %5.1f GB/s\n", grid,
+               bytes / r / 1e3, bytes / w / 1e3);
+    }
+    hipStream_t s;
+    if (hipStreamCreateWithFlags(&s, hipStreamNonBlocking) != hipSuccess) return 1;
+    for (int round = 0; round < 2; ++round) {
+        const float cr = time_us([&] { (void)hipMemcpyAsync(dev, host, bytes, hipMemcpyHostToDevice, s); }, 10, s);
+        const float cw = time_us([&] { (void)hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, s); }, 10, s);
+        if (cr < 0 || cw < 0) return 1;
+        printf("the runtime's asynchronous copy of the same 64 MiB on a stream: host to device %5.1f GB/s, device to host %5.1f GB/s\n",
+               bytes / cr / 1e3, bytes / cw / 1e3);
+    }
+    (void)hipStreamDestroy(s);
+    if (hipDeviceSynchronize() != hipSuccess) return 1;
+    (void)hipFree(dev);
+    (void)hipHostFree(host);
+    return 0;
+}
+
 int main() {
     float *out;
     if (hipMalloc(&out, 4) != hipSuccess) return 1;
@@ -185,6 +219,7 @@ int main() {
     rc |= run<ADD_F64>("v_add_f64", 32, out);
     rc |= run<GREEDY_MIX>("greedy element (9 instructions)", 72, out);
     rc |= memory_ceilings(out);
+    rc |= host_link_ceilings(out);
     if (hipDeviceSynchronize() != hipSuccess) rc = 1;
     (void)hipFree(out);
     return rc;
