@@ -475,7 +475,8 @@ def main() -> int:
             ts.sort()
             return ts[len(ts) // 2], ts[-1], max(warm_ts)
         res, back, n_h = {}, {}, 0
-        for label, overlap in (("overlapped", True), ("serialized", False)):
+        for label, overlap in (("direct", P.CNR_HOST_DIRECT), ("overlapped", P.CNR_HOST_OVERLAP),
+                               ("serialized", P.CNR_HOST_SERIAL)):
             def to_host():
                 nonlocal n_h
                 n_h = writer.encode_to_host(cks[0], tables[0], overlap=overlap)
@@ -488,12 +489,18 @@ def main() -> int:
         for label, overlap in (("direct", P.CNR_HOST_DIRECT), ("overlapped", P.CNR_HOST_OVERLAP),
                                ("serialized", P.CNR_HOST_SERIAL)):
             back[label] = median_s(lambda: writer.restore_from_host(stale[0], w.n_rows, n_h, overlap=overlap), reps=50, warm=16)
-        out["to_host"] = {"workload": "table 0: %d dirty rows encoded in chunks of %d rows into pinned host memory; "
-                                      "median of 7 calls" % (n_h, writer.chunk),
+        # `value` is the way the writer takes by default for this row length
+        to_path = "direct" if writer._to_host_path(None) == P.CNR_HOST_DIRECT else "overlapped"
+        out["to_host"] = {"workload": "table 0: %d dirty rows encoded into pinned host memory, by the encode kernel's "
+                                      "own stores (direct) or in chunks of %d rows with staged copies; median of 7 "
+                                      "calls" % (n_h, writer.chunk),
+                          "direct_ms": round(res["direct"][0] * 1e3, 3),
                           "overlapped_ms": round(res["overlapped"][0] * 1e3, 3),
                           "serialized_ms": round(res["serialized"][0] * 1e3, 3),
-                          "slowest_call_ms": round(max(res["overlapped"][1], res["serialized"][1]) * 1e3, 3),
-                          "value": round(n_h * w.dim * 4 / res["overlapped"][0] / 1e9, 1), "unit": "GB/s",
+                          "slowest_call_ms": round(max(r[1] for r in res.values()) * 1e3, 3),
+                          "path": to_path,
+                          "host_link_GBps": round(n_h * (12 + writer.prb) / res[to_path][0] / 1e9, 1),
+                          "value": round(n_h * w.dim * 4 / res[to_path][0] / 1e9, 1), "unit": "GB/s",
                           "host_bytes": int(n_h * (12 + writer.prb))}
         out["from_host"] = {"workload": "table 0: the same %d rows restored from pinned host memory, read by the "
                                         "restore kernel itself (direct) or copied in chunks of %d rows first; median "

@@ -82,7 +82,7 @@ typedef enum {
     CNR_E_ROW_ID = 7,      /* device: a row id >= n_rows was skipped (poll only) */
     CNR_E_HIP = 8,         /* a HIP runtime call failed; see cnr_last_hip_error */
     CNR_E_TOO_LARGE = 9,   /* a size beyond the fixed maximum of an entry point that allocates nothing */
-    CNR_E_HOST_MEMORY = 10 /* a host buffer that a kernel was to read itself is not pinned, device-accessible memory */
+    CNR_E_HOST_MEMORY = 10 /* a host buffer that a kernel was to access itself is not pinned, device-accessible memory */
 } cnr_status;
 
 typedef enum { CNR_IDX_I32 = 0, CNR_IDX_I64 = 1 } cnr_index_type;
@@ -319,7 +319,12 @@ cnr_status cnr_restore_rows_batch(cnr_ctx *ctx, const cnr_table_job *jobs /* hos
  * slice of row_ids, into the host buffers; with `overlap` != 0 the copies run on the writer's stream
  * while the next chunk is encoded, else on `stream` itself.  It only enqueues work; the host buffers
  * are complete after cnr_host_writer_wait (which synchronizes both streams).  One call at a time per
- * writer.
+ * writer.  With CNR_HOST_DIRECT nothing is staged: one encode kernel on `stream` stores scale, bias and
+ * codes into the host buffers over the host link, and the id list is copied on the writer's stream
+ * meanwhile; the host buffers must then be pinned, device-accessible memory, 16-byte aligned
+ * (CNR_E_HOST_MEMORY, CNR_E_ALIGN).  Rows of up to 64 elements leave a wave as one contiguous block and
+ * this way is then slightly faster than the staged one; longer rows leave in pieces that the link does
+ * not merge (a fifth slower at 128 elements), and the staged way is the better one.
  *   n               host value: the number of rows (read it back from cnr_compact_dirty's count first)
  *   row_ids         device, uint32 [n], 16-byte aligned; NULL means rows 0 .. n-1 of the table (a
  *                   full checkpoint)
@@ -343,14 +348,13 @@ cnr_status cnr_restore_rows_batch(cnr_ctx *ctx, const cnr_table_job *jobs /* hos
  * The call only enqueues work; the host buffers may be reused after cnr_host_writer_wait.
  *   host_row_ids    host uint32 [n]; NULL means rows 0 .. n-1 of the table (a full checkpoint)
  *   host_scale, host_bias, host_packed   as cnr_encode_to_host wrote them
- *   overlap         a cnr_host_path; cnr_encode_to_host takes CNR_HOST_SERIAL or CNR_HOST_OVERLAP
- *                   (CNR_E_INVALID otherwise) */
+ *   overlap         a cnr_host_path (CNR_E_INVALID for any other value) */
 typedef struct cnr_host_writer cnr_host_writer; /* opaque */
 
 typedef enum cnr_host_path {
     CNR_HOST_SERIAL = 0,  /* copies on the caller's stream, in order with the kernels */
     CNR_HOST_OVERLAP = 1, /* copies on the writer's stream, overlapping the kernels of the neighbouring chunk */
-    CNR_HOST_DIRECT = 2   /* cnr_restore_from_host only: the kernel reads the pinned host buffers itself */
+    CNR_HOST_DIRECT = 2   /* no copies of the data: the kernel reads or writes the pinned host buffers itself */
 } cnr_host_path;
 
 size_t cnr_host_writer_device_bytes(uint32_t dim, int bits, uint64_t chunk_rows);

@@ -427,7 +427,7 @@ def _host(t, dtype, name: str, n_items: int):
 def cnr_encode_to_host(writer, table, n_rows: int, dim: int, bits: int, row_ids, n: int, mode: int, greedy,
                        host_row_ids, host_scale, host_bias, host_packed, overlap=CNR_HOST_OVERLAP, stream=None) -> None:
     """``dim`` and ``bits`` are the writer's (used here to check the host buffers' sizes); ``overlap`` is
-    CNR_HOST_SERIAL or CNR_HOST_OVERLAP (False and True mean the same)."""
+    CNR_HOST_SERIAL, CNR_HOST_OVERLAP (False and True mean the same) or CNR_HOST_DIRECT."""
     gp = None
     if greedy is not None:
         gp = ctypes.pointer(cnr_greedy_params(int(greedy[0]), float(greedy[1])))

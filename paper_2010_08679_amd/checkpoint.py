@@ -245,11 +245,20 @@ class HostCheckpointWriter:
         except Exception:
             pass
 
+    def _to_host_path(self, overlap):
+        """None: the faster way for this row length (the kernel's own stores for rows of up to 64
+        elements, staged copies that overlap the encode for longer ones)."""
+        if overlap is None:
+            return B.CNR_HOST_DIRECT if self.dim <= 64 else B.CNR_HOST_OVERLAP
+        return int(overlap)
+
     def encode_to_host(self, ck: TableCheckpointer, table: torch.Tensor, mode: int = B.CNR_RANGE_MINMAX,
-                       greedy=None, overlap: bool = True) -> int:
+                       greedy=None, overlap=None) -> int:
         """Encodes the rows listed by ``ck.compact()`` and leaves ids, scale, bias and packed codes in
-        the pinned host buffers; returns the number of rows.  Synchronises at the start (the row
-        count has to reach the host to size the copies) and at the end."""
+        the pinned host buffers; returns the number of rows.  ``overlap`` is a ``CNR_HOST_*`` path
+        (True and False mean OVERLAP and SERIAL), None picks by row length.  Synchronises at the start
+        (the row count has to reach the host to size the copies) and at the end."""
+        overlap = self._to_host_path(overlap)
         main = torch.cuda.current_stream()
         self.n_host.copy_(ck.n_dirty, non_blocking=True)
         main.synchronize()
@@ -261,9 +270,10 @@ class HostCheckpointWriter:
         return n
 
     def encode_table_to_host(self, table: torch.Tensor, n_rows: int, mode: int = B.CNR_RANGE_MINMAX,
-                             greedy=None, overlap: bool = True) -> int:
+                             greedy=None, overlap=None) -> int:
         """A full (baseline) checkpoint: every row of ``table``, no id list, into the pinned host
         buffers; returns ``n_rows``.  Synchronises at the end."""
+        overlap = self._to_host_path(overlap)
         if n_rows > self.capacity:
             raise ValueError("the writer's host buffers hold %d rows" % self.capacity)
         main = torch.cuda.current_stream()

@@ -13,7 +13,9 @@
 // pinned there is a shorter way: the restore kernel reads them itself.  Its loads cross the host link
 // while its stores go to the table, so the link is busy from the first wave to the last, no byte is
 // written to device memory before it is used, and no copy engine, second stream or event is involved
-// (measured 56-57 GB/s against 50 GB/s for the copies of the staged way).
+// (measured 56-57 GB/s against 50 GB/s for the copies of the staged way).  The encode has the same
+// short way, its stores crossing the link; it pays for rows of up to 64 elements, whose codes leave
+// a wave as one contiguous block.
 #include <new>
 
 #include "cnr_common.h"
@@ -133,10 +135,28 @@ cnr_status cnr_encode_to_host(cnr_host_writer *w, const float *table, uint64_t n
     if (n == 0) return CNR_OK;
     if (!host_scale || !host_bias || !host_packed || (row_ids && !host_row_ids)) return CNR_E_INVALID;
     if (!row_ids && n > n_rows) return CNR_E_INVALID;  // without a row list the rows are 0 .. n-1 of the table
-    if (overlap != CNR_HOST_SERIAL && overlap != CNR_HOST_OVERLAP) return CNR_E_INVALID;
+    if (overlap < CNR_HOST_SERIAL || overlap > CNR_HOST_DIRECT) return CNR_E_INVALID;
     hipStream_t main = as_stream(stream);
-    hipStream_t copier = overlap == CNR_HOST_OVERLAP ? w->copy : main;
     hipError_t e = hipSuccess;
+    if (overlap == CNR_HOST_DIRECT) {
+        // The encode kernel stores scale, bias and codes into the pinned buffers itself; the id list,
+        // which exists before the encode starts, is copied on the writer's stream meanwhile.
+        bool pinned = true;
+        float *scale = const_cast<float *>(device_view(host_scale, &pinned));
+        float *bias = const_cast<float *>(device_view(host_bias, &pinned));
+        uint8_t *packed = const_cast<uint8_t *>(device_view(host_packed, &pinned));
+        if (row_ids) (void)device_view(host_row_ids, &pinned);
+        if (!pinned) return CNR_E_HOST_MEMORY;
+        if (row_ids) {
+            e = hipEventRecord(w->fence, main);  // the list is complete once `stream` gets here
+            if (e == hipSuccess) e = hipStreamWaitEvent(w->copy, w->fence, 0);
+            if (e == hipSuccess) e = hipMemcpyAsync(host_row_ids, row_ids, n * sizeof(uint32_t), hipMemcpyDeviceToHost, w->copy);
+            if (e != hipSuccess) return cnr_hip_status(ctx, e);
+        }
+        return cnr_quantize_rows(ctx, table, n_rows, w->dim, row_ids, nullptr, n, w->bits, mode, greedy, scale, bias,
+                                 nullptr, nullptr, nullptr, packed, stream);
+    }
+    hipStream_t copier = overlap == CNR_HOST_OVERLAP ? w->copy : main;
     uint64_t c = 0;
     for (uint64_t k0 = 0; k0 < n && e == hipSuccess; k0 += w->chunk_rows, ++c) {
         const uint64_t m = n - k0 < w->chunk_rows ? n - k0 : w->chunk_rows;

@@ -520,7 +520,7 @@ def test_greedy_parameter_selection_matches_oracle(ctx):
 
 # ------------------------------------------------------------------ chunked encode with overlapped copies
 
-@pytest.mark.parametrize("overlap", [True, False])
+@pytest.mark.parametrize("overlap", [P.CNR_HOST_OVERLAP, P.CNR_HOST_SERIAL, P.CNR_HOST_DIRECT])
 def test_chunked_encode_to_host_equals_one_shot_encode(ctx, overlap):
     # Sections 4.4 / 5.2: the checkpoint is built chunk by chunk, each chunk handed on while the next
     # is quantized.  The chunks must add up to exactly the unchunked result.
@@ -553,8 +553,7 @@ def test_round_trip_through_host_memory(ctx, overlap, with_ids):
     # equals the one restored by a single call from the device-side encode, and the oracle's
     n_rows, dim, bits = 60_017, 64, 4
     print("case host round trip overlap=%s with_ids=%s" % (overlap, with_ids), flush=True)
-    back_path = P.CNR_HOST_DIRECT if overlap == "direct" else overlap
-    overlap = overlap is not False
+    back_path = overlap = P.CNR_HOST_DIRECT if overlap == "direct" else int(overlap)
     table = synth.table_outlier_mix(n_rows, dim, 0.02, 41, DEV)
     ck = P.TableCheckpointer(ctx, n_rows, dim, device=DEV)
     ck.clear()
@@ -633,6 +632,45 @@ def test_restore_reading_pinned_host_memory_itself(ctx, dim, bits):
     _poll_clean(ctx)
 
 
+@pytest.mark.parametrize("dim,bits,mode", [(64, 2, "minmax"), (64, 3, "minmax"), (64, 8, "minmax"), (128, 4, "minmax"),
+                                           (128, 8, "symmetric"), (256, 3, "minmax"), (32, 4, "minmax"), (8, 8, "minmax"),
+                                           (64, 4, "greedy"), (48, 4, "minmax")])
+def test_encode_writing_pinned_host_memory_itself(ctx, dim, bits, mode):
+    # every encode kernel shape with its outputs in pinned host memory: byte for byte what the same
+    # call leaves in device buffers, nothing written past the last row, with and without an id list
+    n_rows = 20_011
+    print("case encode straight to host dim=%d bits=%d %s" % (dim, bits, mode), flush=True)
+    table = synth.table_outlier_mix(n_rows, dim, 0.02, 47, DEV)
+    ck = P.TableCheckpointer(ctx, n_rows, dim, device=DEV)
+    ck.clear()
+    ck.mark(synth.bernoulli_lookup_stream(n_rows, 0.35, 13, DEV))
+    ck.compact()
+    m = {"minmax": P.CNR_RANGE_MINMAX, "symmetric": P.CNR_RANGE_SYMMETRIC, "greedy": P.CNR_RANGE_GREEDY}[mode]
+    greedy = (20, 0.5) if mode == "greedy" else None
+    enc = ck.alloc_output(bits)
+    ck.encode(table, enc, mode=m, greedy=greedy)
+    n = enc.count()
+    writer = P.HostCheckpointWriter(ctx, dim, bits, capacity=n_rows, chunk_rows=4096, device=DEV)
+    prb = writer.prb
+    for rep in range(2):
+        for v in writer.host.values():
+            v.fill_(0x55 if v.dtype == torch.uint8 else 12345)
+        assert writer.encode_to_host(ck, table, mode=m, greedy=greedy, overlap=P.CNR_HOST_DIRECT) == n
+        assert torch.equal(writer.host["row_ids"][:n], enc.row_ids[:n].cpu())
+        assert torch.equal(writer.host["scale"][:n].view(torch.int32), enc.scale[:n].cpu().view(torch.int32))
+        assert torch.equal(writer.host["bias"][:n].view(torch.int32), enc.bias[:n].cpu().view(torch.int32))
+        assert torch.equal(writer.host["packed"][:n * prb], enc.packed[:n * prb].cpu())
+        assert bool((writer.host["row_ids"][n:] == 12345).all()) and bool((writer.host["scale"][n:] == 12345).all())
+        assert bool((writer.host["bias"][n:] == 12345).all()) and bool((writer.host["packed"][n * prb:] == 0x55).all())
+    assert writer.encode_table_to_host(table, n_rows, mode=m, greedy=greedy, overlap=P.CNR_HOST_DIRECT) == n_rows
+    staged = {k: v.clone() for k, v in writer.host.items()}
+    assert writer.encode_table_to_host(table, n_rows, mode=m, greedy=greedy, overlap=P.CNR_HOST_OVERLAP) == n_rows
+    for k in ("scale", "bias", "packed"):
+        assert torch.equal(writer.host[k].view(torch.uint8), staged[k].view(torch.uint8)), k
+    writer.close()
+    _poll_clean(ctx)
+
+
 def test_restore_straight_from_host_refuses_pageable_memory(ctx):
     # a buffer the GPU cannot reach is refused on the host, nothing is launched, the table stays as it
     # was, and the runtime is left without a pending error: the same call with copies then works
@@ -666,9 +704,19 @@ def test_restore_straight_from_host_refuses_pageable_memory(ctx):
                             pageable["bias"], pageable["packed"], n, P.CNR_HOST_SERIAL, main)
     P.cnr_host_writer_wait(writer.writer, main)
     assert torch.equal(back, want)
-    with pytest.raises(P.CnrError) as e:                          # the encode has no such path
+    for bad in ("row_ids", "scale", "bias", "packed"):            # the encode's direct way likewise
+        bufs = dict(pinned)
+        bufs[bad] = pageable[bad].clone()
+        kept = bufs[bad].clone()
+        with pytest.raises(P.CnrError) as e:
+            P.cnr_encode_to_host(writer.writer, table, n_rows, dim, bits, ck.row_ids, n, P.CNR_RANGE_MINMAX, None,
+                                 bufs["row_ids"], bufs["scale"], bufs["bias"], bufs["packed"], P.CNR_HOST_DIRECT, main)
+        assert e.value.status == P.CNR_E_HOST_MEMORY, bad
+        P.cnr_host_writer_wait(writer.writer, main)
+        assert torch.equal(bufs[bad], kept)
+    with pytest.raises(P.CnrError) as e:
         P.cnr_encode_to_host(writer.writer, table, n_rows, dim, bits, ck.row_ids, n, P.CNR_RANGE_MINMAX, None,
-                             pinned["row_ids"], pinned["scale"], pinned["bias"], pinned["packed"], P.CNR_HOST_DIRECT, main)
+                             pinned["row_ids"], pinned["scale"], pinned["bias"], pinned["packed"], 3, main)
     assert e.value.status == P.CNR_E_INVALID
     writer.close()
     _poll_clean(ctx)
