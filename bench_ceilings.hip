@@ -9,7 +9,8 @@
 //   2. what the memory system sustains for the access patterns of the encode and the restore
 //      (Sections 5.1, 5.2): rows of 256 bytes, 30 % of a 20 M-row table in ascending order, gathered
 //      (read only) and scattered (written only) with the kernels' lane mapping (16 lanes per row, 16
-//      bytes per lane), next to a sequential read, write and copy of the same table.
+//      bytes per lane), and rows of 512 bytes, 25 % of 10 M, next to a sequential read, write and
+//      copy of the same table.
 //   3. what the host link sustains for 64 MiB of pinned host memory (the size of one table's
 //      incremental checkpoint, Sections 4.4 and 5.1): read and written by a kernel directly, and
 //      moved by the runtime's asynchronous copies.
@@ -90,26 +91,43 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr uint64_t kRows = 20000000;  // rows of 64 floats: 5.12 GB
 constexpr int kRowFloats = 64;
 
-// rows ids[k], k < n, each by 16 lanes; four rows per 16-lane group and pass, as in the library's kernels
-template <bool WRITE>
+// rows ids[k], k < n, of 64 * PIECES floats, each by 16 lanes (a lane takes 16 bytes of every 256-byte
+// piece); four rows per 16-lane group and pass, as in the library's kernels
+// With SIDE > 0 every pass of 16 rows also reads 64 * SIDE consecutive bytes of `side` (what the packed
+// codes are to the restore: SIDE = 8 for 32 bytes per row, 32 for 128).
+template <bool WRITE, int PIECES, int SIDE = 0>
 __global__ void __launch_bounds__(256) sparse_rows_kernel(float *__restrict__ table, const uint32_t *__restrict__ ids, uint64_t n,
-                                                          uint32_t n_waves, float *out) {
+                                                          uint32_t n_waves, float *out, const float *__restrict__ side = nullptr) {
     const int lane = threadIdx.x & 63, g = lane >> 4, l = lane & 15;
     float acc = 0;
     for (uint64_t pass = (uint64_t)blockIdx.x * 4 + threadIdx.x / 64; pass * 16 < n; pass += n_waves) {
         const uint64_t k0 = pass * 16 + 4 * g;
+        if constexpr (SIDE == 8) {
+            typedef float f32x2 __attribute__((ext_vector_type(2)));
+            const f32x2 v = __builtin_nontemporal_load(reinterpret_cast<const f32x2 *>(side) + pass * 64 + lane);
+            acc += v.x + v.y;
+        } else if constexpr (SIDE >= 16) {
+#pragma unroll
+            for (int i = 0; i < SIDE / 16; ++i) {
+                const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(side) + (pass * (SIDE / 16) + i) * 64 + lane);
+                acc += v.x + v.w;
+            }
+        }
         uint32_t rid[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) rid[u] = k0 + u < n ? ids[k0 + u] : 0xFFFFFFFFu;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             if (rid[u] == 0xFFFFFFFFu) continue;  // ids are below kRows by construction
-            f32x4 *p = reinterpret_cast<f32x4 *>(table + (uint64_t)rid[u] * kRowFloats + 4 * l);
-            if (WRITE) {
-                __builtin_nontemporal_store(f32x4{1.f, 2.f, (float)l, (float)u}, p);
-            } else {
-                const f32x4 v = __builtin_nontemporal_load(p);
-                acc += v.x + v.y + v.z + v.w;
+            f32x4 *p = reinterpret_cast<f32x4 *>(table + (uint64_t)rid[u] * (kRowFloats * PIECES) + 4 * l);
+#pragma unroll
+            for (int c = 0; c < PIECES; ++c) {
+                if (WRITE) {
+                    __builtin_nontemporal_store(f32x4{1.f, 2.f, (float)l, (float)u}, p + 16 * c);
+                } else {
+                    const f32x4 v = __builtin_nontemporal_load(p + 16 * c);
+                    acc += v.x + v.y + v.z + v.w;
+                }
             }
         }
     }
@@ -139,21 +157,46 @@ static float time_us(F launch, int reps, hipStream_t stream = 0) {
     if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) return -1;
     return ms / reps * 1e3f;
 }
-static int memory_ceilings(float *out) {
-    float *t[2];
-    for (int i = 0; i < 2; ++i)
-        if (hipMalloc(&t[i], kRows * kRowFloats * 4) != hipSuccess || hipMemset(t[i], 0, kRows * kRowFloats * 4) != hipSuccess) return 1;
+// a fraction of the rows of 64 * PIECES floats of the same 5.12 GB, ascending: gathered, then scattered
+template <int PIECES>
+static int sparse_rows(float *t[2], double fraction, int *flip, float *out) {
+    const uint64_t rows = kRows / PIECES;
     std::vector<uint32_t> h;
-    uint64_t s = 88172645463325252ull;  // xorshift: about 30 % of the rows, ascending
-    for (uint64_t r = 0; r < kRows; ++r) {
+    uint64_t s = 88172645463325252ull;  // xorshift
+    for (uint64_t r = 0; r < rows; ++r) {
         s ^= s << 13; s ^= s >> 7; s ^= s << 17;
-        if ((s >> 11) * (1.0 / 9007199254740992.0) < 0.3) h.push_back((uint32_t)r);
+        if ((s >> 11) * (1.0 / 9007199254740992.0) < fraction) h.push_back((uint32_t)r);
     }
     const uint64_t n = h.size();
     uint32_t *ids;
     if (hipMalloc(&ids, n * 4) != hipSuccess || hipMemcpy(ids, h.data(), n * 4, hipMemcpyHostToDevice) != hipSuccess) return 1;
+    const double row_bytes = (double)n * kRowFloats * PIECES * 4;
+    const unsigned grid = (unsigned)((n + 63) / 64) < 24576u ? (unsigned)((n + 63) / 64) : 24576u;
+    const float gr = time_us([&] { sparse_rows_kernel<false, PIECES><<<grid, 256>>>(t[*flip ^= 1], ids, n, grid * 4, out); }, 10);
+    const float sw = time_us([&] { sparse_rows_kernel<true, PIECES><<<grid, 256>>>(t[*flip ^= 1], ids, n, grid * 4, out); }, 10);
+    if (gr < 0 || sw < 0) return 1;
+    printf("%llu of %llu rows of %d bytes, ascending, %u workgroups: gather-read %6.2f TB/s   scatter-write %6.2f TB/s (row bytes alone)\n",
+           (unsigned long long)n, (unsigned long long)rows, kRowFloats * PIECES * 4, grid, row_bytes / gr / 1e6, row_bytes / sw / 1e6);
+    // the restore's mix: the same scatter while 64 * SIDE bytes per 16 rows are read from the other table (n * SIDE * 4 bytes
+    // in all, far less than the table holds)
+    constexpr int kSide = PIECES == 1 ? 8 : 32;
+    const float mix = time_us([&] {
+        *flip ^= 1;
+        sparse_rows_kernel<true, PIECES, kSide><<<grid, 256>>>(t[*flip], ids, n, grid * 4, out, t[*flip ^ 1]);
+    }, 10);
+    if (mix < 0) return 1;
+    printf("  the same scatter with %d bytes per row read from a sequential buffer meanwhile: %6.2f TB/s (rows + that buffer)\n", kSide * 4,
+           (row_bytes + (double)n * kSide * 4) / mix / 1e6);
+    (void)hipFree(ids);
+    return 0;
+}
+
+static int memory_ceilings(float *out) {
+    float *t[2];
+    for (int i = 0; i < 2; ++i)
+        if (hipMalloc(&t[i], kRows * kRowFloats * 4) != hipSuccess || hipMemset(t[i], 0, kRows * kRowFloats * 4) != hipSuccess) return 1;
     const uint64_t n16 = kRows * kRowFloats / 4;
-    const double table_bytes = (double)kRows * kRowFloats * 4, row_bytes = (double)n * kRowFloats * 4;
+    const double table_bytes = (double)kRows * kRowFloats * 4;
     int flip = 0;
     for (unsigned grid : {2048u, 8192u, 24576u}) {
         const float r = time_us([&] { stream_kernel<0><<<grid, 256>>>((const f32x4 *)t[0], (f32x4 *)t[1], n16, out); }, 5);
@@ -163,13 +206,8 @@ static int memory_ceilings(float *out) {
         printf("whole table, %5u workgroups: read %6.2f TB/s   write %6.2f TB/s   copy %6.2f TB/s (read + write)\n", grid,
                table_bytes / r / 1e6, table_bytes / w / 1e6, 2 * table_bytes / c / 1e6);
     }
-    const unsigned grid = (unsigned)((n + 63) / 64) < 24576u ? (unsigned)((n + 63) / 64) : 24576u;
-    const float gr = time_us([&] { sparse_rows_kernel<false><<<grid, 256>>>(t[flip ^= 1], ids, n, grid * 4, out); }, 10);
-    const float sw = time_us([&] { sparse_rows_kernel<true><<<grid, 256>>>(t[flip ^= 1], ids, n, grid * 4, out); }, 10);
-    if (gr < 0 || sw < 0) return 1;
-    printf("%llu of %llu rows of 256 bytes, ascending, %u workgroups: gather-read %6.2f TB/s   scatter-write %6.2f TB/s (row bytes alone)\n",
-           (unsigned long long)n, (unsigned long long)kRows, grid, row_bytes / gr / 1e6, row_bytes / sw / 1e6);
-    (void)hipFree(t[0]); (void)hipFree(t[1]); (void)hipFree(ids);
+    if (sparse_rows<1>(t, 0.30, &flip, out) || sparse_rows<2>(t, 0.25, &flip, out)) return 1;
+    (void)hipFree(t[0]); (void)hipFree(t[1]);
     return 0;
 }
 
