@@ -93,20 +93,21 @@ constexpr int kRowFloats = 64;
 
 // rows ids[k], k < n, of 64 * PIECES floats, each by 16 lanes (a lane takes 16 bytes of every 256-byte
 // piece); four rows per 16-lane group and pass, as in the library's kernels
-// With SIDE > 0 every pass of 16 rows also reads 64 * SIDE consecutive bytes of `side` (what the packed
-// codes are to the restore: SIDE = 8 for 32 bytes per row, 32 for 128).
+// With SIDE > 0 every pass of 16 rows also moves 64 * SIDE consecutive bytes of `side` the other way
+// (what the packed codes are to the restore, which reads them, and to the encode, which writes them:
+// SIDE = 8 for 32 bytes per row, 32 for 128).
 template <bool WRITE, int PIECES, int SIDE = 0>
 __global__ void __launch_bounds__(256) sparse_rows_kernel(float *__restrict__ table, const uint32_t *__restrict__ ids, uint64_t n,
-                                                          uint32_t n_waves, float *out, const float *__restrict__ side = nullptr) {
+                                                          uint32_t n_waves, float *out, float *__restrict__ side = nullptr) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
     const int lane = threadIdx.x & 63, g = lane >> 4, l = lane & 15;
     float acc = 0;
     for (uint64_t pass = (uint64_t)blockIdx.x * 4 + threadIdx.x / 64; pass * 16 < n; pass += n_waves) {
         const uint64_t k0 = pass * 16 + 4 * g;
-        if constexpr (SIDE == 8) {
-            typedef float f32x2 __attribute__((ext_vector_type(2)));
+        if constexpr (WRITE && SIDE == 8) {
             const f32x2 v = __builtin_nontemporal_load(reinterpret_cast<const f32x2 *>(side) + pass * 64 + lane);
             acc += v.x + v.y;
-        } else if constexpr (SIDE >= 16) {
+        } else if constexpr (WRITE && SIDE >= 16) {
 #pragma unroll
             for (int i = 0; i < SIDE / 16; ++i) {
                 const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(side) + (pass * (SIDE / 16) + i) * 64 + lane);
@@ -129,6 +130,13 @@ __global__ void __launch_bounds__(256) sparse_rows_kernel(float *__restrict__ ta
                     acc += v.x + v.y + v.z + v.w;
                 }
             }
+        }
+        if constexpr (!WRITE && SIDE == 8) {
+            __builtin_nontemporal_store(f32x2{acc, acc}, reinterpret_cast<f32x2 *>(side) + pass * 64 + lane);
+        } else if constexpr (!WRITE && SIDE >= 16) {
+#pragma unroll
+            for (int i = 0; i < SIDE / 16; ++i)
+                __builtin_nontemporal_store(f32x4{acc, acc, acc, acc}, reinterpret_cast<f32x4 *>(side) + (pass * (SIDE / 16) + i) * 64 + lane);
         }
     }
     if (acc == 123.456f) out[0] = acc;
@@ -187,6 +195,14 @@ static int sparse_rows(float *t[2], double fraction, int *flip, float *out) {
     if (mix < 0) return 1;
     printf("  the same scatter with %d bytes per row read from a sequential buffer meanwhile: %6.2f TB/s (rows + that buffer)\n", kSide * 4,
            (row_bytes + (double)n * kSide * 4) / mix / 1e6);
+    // the encode's mix: the gather while that many bytes per row are written to the other table
+    const float xim = time_us([&] {
+        *flip ^= 1;
+        sparse_rows_kernel<false, PIECES, kSide><<<grid, 256>>>(t[*flip], ids, n, grid * 4, out, t[*flip ^ 1]);
+    }, 10);
+    if (xim < 0) return 1;
+    printf("  the same gather with %d bytes per row written to a sequential buffer meanwhile: %6.2f TB/s (rows + that buffer)\n", kSide * 4,
+           (row_bytes + (double)n * kSide * 4) / xim / 1e6);
     (void)hipFree(ids);
     return 0;
 }
