@@ -96,7 +96,9 @@ constexpr int kRowFloats = 64;
 // With SIDE > 0 every pass of 16 rows also moves 64 * SIDE consecutive bytes of `side` the other way
 // (what the packed codes are to the restore, which reads them, and to the encode, which writes them:
 // SIDE = 8 for 32 bytes per row, 32 for 128).
-template <bool WRITE, int PIECES, int SIDE = 0>
+// THROUGH: the scatter's stores carry the write-through bits the restore kernel uses for rows that one
+// instruction writes whole (system-scope, streaming), instead of the plain non-temporal hint.
+template <bool WRITE, int PIECES, int SIDE = 0, bool THROUGH = false>
 __global__ void __launch_bounds__(256) sparse_rows_kernel(float *__restrict__ table, const uint32_t *__restrict__ ids, uint64_t n,
                                                           uint32_t n_waves, float *out, float *__restrict__ side = nullptr) {
     typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -123,7 +125,10 @@ __global__ void __launch_bounds__(256) sparse_rows_kernel(float *__restrict__ ta
             f32x4 *p = reinterpret_cast<f32x4 *>(table + (uint64_t)rid[u] * (kRowFloats * PIECES) + 4 * l);
 #pragma unroll
             for (int c = 0; c < PIECES; ++c) {
-                if (WRITE) {
+                if (WRITE && THROUGH) {
+                    const f32x4 v = {1.f, 2.f, (float)l, (float)u};
+                    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" ::"v"(p + 16 * c), "v"(v) : "memory");
+                } else if (WRITE) {
                     __builtin_nontemporal_store(f32x4{1.f, 2.f, (float)l, (float)u}, p + 16 * c);
                 } else {
                     const f32x4 v = __builtin_nontemporal_load(p + 16 * c);
@@ -195,6 +200,14 @@ static int sparse_rows(float *t[2], double fraction, int *flip, float *out) {
     if (mix < 0) return 1;
     printf("  the same scatter with %d bytes per row read from a sequential buffer meanwhile: %6.2f TB/s (rows + that buffer)\n", kSide * 4,
            (row_bytes + (double)n * kSide * 4) / mix / 1e6);
+    const float swt = time_us([&] { sparse_rows_kernel<true, PIECES, 0, true><<<grid, 256>>>(t[*flip ^= 1], ids, n, grid * 4, out); }, 10);
+    const float mixt = time_us([&] {
+        *flip ^= 1;
+        sparse_rows_kernel<true, PIECES, kSide, true><<<grid, 256>>>(t[*flip], ids, n, grid * 4, out, t[*flip ^ 1]);
+    }, 10);
+    if (swt < 0 || mixt < 0) return 1;
+    printf("  with write-through stores: scatter alone %6.2f TB/s, with the %d bytes per row read meanwhile %6.2f TB/s\n", row_bytes / swt / 1e6,
+           kSide * 4, (row_bytes + (double)n * kSide * 4) / mixt / 1e6);
     // the encode's mix: the gather while that many bytes per row are written to the other table
     const float xim = time_us([&] {
         *flip ^= 1;
