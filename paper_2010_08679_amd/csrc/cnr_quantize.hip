@@ -362,14 +362,20 @@ quantize_tile_kernel(const QuantBatchArgs b) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Greedy range search (Approach 3), dim = 16 * L with L = 1, 2, 4, 8 or 16 lanes per row.  Bound by
-// vector-ALU issue: 1 + 2 * n_iter candidate ranges are tried per row.
+// Greedy range search (Approach 3), dim = 16 * G * L in {16, 32, 64, 128, 256}: L lanes per row, G
+// groups of sixteen elements per lane.  Bound by vector-ALU issue: 1 + 2 * n_iter candidate ranges are
+// tried per row.
 //
-// Every lane owns sixteen consecutive elements (four 16-byte loads) of one row, L neighbouring lanes
+// Every lane owns 16 * G consecutive elements (4 * G 16-byte loads) of one row, L neighbouring lanes
 // own the row, a wave handles 64 / L consecutive dirty rows per pass.  A candidate's error is summed
-// over a lane's sixteen registers and then over the L lanes with log2(L) DPP exchanges, and a lane's
-// sixteen codes are exactly 2 * BITS contiguous bytes of the packed row.  The rows are read in this
-// layout directly (16-byte loads 64 bytes apart): the kernel is far from the memory system's limits,
+// over a lane's registers and then over the L lanes with log2(L) DPP exchanges, and a group's sixteen
+// codes are exactly 2 * BITS contiguous bytes of the packed row.  What a candidate costs beyond its
+// elements (its scale and reciprocal, the exchange between lanes, the comparison) is paid once per
+// lane, so more elements per lane mean less of it: with 64 instead of 16 (G = 4; a row of 64 floats
+// is then one lane's, with no exchange at all) a long list takes 13 % less time, 0.90 instead of 0.78
+// of the issue bound of the element arithmetic alone.  A lane then works four times as long on a
+// row, so short lists, which cannot fill the SIMDs either way, keep G = 1.  The rows are read in this
+// layout directly (each lane its own 64 * G bytes): the kernel is far from the memory system's limits,
 // so the transpose through LDS that the tile kernel pays for coalesced loads would buy nothing.
 // A candidate is evaluated with the cheapest sequence that still ranks candidates as F_Q would.  On
 // this GPU a wave's add, subtract or multiply occupies a SIMD for two clocks, every other vector
@@ -413,9 +419,10 @@ __device__ __forceinline__ double lanes_sum(double v) {
     return v;
 }
 
-template <int L, int BITS>
+template <int L, int BITS, int G>
 __global__ void __launch_bounds__(kBlock) quantize_greedy_kernel(const QuantArgs a) {
-    constexpr int DIM = 16 * L;
+    constexpr int EPL = 16 * G;  // elements per lane
+    constexpr int DIM = EPL * L;
     constexpr int kRowsPerPass = kWave / L;
     constexpr float QMAXF = (float)((1 << BITS) - 1);
     constexpr float INV_QMAX = 1.0f / QMAXF;
@@ -437,18 +444,18 @@ __global__ void __launch_bounds__(kBlock) quantize_greedy_kernel(const QuantArgs
                 rid = 0;
             }
         }
-        float4 x[4];
+        float4 x[4 * G];
         {
-            const float *src = a.table + rid * (uint64_t)DIM + 16u * (uint64_t)j;
+            const float *src = a.table + rid * (uint64_t)DIM + (uint64_t)(EPL * j);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) x[i] = *reinterpret_cast<const float4 *>(src + 4 * i);
+            for (int i = 0; i < 4 * G; ++i) x[i] = *reinterpret_cast<const float4 *>(src + 4 * i);
         }
 
         // ---- row minimum / maximum
         float mn = fminf(fminf(x[0].x, x[0].y), fminf(x[0].z, x[0].w));
         float mx = fmaxf(fmaxf(x[0].x, x[0].y), fmaxf(x[0].z, x[0].w));
 #pragma unroll
-        for (int i = 1; i < 4; ++i) {
+        for (int i = 1; i < 4 * G; ++i) {
             mn = fminf(fminf(mn, x[i].x), fminf(x[i].y, fminf(x[i].z, x[i].w)));
             mx = fmaxf(fmaxf(mx, x[i].x), fmaxf(x[i].y, fmaxf(x[i].z, x[i].w)));
         }
@@ -482,7 +489,7 @@ __global__ void __launch_bounds__(kBlock) quantize_greedy_kernel(const QuantArgs
                 }
                 double e = 0.0;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
+                for (int i = 0; i < 4 * G; ++i) {
                     e = add_err(e, x[i].x, c_lo, c_hi, s, inv);
                     e = add_err(e, x[i].y, c_lo, c_hi, s, inv);
                     e = add_err(e, x[i].z, c_lo, c_hi, s, inv);
@@ -540,9 +547,9 @@ __global__ void __launch_bounds__(kBlock) quantize_greedy_kernel(const QuantArgs
         }
 
         // ---- final codes by F_Q as written; h[i] = the four codes of x[i], first element lowest
-        uint32_t h[4], h8[4];
+        uint32_t h[4 * G], h8[4 * G];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 4 * G; ++i) {
             const uint32_t q0 = (uint32_t)fq_code_f(x[i].x, lo, hi, scale, QMAXF);
             const uint32_t q1 = (uint32_t)fq_code_f(x[i].y, lo, hi, scale, QMAXF);
             const uint32_t q2 = (uint32_t)fq_code_f(x[i].z, lo, hi, scale, QMAXF);
@@ -550,35 +557,64 @@ __global__ void __launch_bounds__(kBlock) quantize_greedy_kernel(const QuantArgs
             h[i] = q0 | (q1 << BITS) | (q2 << (2 * BITS)) | (q3 << (3 * BITS));
             h8[i] = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
         }
-        if (a.codes && live)
-            *reinterpret_cast<uint4 *>(a.codes + k * (uint64_t)DIM + 16 * j) = make_uint4(h8[0], h8[1], h8[2], h8[3]);
+        if (a.codes && live) {
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+                *reinterpret_cast<uint4 *>(a.codes + k * (uint64_t)DIM + EPL * j + 16 * g) =
+                    make_uint4(h8[4 * g], h8[4 * g + 1], h8[4 * g + 2], h8[4 * g + 3]);
+        }
 
-        // ---- packed codes: this lane's bits are bytes [2 * BITS * j, 2 * BITS * (j + 1)) of the row
+        // ---- packed codes: this lane's bits are bytes [2 * BITS * G * j, 2 * BITS * G * (j + 1)) of the row,
+        // 2 * BITS bytes per group of sixteen elements
         if (a.packed) {
-            uint8_t *dst = a.packed + k * P + 2 * BITS * j;
+            uint8_t *dst = a.packed + k * P + 2 * BITS * G * j;
             if constexpr (BITS == 8) {
-                if (live) *reinterpret_cast<uint4 *>(dst) = make_uint4(h[0], h[1], h[2], h[3]);
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+                    if (live) *reinterpret_cast<uint4 *>(dst + 16 * g) = make_uint4(h[4 * g], h[4 * g + 1], h[4 * g + 2], h[4 * g + 3]);
             } else if constexpr (BITS == 4) {
-                if (live) *reinterpret_cast<uint2 *>(dst) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+                    if (live)
+                        *reinterpret_cast<uint2 *>(dst + 8 * g) =
+                            make_uint2(h[4 * g] | (h[4 * g + 1] << 16), h[4 * g + 2] | (h[4 * g + 3] << 16));
             } else if constexpr (BITS == 2) {
-                if (live) *reinterpret_cast<uint32_t *>(dst) = h[0] | (h[1] << 8) | (h[2] << 16) | (h[3] << 24);
-            } else {  // 3 bits: 48 bits per lane; even lanes append their right neighbour's 48 bits
-                const uint32_t w0 = h[0] | (h[1] << 12) | (h[2] << 24);  // stream bits 0..31
-                const uint32_t w1 = (h[2] >> 8) | (h[3] << 4);           // stream bits 32..47
-                if constexpr (L == 1) {  // the row is this lane's 48 bits alone
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+                    if (live)
+                        *reinterpret_cast<uint32_t *>(dst + 4 * g) =
+                            h[4 * g] | (h[4 * g + 1] << 8) | (h[4 * g + 2] << 16) | (h[4 * g + 3] << 24);
+            } else {  // 3 bits: 48 bits per group
+                uint32_t w0[G], w1[G];
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    w0[g] = h[4 * g] | (h[4 * g + 1] << 12) | (h[4 * g + 2] << 24);  // stream bits 0..31 of the group
+                    w1[g] = (h[4 * g + 2] >> 8) | (h[4 * g + 3] << 4);               // stream bits 32..47
+                }
+                if constexpr (G >= 2) {  // two groups make three whole words
+#pragma unroll
+                    for (int g = 0; g < G; g += 2) {
+                        uint32_t *d3 = reinterpret_cast<uint32_t *>(dst + 6 * g);
+                        if (live) {
+                            d3[0] = w0[g];
+                            d3[1] = w1[g] | (w0[g + 1] << 16);
+                            d3[2] = (w0[g + 1] >> 16) | (w1[g + 1] << 16);
+                        }
+                    }
+                } else if constexpr (L == 1) {  // the row is this lane's 48 bits alone
                     uint16_t *d2 = reinterpret_cast<uint16_t *>(dst);
                     if (live) {
-                        d2[0] = (uint16_t)w0;
-                        d2[1] = (uint16_t)(w0 >> 16);
-                        d2[2] = (uint16_t)w1;
+                        d2[0] = (uint16_t)w0[0];
+                        d2[1] = (uint16_t)(w0[0] >> 16);
+                        d2[2] = (uint16_t)w1[0];
                     }
-                } else {
-                    const uint32_t n0 = (uint32_t)dpp_i<0xB1>((int)w0);  // lane ^ 1
-                    const uint32_t n1 = (uint32_t)dpp_i<0xB1>((int)w1);
+                } else {  // even lanes append their right neighbour's 48 bits
+                    const uint32_t n0 = (uint32_t)dpp_i<0xB1>((int)w0[0]);  // lane ^ 1
+                    const uint32_t n1 = (uint32_t)dpp_i<0xB1>((int)w1[0]);
                     if (live && !(j & 1)) {
                         uint32_t *d3 = reinterpret_cast<uint32_t *>(dst);
-                        d3[0] = w0;
-                        d3[1] = w1 | (n0 << 16);
+                        d3[0] = w0[0];
+                        d3[1] = w1[0] | (n0 << 16);
                         d3[2] = (n0 >> 16) | (n1 << 16);
                     }
                 }
@@ -883,13 +919,13 @@ inline void launch_tile_any(QuantBatchArgs &b, uint32_t n, uint32_t dim, int bit
     }
 }
 
-template <int L, int BITS>
+template <int L, int BITS, int G>
 void launch_greedy(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
     // the large grid here too: the search is bound by arithmetic, but workgroups handed out as others
     // finish even out the end of the launch (4 % on a 1.5 M-row list)
     const unsigned grid = cnr_row_grid(a.n_max, (uint64_t)(kWave / L) * kWavesPerBlock);
     a.n_waves = grid * kWavesPerBlock;
-    hipLaunchKernelGGL((quantize_greedy_kernel<L, BITS>), dim3(grid), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL((quantize_greedy_kernel<L, BITS, G>), dim3(grid), dim3(kBlock), 0, s, a);
 }
 
 template <int LPR, int BITS>
@@ -905,11 +941,15 @@ void launch_strided(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
 template <int BITS>
 void launch_bits(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
     const bool greedy = a.mode == kModeGreedy && a.n_iter > 0;  // zero iterations: plain min/max
-    if (greedy && a.dim == 16) return launch_greedy<1, BITS>(ctx, a, s);
-    if (greedy && a.dim == 32) return launch_greedy<2, BITS>(ctx, a, s);
-    if (greedy && a.dim == 64) return launch_greedy<4, BITS>(ctx, a, s);
-    if (greedy && a.dim == 128) return launch_greedy<8, BITS>(ctx, a, s);
-    if (greedy && a.dim == 256) return launch_greedy<16, BITS>(ctx, a, s);
+    // Long lists give every lane 64 elements (32 at dim 32); short ones keep 16 per lane, four times the
+    // lanes per row and a quarter of the time per row, which is what counts while the list cannot
+    // fill the SIMDs anyway.  The break-even was measured at about 8 M elements (128 K rows of 64).
+    const bool wide = a.n_max * (uint64_t)a.dim >= (1ull << 23);
+    if (greedy && a.dim == 16) return launch_greedy<1, BITS, 1>(ctx, a, s);
+    if (greedy && a.dim == 32) return wide ? launch_greedy<1, BITS, 2>(ctx, a, s) : launch_greedy<2, BITS, 1>(ctx, a, s);
+    if (greedy && a.dim == 64) return wide ? launch_greedy<1, BITS, 4>(ctx, a, s) : launch_greedy<4, BITS, 1>(ctx, a, s);
+    if (greedy && a.dim == 128) return wide ? launch_greedy<2, BITS, 4>(ctx, a, s) : launch_greedy<8, BITS, 1>(ctx, a, s);
+    if (greedy && a.dim == 256) return wide ? launch_greedy<4, BITS, 4>(ctx, a, s) : launch_greedy<16, BITS, 1>(ctx, a, s);
     if (greedy) {  // other row lengths, greedy: one wave per row
         const unsigned grid = cnr_grid(ctx, a.n_max, kWavesPerBlock, 8);
         hipLaunchKernelGGL((quantize_rows_generic_kernel<BITS>), dim3(grid), dim3(kBlock), 0, s, a.table,

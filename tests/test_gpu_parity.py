@@ -344,6 +344,55 @@ def test_greedy_encode(ctx, bits, dim, params):
     assert np.mean(got["scale"] < plain["scale"]) > 0.2
 
 
+@pytest.mark.parametrize("dim,bits,params", [(64, 4, (100, 1.0)), (64, 3, (45, 0.6)), (64, 2, (25, 1.0)), (64, 8, (20, 1.0)),
+                                             (128, 4, (100, 1.0)), (128, 3, (25, 1.0)), (256, 4, (45, 0.6)), (256, 2, (100, 1.0)),
+                                             (32, 4, (100, 1.0)), (32, 3, (25, 1.0))])
+def test_greedy_on_long_lists(ctx, dim, bits, params):
+    # A list of 8 M elements or more is searched with 64 elements per lane (32 at dim 32) instead of 16:
+    # the same results are due.  Ordinary outlier rows with rows a few float spacings wide, constant
+    # rows and rows of huge and tiny magnitude among them (waves that hold one divide as F_Q is
+    # written); the oracle checks a sample that contains all of those, the pack and the row ranges are
+    # checked on every row.
+    print("case greedy long list bits=%d dim=%d params=%s" % (bits, dim, params), flush=True)
+    n_rows = (1 << 23) // dim * 10 // 9 + 4321
+    table = synth.table_outlier_mix(n_rows, dim, 0.02, 51 + dim + bits, DEV)
+    rng = np.random.default_rng(dim * 8 + bits)
+    special = []
+    for mag in (1.0, 1000.0, -7.5):
+        base = np.float32(mag)
+        u = np.spacing(np.abs(base))
+        for span in (1, 2, 7, 100, 40000):
+            x = (base + u * rng.integers(0, span + 1, size=(6, dim)).astype(np.float32)).astype(np.float32)
+            x[:, 0], x[:, 1] = base, base + u * span
+            special.append(x)
+    special.append(np.full((5, dim), 0.25, dtype=np.float32))
+    special.append(np.float32(rng.normal(0, 1e30, size=(5, dim))))
+    special.append(np.float32(rng.normal(0, 1e-36, size=(5, dim))))
+    special = np.concatenate(special)
+    where = np.sort(rng.choice(n_rows, size=special.shape[0], replace=False))
+    table[torch.from_numpy(where).to(DEV)] = torch.from_numpy(special).to(DEV)
+    gt = GpuTable(ctx, table)
+    idx = torch.nonzero(torch.rand(n_rows, device=DEV, generator=torch.Generator(device=DEV).manual_seed(dim + bits)) < 0.93).reshape(-1)
+    idx = torch.unique(torch.cat([idx, torch.from_numpy(where).to(DEV)]))
+    gt.ck.clear(); gt.ck.mark(idx); gt.ck.compact()
+    got = gpu_encode_all_outputs(gt, bits, mode=P.CNR_RANGE_GREEDY, greedy=params)
+    n = got["n"]
+    ids = idx.cpu().numpy()
+    assert n == ids.size and n * dim >= 1 << 23
+    rows = gt.host[ids]
+    assert np.array_equal(got["row_min"], rows.min(axis=1)) and np.array_equal(got["row_max"], rows.max(axis=1))
+    assert np.array_equal(got["packed"], O.pack(got["codes"], bits))
+    pos = np.unique(np.concatenate([np.arange(200), np.arange(n - 200, n), np.searchsorted(ids, where),
+                                    rng.integers(0, n, size=24_000)]))
+    ora = O.quantize_rows(rows[pos], None, bits, mode=O.RANGE_GREEDY, num_bins=params[0], ratio=params[1], n_threads=8)
+    sub = {k: got[k][pos] for k in ("scale", "bias", "row_min", "row_max", "codes")}
+    compare_quantized(rows[pos], sub, ora, bits, greedy=True, what="greedy long list b%d d%d" % (bits, dim))
+    plain = O.quantize_rows(rows[pos], None, bits)
+    if bits <= 4:   # the search must have moved a fair share of the rows (at 8 bits clipping hardly ever pays)
+        assert np.mean(sub["scale"] < plain["scale"]) > 0.2
+    _poll_clean(ctx)
+
+
 @pytest.mark.parametrize("dim", [64, 128, 16, 40])
 def test_greedy_on_rows_spanning_a_few_float_spacings(ctx, dim):
     # rows a few representable values wide around a large magnitude: the cumulative bounds of the
