@@ -346,7 +346,8 @@ def test_greedy_encode(ctx, bits, dim, params):
 
 @pytest.mark.parametrize("dim,bits,params", [(64, 4, (100, 1.0)), (64, 3, (45, 0.6)), (64, 2, (25, 1.0)), (64, 8, (20, 1.0)),
                                              (128, 4, (100, 1.0)), (128, 3, (25, 1.0)), (256, 4, (45, 0.6)), (256, 2, (100, 1.0)),
-                                             (32, 4, (100, 1.0)), (32, 3, (25, 1.0))])
+                                             (32, 4, (100, 1.0)), (32, 3, (25, 1.0)), (32, 2, (45, 0.6)), (32, 8, (20, 1.0)),
+                                             (128, 2, (45, 0.6)), (128, 8, (20, 1.0)), (256, 3, (25, 1.0)), (256, 8, (20, 0.5))])
 def test_greedy_on_long_lists(ctx, dim, bits, params):
     # A list of 8 M elements or more is searched with 64 elements per lane (32 at dim 32) instead of 16:
     # the same results are due.  Ordinary outlier rows with rows a few float spacings wide, constant
