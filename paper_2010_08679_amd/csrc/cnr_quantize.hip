@@ -420,7 +420,7 @@ __device__ __forceinline__ double lanes_sum(double v) {
 }
 
 template <int L, int BITS, int G>
-__global__ void __launch_bounds__(kBlock) quantize_greedy_kernel(const QuantArgs a) {
+__global__ void __launch_bounds__(kBlock) quantize_greedy_kernel(const QuantArgs a, uint64_t n_from, uint64_t n_below) {
     constexpr int EPL = 16 * G;  // elements per lane
     constexpr int DIM = EPL * L;
     constexpr int kRowsPerPass = kWave / L;
@@ -428,6 +428,7 @@ __global__ void __launch_bounds__(kBlock) quantize_greedy_kernel(const QuantArgs
     constexpr float INV_QMAX = 1.0f / QMAXF;
     constexpr uint64_t P = (uint64_t)DIM * BITS / 8;  // packed bytes per row
     const uint64_t n = row_count(a);
+    if (n < n_from || n >= n_below) return;  // this list length is the other launch's (uniform over the grid)
     const int lane = tid_x() & (kWave - 1);
     const int j = lane % L;  // lane within the row
     const uint32_t n_waves = a.n_waves;
@@ -919,13 +920,28 @@ inline void launch_tile_any(QuantBatchArgs &b, uint32_t n, uint32_t dim, int bit
     }
 }
 
+// Runs for lists of n_from <= n < n_below rows (n is the count on the device where there is one).
 template <int L, int BITS, int G>
-void launch_greedy(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
+void launch_greedy(cnr_ctx *ctx, QuantArgs &a, hipStream_t s, uint64_t n_from, uint64_t n_below) {
     // the large grid here too: the search is bound by arithmetic, but workgroups handed out as others
     // finish even out the end of the launch (4 % on a 1.5 M-row list)
-    const unsigned grid = cnr_row_grid(a.n_max, (uint64_t)(kWave / L) * kWavesPerBlock);
+    const uint64_t most = a.n_max < n_below ? a.n_max : n_below;
+    const unsigned grid = cnr_row_grid(most, (uint64_t)(kWave / L) * kWavesPerBlock);
     a.n_waves = grid * kWavesPerBlock;
-    hipLaunchKernelGGL((quantize_greedy_kernel<L, BITS, G>), dim3(grid), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL((quantize_greedy_kernel<L, BITS, G>), dim3(grid), dim3(kBlock), 0, s, a, n_from, n_below);
+}
+// Long lists give every lane 64 elements (32 at dim 32); short ones keep 16 per lane, four times the
+// lanes per row and a quarter of the time per row, which is what counts while the list cannot fill
+// the SIMDs anyway.  The break-even was measured at about 8 M elements (128 K rows of 64).  Where the
+// length is a count on the device and the capacity allows a long list, both kernels are launched
+// and the one whose range the count is not in returns at once.
+template <int L_NARROW, int L_WIDE, int G_WIDE, int BITS>
+void launch_greedy_by_length(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
+    const uint64_t wide_rows = (1ull << 23) / a.dim;
+    const bool may_be_wide = a.n_max >= wide_rows;
+    const bool may_be_narrow = !may_be_wide || a.n_dev != nullptr;
+    if (may_be_narrow) launch_greedy<L_NARROW, BITS, 1>(ctx, a, s, 0, may_be_wide ? wide_rows : ~0ull);
+    if (may_be_wide) launch_greedy<L_WIDE, BITS, G_WIDE>(ctx, a, s, may_be_narrow ? wide_rows : 0, ~0ull);
 }
 
 template <int LPR, int BITS>
@@ -941,15 +957,11 @@ void launch_strided(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
 template <int BITS>
 void launch_bits(cnr_ctx *ctx, QuantArgs &a, hipStream_t s) {
     const bool greedy = a.mode == kModeGreedy && a.n_iter > 0;  // zero iterations: plain min/max
-    // Long lists give every lane 64 elements (32 at dim 32); short ones keep 16 per lane, four times the
-    // lanes per row and a quarter of the time per row, which is what counts while the list cannot
-    // fill the SIMDs anyway.  The break-even was measured at about 8 M elements (128 K rows of 64).
-    const bool wide = a.n_max * (uint64_t)a.dim >= (1ull << 23);
-    if (greedy && a.dim == 16) return launch_greedy<1, BITS, 1>(ctx, a, s);
-    if (greedy && a.dim == 32) return wide ? launch_greedy<1, BITS, 2>(ctx, a, s) : launch_greedy<2, BITS, 1>(ctx, a, s);
-    if (greedy && a.dim == 64) return wide ? launch_greedy<1, BITS, 4>(ctx, a, s) : launch_greedy<4, BITS, 1>(ctx, a, s);
-    if (greedy && a.dim == 128) return wide ? launch_greedy<2, BITS, 4>(ctx, a, s) : launch_greedy<8, BITS, 1>(ctx, a, s);
-    if (greedy && a.dim == 256) return wide ? launch_greedy<4, BITS, 4>(ctx, a, s) : launch_greedy<16, BITS, 1>(ctx, a, s);
+    if (greedy && a.dim == 16) return launch_greedy<1, BITS, 1>(ctx, a, s, 0, ~0ull);
+    if (greedy && a.dim == 32) return launch_greedy_by_length<2, 1, 2, BITS>(ctx, a, s);
+    if (greedy && a.dim == 64) return launch_greedy_by_length<4, 1, 4, BITS>(ctx, a, s);
+    if (greedy && a.dim == 128) return launch_greedy_by_length<8, 2, 4, BITS>(ctx, a, s);
+    if (greedy && a.dim == 256) return launch_greedy_by_length<16, 4, 4, BITS>(ctx, a, s);
     if (greedy) {  // other row lengths, greedy: one wave per row
         const unsigned grid = cnr_grid(ctx, a.n_max, kWavesPerBlock, 8);
         hipLaunchKernelGGL((quantize_rows_generic_kernel<BITS>), dim3(grid), dim3(kBlock), 0, s, a.table,

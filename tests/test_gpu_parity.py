@@ -391,6 +391,16 @@ def test_greedy_on_long_lists(ctx, dim, bits, params):
     plain = O.quantize_rows(rows[pos], None, bits)
     if bits <= 4:   # the search must have moved a fair share of the rows (at 8 bits clipping hardly ever pays)
         assert np.mean(sub["scale"] < plain["scale"]) > 0.2
+    # the same buffers (their capacity allows a long list) with a short list, its length known on the
+    # device alone: the kernel for short lists must be the one that runs, and nothing else may write
+    few = torch.from_numpy(np.sort(rng.choice(n_rows, size=3001, replace=False))).to(DEV)
+    gt.ck.clear(); gt.ck.mark(few); gt.ck.compact()
+    got = gpu_encode_all_outputs(gt, bits, mode=P.CNR_RANGE_GREEDY, greedy=params)
+    assert got["n"] == 3001
+    rows = gt.host[few.cpu().numpy()]
+    ora = O.quantize_rows(rows, None, bits, mode=O.RANGE_GREEDY, num_bins=params[0], ratio=params[1], n_threads=8)
+    compare_quantized(rows, got, ora, bits, greedy=True, what="greedy short list in long buffers b%d d%d" % (bits, dim))
+    assert np.array_equal(got["packed"], O.pack(got["codes"], bits))
     _poll_clean(ctx)
 
 
