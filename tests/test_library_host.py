@@ -31,6 +31,32 @@ def test_library_exports_every_declared_symbol():
     assert sorted(binding.EXPORTS) == declared
 
 
+def test_binding_constants_equal_the_header_enumerators():
+    # every enumerator and numeric macro of the header that the binding names has the header's value
+    text = open(os.path.join(ROOT, "include", "cnr.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    header = {}
+    for body in re.findall(r"enum[^{;]*\{(.*?)\}", text, flags=re.S):
+        nxt = 0
+        for item in body.split(","):
+            m = re.match(r"\s*(CNR_[A-Z0-9_]+)\s*(?:=\s*(-?\d+))?\s*$", item)
+            if not m:
+                continue
+            nxt = int(m.group(2)) if m.group(2) is not None else nxt
+            header[m.group(1)] = nxt
+            nxt += 1
+    for name, value in re.findall(r"#define\s+(CNR_[A-Z0-9_]+)\s+(\d+)u?\s*$", text, flags=re.M):
+        header[name] = int(value)
+    assert header["CNR_OK"] == 0 and header["CNR_HOST_DIRECT"] == 2 and header["CNR_E_HOST_MEMORY"] == 10
+    named = [n for n in dir(binding) if n.startswith("CNR_") and isinstance(getattr(binding, n), int)]
+    assert len(named) >= 20
+    for n in named:
+        if n in header:
+            assert getattr(binding, n) == header[n], n
+    missing = [n for n in header if n.startswith(("CNR_E_", "CNR_HOST_", "CNR_RANGE_", "CNR_IDX_")) and n not in named]
+    assert not missing, missing
+
+
 def test_size_helpers_match_oracle():
     for n_rows in (0, 1, 31, 32, 33, 100_000, 5_000_000, 40_000_000):
         assert P.cnr_bitmap_words(n_rows) == O.bitmap_words(n_rows)
