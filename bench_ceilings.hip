@@ -11,6 +11,8 @@
 //      (read only) and scattered (written only) with the kernels' lane mapping (16 lanes per row, 16
 //      bytes per lane), and rows of 512 bytes, 25 % of 10 M, next to a sequential read, write and
 //      copy of the same table.
+//   4. what one compute unit streams from the L2 of its XCD (the bound of the bulk mark through bitmap
+//      slices, Section 5.1.1).
 //   3. what the host link sustains for 64 MiB of pinned host memory (the size of one table's
 //      incremental checkpoint, Sections 4.4 and 5.1): read and written by a kernel directly, and
 //      moved by the runtime's asynchronous copies.
@@ -271,6 +273,43 @@ static int host_link_ceilings(float *out) {
     return 0;
 }
 
+// ---- what one compute unit streams ----------------------------------------------------------------
+// The bulk mark through bitmap slices (Section 5.1.1) has every workgroup (1,024 threads, one per
+// compute unit) read one eighth of a table's index stream, the same eighth as the other workgroups
+// of its team, so that the bytes come from the L2 of the workgroup's XCD.  This is that read alone:
+// 256 workgroups, workgroup x reads eighth x & 7 of a 24 MB buffer with 16-byte loads, UNROLL loads
+// per lane in flight.
+template <int UNROLL>
+__global__ void __launch_bounds__(1024) shared_stream_kernel(const f32x4 *__restrict__ a, uint64_t n16, float *out) {
+    const uint64_t per_part = n16 / 8;
+    const f32x4 *p = a + (blockIdx.x & 7) * per_part;
+    float acc = 0;
+    for (uint64_t i = threadIdx.x; i < per_part; i += 1024 * UNROLL) {
+        f32x4 v[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            if (i + 1024 * u < per_part) v[u] = p[i + 1024 * u];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            if (i + 1024 * u < per_part) acc += v[u].x + v[u].w;
+    }
+    if (acc == 123.456f) out[0] = acc;
+}
+static int compute_unit_stream(float *out) {
+    const uint64_t bytes = 24ull << 20, n16 = bytes / 16;
+    float *buf = nullptr;
+    if (hipMalloc(&buf, bytes) != hipSuccess || hipMemset(buf, 0, bytes) != hipSuccess) return 1;
+    const float t4 = time_us([&] { shared_stream_kernel<4><<<256, 1024>>>((const f32x4 *)buf, n16, out); }, 10);
+    const float t16 = time_us([&] { shared_stream_kernel<16><<<256, 1024>>>((const f32x4 *)buf, n16, out); }, 10);
+    if (t4 < 0 || t16 < 0) return 1;
+    const double per_wg = (double)bytes / 8;
+    printf("256 workgroups of 1024 threads, each streaming an eighth (3 MB) of a 24 MB buffer shared by 32 of them: %5.1f GB/s per compute unit with 4 loads "
+           "per lane in flight, %5.1f with 16 (%4.1f and %4.1f TB/s over the chip)\n",
+           per_wg / t4 / 1e3, per_wg / t16 / 1e3, 256 * per_wg / t4 / 1e6, 256 * per_wg / t16 / 1e6);
+    (void)hipFree(buf);
+    return 0;
+}
+
 int main() {
     float *out;
     if (hipMalloc(&out, 4) != hipSuccess) return 1;
@@ -287,6 +326,7 @@ int main() {
     rc |= run<GREEDY_MIX>("greedy element (9 instructions)", 72, out);
     rc |= memory_ceilings(out);
     rc |= host_link_ceilings(out);
+    rc |= compute_unit_stream(out);
     if (hipDeviceSynchronize() != hipSuccess) rc = 1;
     (void)hipFree(out);
     return rc;

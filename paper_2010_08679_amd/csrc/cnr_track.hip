@@ -515,7 +515,7 @@ cnr_status cnr_mark_touched_batch(cnr_ctx *ctx, const cnr_table_job *jobs, uint3
         // Three routes.  Short streams: atomic ORs on the bitmap (about 16 G atomics/s; the other two
         // pay a pass over n_rows bytes).  Long streams: bitmap slices in LDS, or one flag byte per row
         // and a fold.  The slices cost every workgroup of a table its part of the stream (an eighth,
-        // at the 60 GB/s one compute unit reads), whatever the stream holds, and all tables of a call
+        // at the 60 GB/s a workgroup of that kernel gets through it), whatever the stream holds, and all tables of a call
         // run side by side as long as their 8 x slices workgroups fit the chip; the flag bytes cost
         // one scattered store per look-up that gets past the table of lately flagged rows (about 17 ps
         // of the whole chip's time each, a third of the look-ups on the skewed streams that embedding
