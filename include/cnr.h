@@ -123,7 +123,10 @@ cnr_status cnr_destroy(cnr_ctx *ctx);
 size_t cnr_bitmap_words(uint64_t n_rows);               /* ceil(n_rows / 32) */
 size_t cnr_packed_row_bytes(uint32_t dim, int bits);    /* dim*bits/8; 0 if not a whole number */
 size_t cnr_scratch_bytes(uint64_t n_rows);              /* scratch cnr_compact_dirty needs */
-size_t cnr_mark_scratch_bytes(uint64_t n_rows);         /* optional scratch of cnr_mark_touched */
+size_t cnr_mark_scratch_bytes(uint64_t n_rows);         /* optional scratch of cnr_mark_touched: one byte per
+                                                           row, at least 5 MiB for a table of 1.3 M rows or
+                                                           more, four bytes per row below that; never
+                                                           decreases as n_rows grows */
 uint32_t cnr_greedy_iterations(uint32_t num_bins, float ratio); /* n_iter as defined above */
 
 /* ---- tracking (Section 5.1.1) ----------------------------------------------------------- */

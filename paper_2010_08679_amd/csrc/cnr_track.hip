@@ -21,7 +21,8 @@ struct TrackJob {
     uint64_t n_rows;
     const void *idx;      // mark: look-up indices
     uint64_t n_idx;
-    uint8_t *flags;       // mark, bulk route: one byte per row, zero on entry and on exit
+    uint8_t *flags;       // mark, bulk route: the scratch (flag bytes or slabs), zero on entry and on exit
+    uint32_t parts;       // mark, LDS slices: workgroups that share this table's stream = slabs to fold
     uint32_t *row_ids;    // compact
     uint64_t capacity;
     uint64_t *n_dirty;
@@ -178,18 +179,37 @@ __global__ void __launch_bounds__(kSeenThreads) mark_flags_kernel(const TrackBat
 // mark, second bulk variant, for tables of up to a few tens of millions of rows: bitmap slices in LDS.
 //
 // A workgroup owns kSliceRows consecutive rows of one table as a bitmap in LDS (all 160 KB of a
-// compute unit) and one eighth of the table's index stream: it reads its share of the stream, sets
-// the bits of the look-ups that fall into its rows with LDS atomics, and stores the slice to slab
-// s (= its eighth of the stream) of the scratch buffer, eight partial bitmaps per table that
-// fold_slabs_kernel ORs into the bitmap and zeroes again.  Nothing is scattered to memory; the
-// price is that the W = ceil(n_rows / kSliceRows) workgroups of a team read the same eighth of the
-// stream.  Workgroups are dealt to the eight XCDs in turn along x, so x & 7 names both the eighth
+// compute unit) and one part of the table's index stream (an eighth; down to a thirty-second for
+// small tables, see slice_parts_max): it reads its share of the stream, sets the bits of the
+// look-ups that fall into its rows with LDS atomics, and stores the slice to slab s (= its part of
+// the stream) of the scratch buffer, partial bitmaps that fold_slabs_kernel ORs into the bitmap and
+// zeroes again.  Nothing is scattered to memory; the price is that the W = ceil(n_rows / kSliceRows)
+// workgroups of a team read the same part of the stream.  Workgroups are dealt to the eight XCDs in
+// turn along x and the number of parts is a multiple of eight, so x & 7 names both the part (mod 8)
 // and the XCD: a team shares its part of the stream through one L2 and memory is read once.
 // ---------------------------------------------------------------------------------------------
 constexpr int kSliceThreads = 1024;
 constexpr uint32_t kSliceWords = 40960;
 constexpr uint64_t kSliceRows = 32ull * kSliceWords;
-constexpr uint32_t kStreamParts = 8;
+constexpr uint32_t kStreamParts = 8;      // parts of a stream, at least
+constexpr uint32_t kStreamPartsMax = 32;  // and at most, where the scratch has room for that many slabs
+// The scratch of a table: one byte per row (eight slabs, or the flag bytes), and never less than 32
+// slabs of one whole slice, so that a table of one or two slices, whose 8 or 16 workgroups would
+// leave most of the chip idle, can be shared out over 32 or 16 parts of its stream instead.
+constexpr uint64_t kScratchFloorBytes = (uint64_t)kStreamPartsMax * kSliceWords * 4u;
+inline uint64_t mark_scratch_bytes(uint64_t n_rows) {
+    const uint64_t words = cnr_bitmap_words(n_rows);
+    const uint64_t per_row = words * 32u, slabs32 = words * 4u * kStreamPartsMax;
+    const uint64_t floor = slabs32 < kScratchFloorBytes ? slabs32 : kScratchFloorBytes;
+    return per_row > floor ? per_row : floor;
+}
+// The most parts (a multiple of eight) a table's scratch has slabs for.
+inline uint32_t slice_parts_max(uint64_t n_rows) {
+    const uint64_t words = cnr_bitmap_words(n_rows);
+    if (words == 0) return kStreamParts;
+    const uint64_t fit = (mark_scratch_bytes(n_rows) / (words * 4u)) & ~7ull;
+    return (uint32_t)(fit > kStreamPartsMax ? kStreamPartsMax : fit < kStreamParts ? kStreamParts : fit);
+}
 
 template <typename IdxT>
 __global__ void __launch_bounds__(kSliceThreads) mark_slices_kernel(const TrackBatch b, cnr_dev_errors *err) {
@@ -198,7 +218,7 @@ __global__ void __launch_bounds__(kSliceThreads) mark_slices_kernel(const TrackB
     constexpr int kUnroll = 4;
     __shared__ uint32_t bits[kSliceWords];
     const TrackJob &t = b.job[wg_y()];
-    const uint32_t part = wg_x() & (kStreamParts - 1u), w = wg_x() / kStreamParts;
+    const uint32_t part = wg_x() % t.parts, w = wg_x() / t.parts;
     const uint32_t n_rows = (uint32_t)t.n_rows;
     const uint64_t first = (uint64_t)w * kSliceRows;
     if (first >= t.n_rows) return;  // the whole workgroup: tables of a batch differ in size
@@ -216,7 +236,7 @@ __global__ void __launch_bounds__(kSliceThreads) mark_slices_kernel(const TrackB
     const vec_t *vecs = reinterpret_cast<const vec_t *>(idx + head);
     const uint64_t n_vec = (n - head) / kVec;
     const uint64_t tail = head + n_vec * kVec;
-    const uint64_t per_part = (n_vec + kStreamParts - 1u) / kStreamParts;
+    const uint64_t per_part = (n_vec + t.parts - 1u) / t.parts;
     const uint64_t v0 = part * per_part;
     const uint64_t v1 = v0 + per_part < n_vec ? v0 + per_part : n_vec;
 
@@ -271,7 +291,7 @@ __global__ void __launch_bounds__(kSliceThreads) mark_slices_kernel(const TrackB
     for (uint32_t i = tid; i < words; i += kSliceThreads) slab[i] = bits[i];
 }
 
-// bitmap |= OR of the eight slabs; the slabs are left all zero.
+// bitmap |= OR of the table's slabs; the slabs are left all zero.
 __global__ void __launch_bounds__(kBlock) fold_slabs_kernel(const TrackBatch b) {
     const TrackJob &t = b.job[wg_y()];
     uint32_t *__restrict__ slabs = reinterpret_cast<uint32_t *>(t.flags);
@@ -280,8 +300,7 @@ __global__ void __launch_bounds__(kBlock) fold_slabs_kernel(const TrackBatch b) 
     const uint64_t stride = (uint64_t)b.grid_x * kBlock;
     for (uint64_t i = (uint64_t)wg_x() * kBlock + tid_x(); i < n_words; i += stride) {
         uint32_t acc = 0;
-#pragma unroll
-        for (uint32_t s = 0; s < kStreamParts; ++s) {
+        for (uint32_t s = 0; s < t.parts; ++s) {
             acc |= slabs[s * n_words + i];
             slabs[s * n_words + i] = 0u;
         }
@@ -460,7 +479,7 @@ cnr_status check_tracked_table(const cnr_table_job &j) {
 
 extern "C" {
 
-size_t cnr_mark_scratch_bytes(uint64_t n_rows) { return (size_t)(cnr_bitmap_words(n_rows) * 32u); }
+size_t cnr_mark_scratch_bytes(uint64_t n_rows) { return (size_t)mark_scratch_bytes(n_rows); }
 
 cnr_status cnr_clear_bitmap_batch(cnr_ctx *ctx, const cnr_table_job *jobs, uint32_t n_jobs, void *stream) {
     cnr_status st = cnr_enter(ctx);
@@ -514,9 +533,9 @@ cnr_status cnr_mark_touched_batch(cnr_ctx *ctx, const cnr_table_job *jobs, uint3
     for (uint32_t first = 0; first < n_jobs; first += CNR_MAX_BATCH) {
         // Three routes.  Short streams: atomic ORs on the bitmap (about 16 G atomics/s; the other two
         // pay a pass over n_rows bytes).  Long streams: bitmap slices in LDS, or one flag byte per row
-        // and a fold.  The slices cost every workgroup of a table its part of the stream (an eighth,
-        // at the 60 GB/s a workgroup of that kernel gets through it), whatever the stream holds, and all tables of a call
-        // run side by side as long as their 8 x slices workgroups fit the chip; the flag bytes cost
+        // and a fold.  The slices cost every workgroup of a table its part of the stream (an eighth or
+        // less, at the 60 GB/s a workgroup of that kernel gets through it), whatever the stream holds, and
+        // all tables of a call run side by side as long as their workgroups fit the chip; the flag bytes cost
         // one scattered store per look-up that gets past the table of lately flagged rows (about 17 ps
         // of the whole chip's time each, a third of the look-ups on the skewed streams that embedding
         // look-ups are), one table after the other.  So one or two tables marked alone are faster
@@ -525,20 +544,38 @@ cnr_status cnr_mark_touched_batch(cnr_ctx *ctx, const cnr_table_job *jobs, uint3
         // call takes, for all its tables of up to kSliceTeamMax slices together, the route this
         // estimate makes the cheaper one.  Larger tables always take the flag bytes.
         constexpr uint64_t kSliceTeamMax = 16;
-        constexpr double kSlicePsPerByte = 1e12 / 60e9 / kStreamParts;  // a workgroup's part of the stream at 60 GB/s
+        constexpr double kSlicePsPerByte = 1e12 / 60e9;                  // a workgroup gets through its part of the stream at 60 GB/s
         constexpr double kFlagPsPerLookup = 6.0;                         // 17 ps x about a third that become stores
-        uint64_t elig_wgs = 0, elig_max_idx = 0, elig_sum_idx = 0;
+        uint64_t elig_teams = 0, elig_sum_idx = 0;
         for (uint32_t i = first; i < n_jobs && i < first + CNR_MAX_BATCH; ++i) {
             const cnr_table_job &j = jobs[i];
             const uint64_t team = (j.n_rows + kSliceRows - 1) / kSliceRows;
             if (j.n_indices == 0 || !(j.mark_scratch && j.n_rows && j.n_indices > j.n_rows / 256 + 65536) || team > kSliceTeamMax)
                 continue;
-            elig_wgs += kStreamParts * team;
+            elig_teams += team;
             elig_sum_idx += j.n_indices;
-            if (j.n_indices > elig_max_idx) elig_max_idx = j.n_indices;
+        }
+        // Parts per stream: eight, or as many more (in eights, as far as a table's scratch has slabs) as
+        // it takes for the workgroups of the call to fill the chip.
+        uint32_t want_parts = kStreamParts;
+        if (elig_teams) {
+            const uint64_t fill = (((uint64_t)ctx->n_cu + elig_teams - 1) / elig_teams + 7u) & ~7ull;
+            want_parts = (uint32_t)(fill < kStreamParts ? kStreamParts : fill > kStreamPartsMax ? kStreamPartsMax : fill);
+        }
+        uint64_t elig_wgs = 0;
+        double elig_longest = 0;  // the longest part of a stream a workgroup reads, in look-ups
+        for (uint32_t i = first; i < n_jobs && i < first + CNR_MAX_BATCH; ++i) {
+            const cnr_table_job &j = jobs[i];
+            const uint64_t team = (j.n_rows + kSliceRows - 1) / kSliceRows;
+            if (j.n_indices == 0 || !(j.mark_scratch && j.n_rows && j.n_indices > j.n_rows / 256 + 65536) || team > kSliceTeamMax)
+                continue;
+            const uint32_t most = slice_parts_max(j.n_rows);
+            const uint32_t parts = want_parts < most ? want_parts : most;
+            elig_wgs += team * parts;
+            if ((double)j.n_indices / parts > elig_longest) elig_longest = (double)j.n_indices / parts;
         }
         const uint64_t rounds = (elig_wgs + (uint64_t)ctx->n_cu - 1) / (uint64_t)ctx->n_cu;
-        const bool slices_pay = (double)elig_max_idx * (type == CNR_IDX_I64 ? 8.0 : 4.0) * kSlicePsPerByte * (double)rounds <
+        const bool slices_pay = elig_longest * (type == CNR_IDX_I64 ? 8.0 : 4.0) * kSlicePsPerByte * (double)rounds <
                                 (double)elig_sum_idx * kFlagPsPerLookup;
         TrackBatch slices = {}, bulk = {}, direct = {};
         uint32_t n_slices = 0, n_bulk = 0, n_direct = 0;
@@ -557,7 +594,9 @@ cnr_status cnr_mark_touched_batch(cnr_ctx *ctx, const cnr_table_job *jobs, uint3
             t.flags = (uint8_t *)j.mark_scratch;
             const uint64_t words = cnr_bitmap_words(j.n_rows);
             if (use_slices) {
-                if (team > slices_team) slices_team = team;
+                const uint32_t most = slice_parts_max(j.n_rows);
+                t.parts = want_parts < most ? want_parts : most;
+                if (team * t.parts > slices_team) slices_team = team * t.parts;
                 if (words > slices_words) slices_words = words;
             } else if (long_stream) {
                 if (j.n_indices > bulk_idx) bulk_idx = j.n_indices;
@@ -567,7 +606,7 @@ cnr_status cnr_mark_touched_batch(cnr_ctx *ctx, const cnr_table_job *jobs, uint3
             }
         }
         if (n_slices) {
-            const dim3 grid((unsigned)(kStreamParts * slices_team), n_slices);
+            const dim3 grid((unsigned)slices_team, n_slices);  // the most workgroups any table of the launch has
             if (type == CNR_IDX_I64)
                 hipLaunchKernelGGL(mark_slices_kernel<int64_t>, grid, dim3(kSliceThreads), 0, s, slices, ctx->dev_err);
             else
